@@ -1,0 +1,133 @@
+/*
+ * gsa.h -- C ABI of libgsa: Gated Slot Attention (GSA) on AMD MI355X (gfx950).
+ *
+ * The operator (paper, Section 3.2, Eq. (gsa)), per sequence and head, with
+ * g_t = log alpha_t the log forget gate (one value per memory slot):
+ *
+ *     Kt_t = Diag(exp g_t) Kt_{t-1} + (1 - exp g_t) (x) k_t       in R^{m x d_k}
+ *     Vt_t = Diag(exp g_t) Vt_{t-1} + (1 - exp g_t) (x) v_t       in R^{m x d_v}
+ *     o_t  = Vt_t^T softmax(scale * Kt_t q_t)                     softmax over the m slots
+ *
+ * Token t reads the memories after its own write.  The paper applies no score
+ * scaling; scale = 1.0f reproduces it.
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer to a dense row-major array with
+ *     the last index fastest.  The caller owns every buffer, including the
+ *     workspace; the library never allocates, frees or synchronises.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns at once.
+ *   - q,k,v,o,dO,dq,dk,dv have element type `dtype` (fp32 or bf16); g, dg,
+ *     z_saved and every memory (slot state) are fp32.  Accumulation is fp32.
+ *   - g must be <= 0.  Values below -30 are treated as -30 (alpha = 9e-14,
+ *     below fp32 resolution of the result).  NaN gates give NaN outputs.
+ *   - Outputs must not overlap inputs or each other (the decode step updates
+ *     its memories in place, that is its contract).
+ *   - Errors are return codes; arguments are validated on the host before any
+ *     device work is enqueued, and a failed call enqueues nothing.
+ *   - Supported shapes: m in {16, 32, 64, 128}; d_k and d_v multiples of 64, at most
+ *     1024; H, B, T >= 1 (T = 0 is accepted and does nothing).
+ */
+#ifndef GSA_H
+#define GSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GSA_OK = 0,
+    GSA_ERR_NULL = 1,        /* a required pointer is NULL */
+    GSA_ERR_SHAPE = 2,       /* a dimension is out of range or inconsistent */
+    GSA_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for */
+    GSA_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
+    GSA_ERR_HIP = 5          /* the HIP runtime reported an error at launch */
+} gsa_status;
+
+typedef enum { GSA_F32 = 0, GSA_BF16 = 1 } gsa_dtype;
+
+/*
+ * Problem shape.  Two forms:
+ *   batch  : cu_seqlens == NULL; B sequences of T tokens; n_seqs is ignored.
+ *   packed : cu_seqlens != NULL (device int32 [n_seqs+1], non-decreasing,
+ *            cu_seqlens[0] = 0, cu_seqlens[n_seqs] = T); B must be 1; sequence
+ *            s covers tokens cu_seqlens[s] .. cu_seqlens[s+1]-1 and starts from
+ *            its own initial memories.  Offsets are clamped into [0,T] on the
+ *            device; tokens covered by no sequence receive no output.
+ * Memories are indexed by sequence: [n, H, m, d] with n = B (batch) or n_seqs.
+ */
+typedef struct {
+    int32_t B, T, H, d_k, d_v, m;
+    int32_t dtype;              /* gsa_dtype */
+    float scale;
+    const int32_t *cu_seqlens;  /* device pointer or NULL */
+    int32_t n_seqs;
+} gsa_problem;
+
+const char *gsa_status_string(gsa_status s);
+
+/* Version of this ABI (bumped when a signature changes). */
+int32_t gsa_abi_version(void);
+
+/*
+ * Bytes of workspace gsa_fwd (want_bwd = 0) or gsa_bwd (want_bwd != 0) needs
+ * for this problem.  The workspace holds the per-chunk memories of the
+ * chunkwise evaluation (Appendix A, Eq. (gla-chunk-gate)) and small per-token
+ * scratch; its contents are meaningless to the caller.  It must be 256-byte
+ * aligned.  Host call, touches no device.
+ */
+gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes);
+
+/*
+ * Forward (Eq. (gsa); chunkwise evaluation after Appendix A and Algorithm 1).
+ *   q,k [B,T,H,d_k]  v [B,T,H,d_v]  (dtype)      g [B,T,H,m] fp32
+ *   K0,V0 [n,H,m,d_k|d_v] fp32 initial memories, or NULL for zeros
+ *   o [B,T,H,d_v] (dtype)                       output
+ *   z_saved [B,T,H,m] fp32 or NULL             pre-softmax slot scores
+ *                                               scale*Kt_t q_t, the one tensor
+ *                                               gsa_bwd needs besides the inputs
+ *   KT,VT [n,H,m,d] fp32 or NULL               memories after the last token
+ */
+gsa_status gsa_fwd(const gsa_problem *p,
+                   const void *q, const void *k, const void *v, const float *g,
+                   const float *K0, const float *V0,
+                   void *o, float *z_saved, float *KT, float *VT,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of L = sum <dO_t,o_t> + <dKT,Kt_T> + <dVT,Vt_T> (Algorithm 1,
+ * backward pass; the per-chunk memories are recomputed from k,v,g rather than
+ * stored by the forward).
+ *   inputs : q,k,v,g,K0,V0 as given to gsa_fwd; z_saved as written by it;
+ *            dO [B,T,H,d_v] (dtype); dKT,dVT [n,H,m,d] fp32 or NULL (zeros)
+ *   outputs: dq,dk [B,T,H,d_k], dv [B,T,H,d_v] (dtype); dg [B,T,H,m] fp32,
+ *            the gradient with respect to g with the write intensity
+ *            1 - exp(g) tied to it; dK0,dV0 [n,H,m,d] fp32 or NULL
+ */
+gsa_status gsa_bwd(const gsa_problem *p,
+                   const void *q, const void *k, const void *v, const float *g,
+                   const float *K0, const float *V0, const float *z_saved, const void *dO,
+                   const float *dKT, const float *dVT,
+                   void *dq, void *dk, void *dv, float *dg, float *dK0, float *dV0,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One recurrent step of Eq. (gsa) (the decode form, Figure 1) for B*H
+ * independent memories, which are read, updated and written back in place.
+ *   q,k [B,H,d_k]  v [B,H,d_v] (dtype)   g [B,H,m] fp32
+ *   K_state [B,H,m,d_k], V_state [B,H,m,d_v] fp32, in/out
+ *   o [B,H,d_v] (dtype)
+ * Needs no workspace.
+ */
+gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
+                           int32_t dtype, float scale,
+                           const void *q, const void *k, const void *v, const float *g,
+                           float *K_state, float *V_state, void *o, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSA_H */

@@ -1,0 +1,6 @@
+"""libgsa: Gated Slot Attention (arXiv 2409.07146) as hand-written HIP kernels for MI355X.
+
+The package is a thin binding over the C-ABI library `libgsa.so` built from `csrc/`.
+"""
+from .api import (GsaError, alloc_workspace, gsa_bwd, gsa_decode_step, gsa_fwd,  # noqa: F401
+                  gsa_workspace_bytes, make_problem)

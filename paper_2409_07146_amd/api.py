@@ -1,0 +1,147 @@
+"""Thin Python binding of libgsa: same entry points as include/gsa.h, torch tensors in.
+
+Argument marshalling only -- every step of the operator runs in the HIP kernels.
+PyTorch supplies device memory and the current stream, nothing else.
+"""
+import ctypes
+from typing import Optional
+
+import torch
+
+from . import _lib
+
+GSA_F32, GSA_BF16 = 0, 1
+_DTYPES = {torch.float32: GSA_F32, torch.bfloat16: GSA_BF16}
+
+
+class GsaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = _lib.load().gsa_status_string(code).decode()
+        super().__init__("%s failed: %s (status %d)" % (where, msg, code))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _check(t, name, dtype=None, shape=None, optional=False):
+    if t is None:
+        if optional:
+            return
+        raise ValueError("%s is required" % name)
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def make_problem(q, v, g, scale=1.0, cu_seqlens=None):
+    B, T, H, d_k = q.shape
+    d_v, m = v.shape[-1], g.shape[-1]
+    if q.dtype not in _DTYPES:
+        raise ValueError("q,k,v must be float32 or bfloat16")
+    p = _lib.GsaProblem()
+    p.B, p.T, p.H, p.d_k, p.d_v, p.m = B, T, H, d_k, d_v, m
+    p.dtype = _DTYPES[q.dtype]
+    p.scale = float(scale)
+    if cu_seqlens is not None:
+        _check(cu_seqlens, "cu_seqlens", torch.int32)
+        p.cu_seqlens = cu_seqlens.data_ptr()
+        p.n_seqs = cu_seqlens.numel() - 1
+    else:
+        p.cu_seqlens = None
+        p.n_seqs = B
+    return p
+
+
+def gsa_workspace_bytes(problem, want_bwd: bool) -> int:
+    n = ctypes.c_size_t(0)
+    rc = _lib.load().gsa_workspace_bytes(ctypes.byref(problem), int(bool(want_bwd)), ctypes.byref(n))
+    if rc != 0:
+        raise GsaError(rc, "gsa_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_workspace(problem, want_bwd: bool, device) -> torch.Tensor:
+    n = gsa_workspace_bytes(problem, want_bwd)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=True, final_state=False,
+            workspace=None):
+    """Returns (o, z_saved or None, KT or None, VT or None)."""
+    B, T, H, d_k = q.shape
+    d_v, m = v.shape[-1], g.shape[-1]
+    p = make_problem(q, v, g, scale, cu_seqlens)
+    n = p.n_seqs
+    _check(q, "q", q.dtype, (B, T, H, d_k)); _check(k, "k", q.dtype, (B, T, H, d_k))
+    _check(v, "v", q.dtype, (B, T, H, d_v)); _check(g, "g", torch.float32, (B, T, H, m))
+    _check(K0, "K0", torch.float32, (n, H, m, d_k), optional=True)
+    _check(V0, "V0", torch.float32, (n, H, m, d_v), optional=True)
+    if workspace is None:
+        workspace = alloc_workspace(p, False, q.device)
+    o = torch.empty_like(v)
+    z = torch.empty((B, T, H, m), dtype=torch.float32, device=q.device) if save_z else None
+    KT = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if final_state else None
+    VT = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if final_state else None
+    rc = _lib.load().gsa_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(K0), _ptr(V0),
+                             _ptr(o), _ptr(z), _ptr(KT), _ptr(VT), _ptr(workspace), workspace.numel(),
+                             _stream(q))
+    if rc != 0:
+        raise GsaError(rc, "gsa_fwd")
+    return o, z, KT, VT
+
+
+def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, cu_seqlens=None,
+            initial_state_grad=False, workspace=None):
+    """Returns (dq, dk, dv, dg, dK0 or None, dV0 or None)."""
+    B, T, H, d_k = q.shape
+    d_v, m = v.shape[-1], g.shape[-1]
+    p = make_problem(q, v, g, scale, cu_seqlens)
+    n = p.n_seqs
+    _check(q, "q", q.dtype, (B, T, H, d_k)); _check(k, "k", q.dtype, (B, T, H, d_k))
+    _check(v, "v", q.dtype, (B, T, H, d_v)); _check(g, "g", torch.float32, (B, T, H, m))
+    _check(z_saved, "z_saved", torch.float32, (B, T, H, m)); _check(dO, "dO", q.dtype, (B, T, H, d_v))
+    for t, nm, d in ((K0, "K0", d_k), (V0, "V0", d_v), (dKT, "dKT", d_k), (dVT, "dVT", d_v)):
+        _check(t, nm, torch.float32, (n, H, m, d), optional=True)
+    if workspace is None:
+        workspace = alloc_workspace(p, True, q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dg = torch.empty_like(g)
+    dK0 = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if initial_state_grad else None
+    dV0 = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if initial_state_grad else None
+    rc = _lib.load().gsa_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(K0), _ptr(V0),
+                             _ptr(z_saved), _ptr(dO), _ptr(dKT), _ptr(dVT), _ptr(dq), _ptr(dk), _ptr(dv),
+                             _ptr(dg), _ptr(dK0), _ptr(dV0), _ptr(workspace), workspace.numel(), _stream(q))
+    if rc != 0:
+        raise GsaError(rc, "gsa_bwd")
+    return dq, dk, dv, dg, dK0, dV0
+
+
+def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None):
+    """q,k [B,H,d_k], v [B,H,d_v], g [B,H,m]; K_state,V_state fp32 [B,H,m,d], updated in place.
+    Returns o [B,H,d_v]."""
+    B, H, d_k = q.shape
+    d_v, m = v.shape[-1], g.shape[-1]
+    if q.dtype not in _DTYPES:
+        raise ValueError("q,k,v must be float32 or bfloat16")
+    _check(q, "q", q.dtype, (B, H, d_k)); _check(k, "k", q.dtype, (B, H, d_k))
+    _check(v, "v", q.dtype, (B, H, d_v)); _check(g, "g", torch.float32, (B, H, m))
+    _check(K_state, "K_state", torch.float32, (B, H, m, d_k))
+    _check(V_state, "V_state", torch.float32, (B, H, m, d_v))
+    o = torch.empty_like(v) if out is None else out
+    _check(o, "out", q.dtype, (B, H, d_v))
+    rc = _lib.load().gsa_decode_step(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), _ptr(q), _ptr(k),
+                                     _ptr(v), _ptr(g), _ptr(K_state), _ptr(V_state), _ptr(o), _stream(q))
+    if rc != 0:
+        raise GsaError(rc, "gsa_decode_step")
+    return o

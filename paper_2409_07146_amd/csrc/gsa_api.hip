@@ -1,0 +1,169 @@
+// C ABI of libgsa (see include/gsa.h): argument validation, workspace planning, dispatch.
+// All checks run on the host before anything is enqueued.
+#include "../../include/gsa.h"
+#include "gsa_common.h"
+#include "gsa_internal.h"
+
+namespace {
+
+using gsa::Plan;
+using gsa::Work;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool valid_m(int m, bool sequence_kernels)
+{
+    if (m == 16 || m == 32 || m == 64) return true;
+    return !sequence_kernels && m == 128;
+}
+
+gsa_status make_plan(const gsa_problem *p, Plan *pl)
+{
+    if (!p) return GSA_ERR_NULL;
+    if (p->B < 1 || p->T < 0 || p->H < 1 || p->d_k < 1 || p->d_v < 1 || p->m < 1) return GSA_ERR_SHAPE;
+    if (p->dtype != GSA_F32 && p->dtype != GSA_BF16) return GSA_ERR_SHAPE;
+    if (!(p->scale == p->scale)) return GSA_ERR_SHAPE;
+    if (p->cu_seqlens) {
+        if (p->B != 1 || p->n_seqs < 1) return GSA_ERR_SHAPE;
+    }
+    if (p->d_k % 64 || p->d_v % 64 || p->d_k > 1024 || p->d_v > 1024) return GSA_ERR_UNSUPPORTED;
+    if (!valid_m(p->m, true)) return GSA_ERR_UNSUPPORTED;
+    const int64_t tokens = (int64_t)p->B * p->T;
+    if (tokens * p->H * (int64_t)(p->d_k > p->d_v ? p->d_k : p->d_v) >= ((int64_t)1 << 40)) return GSA_ERR_SHAPE;
+    pl->B = p->B; pl->T = p->T; pl->H = p->H; pl->d_k = p->d_k; pl->d_v = p->d_v; pl->m = p->m;
+    pl->dtype = p->dtype; pl->scale = p->scale; pl->cu_seqlens = p->cu_seqlens;
+    pl->n_seqs = p->cu_seqlens ? p->n_seqs : p->B;
+    pl->tokens = tokens;
+    const int64_t slots = p->cu_seqlens ? ((int64_t)p->T / gsa::kChunk + p->n_seqs)
+                                        : (int64_t)p->B * ((p->T + gsa::kChunk - 1) / gsa::kChunk);
+    if (slots > 0x3fffffff) return GSA_ERR_SHAPE;
+    pl->chunk_slots = (int32_t)slots;
+    const size_t state = (size_t)slots * p->H * p->m * (size_t)(p->d_k + p->d_v) * sizeof(float);
+    const size_t tokm = (size_t)tokens * p->H * p->m * sizeof(float);
+    size_t off = 0;
+    pl->off_table = off;  off += align_up(p->cu_seqlens ? (size_t)slots * 4 * sizeof(int32_t) : 0);
+    pl->off_seqtab = off; off += align_up(p->cu_seqlens ? (size_t)p->n_seqs * 4 * sizeof(int32_t) : 0);
+    pl->off_S = off;      off += align_up(state);
+    pl->total_fwd = off;
+    pl->off_E = off;      off += align_up(state);
+    pl->off_dz = off;     off += align_up(tokm);
+    pl->off_dgf = off;    off += align_up(tokm);
+    pl->total_bwd = off;
+    return GSA_OK;
+}
+
+Work make_work(const Plan &pl, void *ws)
+{
+    unsigned char *b = static_cast<unsigned char *>(ws);
+    Work w;
+    w.table = reinterpret_cast<int32_t *>(b + pl.off_table);
+    w.seqtab = reinterpret_cast<int32_t *>(b + pl.off_seqtab);
+    w.S = reinterpret_cast<float *>(b + pl.off_S);
+    w.E = reinterpret_cast<float *>(b + pl.off_E);
+    w.dz = reinterpret_cast<float *>(b + pl.off_dz);
+    w.dgf = reinterpret_cast<float *>(b + pl.off_dgf);
+    return w;
+}
+
+gsa_status check_workspace(void *ws, size_t have, size_t need)
+{
+    if (need == 0) return GSA_OK;
+    if (!ws) return GSA_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) % kAlign) return GSA_ERR_WORKSPACE;
+    if (have < need) return GSA_ERR_WORKSPACE;
+    return GSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *gsa_status_string(gsa_status s)
+{
+    switch (s) {
+    case GSA_OK: return "ok";
+    case GSA_ERR_NULL: return "a required pointer is NULL";
+    case GSA_ERR_SHAPE: return "a dimension is out of range or inconsistent";
+    case GSA_ERR_UNSUPPORTED: return "shape not supported by this build";
+    case GSA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GSA_ERR_HIP: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+int32_t gsa_abi_version(void) { return 1; }
+
+gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes)
+{
+    if (!bytes) return GSA_ERR_NULL;
+    Plan pl;
+    const gsa_status st = make_plan(p, &pl);
+    if (st != GSA_OK) return st;
+    *bytes = want_bwd ? pl.total_bwd : pl.total_fwd;
+    return GSA_OK;
+}
+
+gsa_status gsa_fwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
+                   const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    gsa_status st = make_plan(p, &pl);
+    if (st != GSA_OK) return st;
+    if (pl.tokens == 0) return GSA_OK;
+    if (!q || !k || !v || !g || !o) return GSA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) || !aligned16(K0) ||
+        !aligned16(V0) || !aligned16(z_saved) || !aligned16(KT) || !aligned16(VT))
+        return GSA_ERR_SHAPE;
+    st = check_workspace(workspace, workspace_bytes, pl.total_fwd);
+    if (st != GSA_OK) return st;
+    const Work w = make_work(pl, workspace);
+    const hipError_t e = gsa::launch_fwd(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
+
+gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
+                   const float *K0, const float *V0, const float *z_saved, const void *dO, const float *dKT,
+                   const float *dVT, void *dq, void *dk, void *dv, float *dg, float *dK0, float *dV0,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    gsa_status st = make_plan(p, &pl);
+    if (st != GSA_OK) return st;
+    if (pl.tokens == 0) return GSA_OK;
+    if (!q || !k || !v || !g || !z_saved || !dO || !dq || !dk || !dv || !dg) return GSA_ERR_NULL;
+    const void *ptrs[] = {q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0};
+    for (const void *ptr : ptrs)
+        if (!aligned16(ptr)) return GSA_ERR_SHAPE;
+    st = check_workspace(workspace, workspace_bytes, pl.total_bwd);
+    if (st != GSA_OK) return st;
+    const Work w = make_work(pl, workspace);
+    const hipError_t e = gsa::launch_bwd(pl, w, q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
+
+gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
+                           const void *q, const void *k, const void *v, const float *g, float *K_state,
+                           float *V_state, void *o, void *stream)
+{
+    if (B < 0 || H < 1 || d_k < 1 || d_v < 1 || m < 1) return GSA_ERR_SHAPE;
+    if (dtype != GSA_F32 && dtype != GSA_BF16) return GSA_ERR_SHAPE;
+    if (!(scale == scale)) return GSA_ERR_SHAPE;
+    if ((int64_t)B * H > 0x7fffffff) return GSA_ERR_SHAPE;
+    if (d_k % 64 || d_v % 64 || d_k > 1024 || d_v > 1024) return GSA_ERR_UNSUPPORTED;
+    if (!valid_m(m, false)) return GSA_ERR_UNSUPPORTED;
+    if (B == 0) return GSA_OK;
+    if (!q || !k || !v || !g || !K_state || !V_state || !o) return GSA_ERR_NULL;
+    const void *ptrs[] = {q, k, v, g, K_state, V_state, o};
+    for (const void *ptr : ptrs)
+        if (!aligned16(ptr)) return GSA_ERR_SHAPE;
+    const hipError_t e = gsa::launch_decode(B * H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
+
+}  // extern "C"

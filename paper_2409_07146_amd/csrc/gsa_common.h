@@ -1,0 +1,272 @@
+// Device-side building blocks shared by the libgsa kernels (gfx950 / CDNA4, wave64).
+//
+// Everything here is written in terms of one matrix-core atom: a 16x16 fp32
+// accumulator tile updated with a depth-32 contraction.  For bf16 operands that
+// is one v_mfma_f32_16x16x32_bf16; for fp32 operands it is eight
+// v_mfma_f32_16x16x4_f32.  Both read their operands as "8 consecutive k per
+// lane" fragments from LDS tiles stored contraction-index-fastest, so every
+// kernel is written once and instantiated for both element types.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gsa {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kWave = 64;
+constexpr int kChunk = 64;          // tokens per chunk (C in Appendix A)
+constexpr int kSub = 16;            // row block inside a chunk sharing one gate reference
+constexpr float kGateFloor = -30.f; // log-gates below this are treated as this
+constexpr float kExpClamp = 80.f;   // largest exponent a factored gate may carry in fp32
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
+
+// ----------------------------------------------------------------------------
+// Matrix-core atom.
+//   A fragment: lane l holds A[row = l%16][k = 8*(l/16) + e], e = 0..7
+//   B fragment: lane l holds B[k = 8*(l/16) + e][col = l%16]
+//   D tile    : lane l holds D[row = 4*(l/16) + j][col = l%16], j = 0..3
+// ----------------------------------------------------------------------------
+template <typename T> struct Atom;
+
+template <> struct Atom<bf16_t> {
+    typedef bf16x8 Frag;
+    static constexpr int kPad = 8;  // elements of padding that keep rows 16-byte aligned
+    __device__ static __forceinline__ Frag load(const bf16_t *p) { return *reinterpret_cast<const Frag *>(p); }
+    __device__ static __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (bf16_t)0.f; return f; }
+    __device__ static __forceinline__ void mma(f32x4 &c, const Frag &a, const Frag &b) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+template <> struct Atom<float> {
+    typedef f32x8 Frag;
+    static constexpr int kPad = 4;
+    __device__ static __forceinline__ Frag load(const float *p) {
+        const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
+        const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+        Frag f;
+        f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
+        f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+        return f;
+    }
+    __device__ static __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = 0.f; return f; }
+    __device__ static __forceinline__ void mma(f32x4 &c, const Frag &a, const Frag &b) {
+        // instruction e contracts k = {e, 8+e, 16+e, 24+e}: lane group l/16 supplies k = 8*(l/16)+e
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], c, 0, 0, 0);
+    }
+};
+
+// acc[MI][NI] += A[16*mi + r][k] * B[16*ni + r][k] summed over k in [0,K), K a multiple of 32.
+// A and B are LDS tiles stored [row][k] with row strides lda, ldb (elements).
+template <typename T, int MI, int NI>
+__device__ __forceinline__ void gemm_nt(f32x4 (&acc)[MI][NI], const T *A, int lda, const T *B, int ldb,
+                                        int K, int lane)
+{
+    const int r = lane & 15, g8 = (lane >> 4) * 8;
+    for (int k0 = 0; k0 < K; k0 += 32) {
+        typename Atom<T>::Frag a[MI], b[NI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) a[mi] = Atom<T>::load(A + (mi * 16 + r) * lda + k0 + g8);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) b[ni] = Atom<T>::load(B + (ni * 16 + r) * ldb + k0 + g8);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) Atom<T>::mma(acc[mi][ni], a[mi], b[ni]);
+    }
+}
+
+template <int MI, int NI> __device__ __forceinline__ void zero_acc(f32x4 (&acc)[MI][NI])
+{
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+// ----------------------------------------------------------------------------
+// Global -> LDS staging.  Sources are rows of `cols` elements (cols % 8 == 0),
+// row r at src + r*gld.  Rows >= nvalid are filled with zeros.
+// ----------------------------------------------------------------------------
+template <typename Tin> struct Vec8;
+template <> struct Vec8<bf16_t> {
+    float v[8];
+    __device__ __forceinline__ void load(const bf16_t *p) {
+        const bf16x8 x = *reinterpret_cast<const bf16x8 *>(p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (float)x[e];
+    }
+};
+template <> struct Vec8<float> {
+    float v[8];
+    __device__ __forceinline__ void load(const float *p) {
+        const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
+        const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+        v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+        v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+    }
+};
+
+template <typename T> __device__ __forceinline__ void store8(T *dst, const float (&v)[8]);
+template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *dst, const float (&v)[8]) {
+    bf16x8 x;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (bf16_t)v[e];
+    *reinterpret_cast<bf16x8 *>(dst) = x;
+}
+template <> __device__ __forceinline__ void store8<float>(float *dst, const float (&v)[8]) {
+    *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{v[4], v[5], v[6], v[7]};
+}
+
+// dst[r][c] = src[r][c]   (dst row stride ld)
+template <typename T, typename Tin>
+__device__ __forceinline__ void stage_rows(T *dst, int ld, const Tin *src, size_t gld, int rows, int cols,
+                                           int nvalid, int tid, int nthreads)
+{
+    const int vpr = cols >> 3;
+    for (int idx = tid; idx < rows * vpr; idx += nthreads) {
+        const int r = idx / vpr, c = (idx - r * vpr) << 3;
+        Vec8<Tin> x;
+        if (r < nvalid) x.load(src + (size_t)r * gld + c);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x.v[e] = 0.f;
+        }
+        store8<T>(dst + r * ld + c, x.v);
+    }
+}
+
+// dst[c][r] = src[r][c]   (dst row stride ld >= rows): the transposed view that lets a
+// contraction over tokens read 8 consecutive tokens per lane.
+template <typename T, typename Tin>
+__device__ __forceinline__ void stage_cols(T *dst, int ld, const Tin *src, size_t gld, int rows, int cols,
+                                           int nvalid, int tid, int nthreads)
+{
+    const int vpr = cols >> 3;
+    for (int idx = tid; idx < rows * vpr; idx += nthreads) {
+        // consecutive threads take consecutive 16-byte pieces of a row: global loads coalesce
+        const int r = idx / vpr, c = (idx - r * vpr) << 3;
+        Vec8<Tin> x;
+        if (r < nvalid) x.load(src + (size_t)r * gld + c);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x.v[e] = 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[(c + e) * ld + r] = from_f32<T>(x.v[e]);
+    }
+}
+
+// ----------------------------------------------------------------------------
+// Chunk map: which tokens a chunk covers.  Batch form: arithmetic.  Packed form:
+// a table the prepare kernel writes into the workspace.
+// ----------------------------------------------------------------------------
+struct ChunkMap {
+    const int32_t *table;   // packed: [4 * n_chunk_slots] = {seq, tok0, len, index in seq}; batch: NULL
+    const int32_t *seq_tab; // packed: [4 * n_seqs] = {first chunk id, number of chunks, first token, tokens}
+    int32_t T;              // batch: tokens per sequence
+    int32_t chunks_per_seq; // batch: ceil(T / kChunk)
+    int32_t n_chunk_slots;  // upper bound on the number of chunks (grid size)
+};
+
+struct ChunkInfo { int seq, tok0, len, idx; };
+
+__device__ __forceinline__ bool chunk_lookup(const ChunkMap &cm, int c, ChunkInfo &ci)
+{
+    if (cm.table) {
+        ci.seq = cm.table[4 * c + 0];
+        ci.tok0 = cm.table[4 * c + 1];
+        ci.len = cm.table[4 * c + 2];
+        ci.idx = cm.table[4 * c + 3];
+        return ci.len > 0;
+    }
+    ci.seq = c / cm.chunks_per_seq;
+    ci.idx = c - ci.seq * cm.chunks_per_seq;
+    const int off = ci.idx * kChunk;
+    ci.tok0 = ci.seq * cm.T + off;
+    ci.len = min(kChunk, cm.T - off);
+    return true;
+}
+
+// First chunk id, number of chunks and first token of sequence s.
+__device__ __forceinline__ void seq_lookup(const ChunkMap &cm, int s, int &chunk0, int &nchunks, int &tok0, int &ntok)
+{
+    if (cm.seq_tab) {
+        chunk0 = cm.seq_tab[4 * s + 0];
+        nchunks = cm.seq_tab[4 * s + 1];
+        tok0 = cm.seq_tab[4 * s + 2];
+        ntok = cm.seq_tab[4 * s + 3];
+    } else {
+        chunk0 = s * cm.chunks_per_seq;
+        nchunks = cm.chunks_per_seq;
+        tok0 = s * cm.T;
+        ntok = cm.T;
+    }
+}
+
+// ----------------------------------------------------------------------------
+// Gate preparation for one chunk (Algorithm 1, chunk_cumsum, plus the write
+// intensity): from g[len][M] (global, row stride gld) fill
+//   Gs[t][i] = sum_{j<=t} max(g_j[i], floor)      chunk-local inclusive cumulative log gate
+//   Ss[t][i] = 1 - exp(g_t[i])                    write intensity (0 on padded rows)
+// Rows t >= len are padded with g = 0.  Needs blockDim.x = NT threads, NT % M == 0,
+// (kChunk * M) % (4 * NT) == 0, and `tot` scratch of (NT/M) * M floats.
+// Ends with a __syncthreads().
+// ----------------------------------------------------------------------------
+template <int M, int NT>
+__device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *tot, const float *g, size_t gld,
+                                          int len, int tid)
+{
+    constexpr int P = NT / M;            // token partitions
+    constexpr int TP = kChunk / P;       // tokens per partition
+    static_assert(NT % M == 0 && kChunk % P == 0, "gate_prep partitioning");
+    const int i = tid % M, part = tid / M;
+    float run = 0.f;
+#pragma unroll 4
+    for (int tt = 0; tt < TP; ++tt) {
+        const int t = part * TP + tt;
+        float gv = 0.f;
+        if (t < len) gv = fmaxf(g[(size_t)t * gld + i], kGateFloor);
+        run += gv;
+        Gs[t * ldg + i] = run;
+        Ss[t * ldg + i] = (t < len) ? -expm1f(gv) : 0.f;
+    }
+    tot[part * M + i] = run;
+    __syncthreads();
+    float off = 0.f;
+    for (int pp = 0; pp < part; ++pp) off += tot[pp * M + i];
+    if (part > 0) {
+#pragma unroll 4
+        for (int tt = 0; tt < TP; ++tt) Gs[(part * TP + tt) * ldg + i] += off;
+    }
+    __syncthreads();
+}
+
+// Reduce over the 16 lanes that share l/16 (the 16 columns of one D-tile row).
+__device__ __forceinline__ float row16_max(float x)
+{
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ float row16_sum(float x)
+{
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+}  // namespace gsa

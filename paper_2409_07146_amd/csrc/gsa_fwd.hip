@@ -1,0 +1,498 @@
+// Forward pass of Gated Slot Attention, chunkwise (paper: Eq. (gsa), Eq. (gsa-2pass),
+// Appendix A Eqs. (gla-chunk-gate)/(gla-chunk), Algorithm 1 forward).
+//
+// Both slot memories decay with the same gate and are written with the same
+// intensity, so they are carried as ONE memory S = [Kt | Vt] of shape
+// [m x (d_k+d_v)]:
+//
+//   scan_fwd_kernel   one workgroup per (sequence, head, column slice of S) walks the
+//                     chunks in order, keeps its slice of S in matrix-core accumulators
+//                     and writes the memory at the START of every chunk to the workspace
+//                     (the only sequential part; column slices are independent).
+//   out_fwd_kernel    one workgroup per (chunk, head): pass-1 scores z (inter-chunk term
+//                     from the stored memory + gated intra-chunk term), softmax over the
+//                     slots in registers, pass-2 output o.  z and p never round-trip HBM
+//                     except for the z the backward needs.
+//
+// Gate handling inside a chunk: rows are grouped in blocks of 16 tokens.  For row block I
+// the reference is the cumulative log gate just before the block, Gref_I.  exp(G_t - G_r)
+// is factored as exp(G_t - Gref_I) * exp(Gref_I - G_r): the first factor is <= 1, the
+// second is <= 1 for every earlier block and bounded by the decay inside one 16-token
+// block on the diagonal.  If that bound exceeds e^80 (not reachable with the paper's gate
+// parameterisation) the diagonal block is evaluated pairwise without factoring.
+#include "gsa_launch.h"
+
+namespace gsa {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+// ---------------------------------------------------------------------------------------
+// Packed form: build the chunk table from the device-side sequence offsets.
+// ---------------------------------------------------------------------------------------
+__global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T, int chunk_slots,
+                               int32_t *__restrict__ table, int32_t *__restrict__ seqtab)
+{
+    __shared__ int total;
+    if (threadIdx.x == 0) {
+        int c0 = 0, prev_end = 0;
+        for (int s = 0; s < n_seqs; ++s) {
+            int b = min(max(cu[s], prev_end), T);
+            int e = min(max(cu[s + 1], b), T);
+            const int nch = (e - b + kChunk - 1) / kChunk;
+            seqtab[4 * s + 0] = c0;
+            seqtab[4 * s + 1] = nch;
+            seqtab[4 * s + 2] = b;
+            seqtab[4 * s + 3] = e - b;
+            c0 += nch;
+            prev_end = e;
+        }
+        total = c0;
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < n_seqs; s += blockDim.x) {
+        const int c0 = seqtab[4 * s + 0], nch = seqtab[4 * s + 1], b = seqtab[4 * s + 2], n = seqtab[4 * s + 3];
+        for (int j = 0; j < nch; ++j) {
+            const int c = c0 + j;
+            if (c >= chunk_slots) break;
+            table[4 * c + 0] = s;
+            table[4 * c + 1] = b + j * kChunk;
+            table[4 * c + 2] = min(kChunk, n - j * kChunk);
+            table[4 * c + 3] = j;
+        }
+    }
+    for (int c = total + threadIdx.x; c < chunk_slots; c += blockDim.x) {
+        table[4 * c + 0] = 0; table[4 * c + 1] = 0; table[4 * c + 2] = 0; table[4 * c + 3] = 0;
+    }
+}
+
+hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
+{
+    if (!pl.cu_seqlens) return hipSuccess;
+    hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(256), 0, st, pl.cu_seqlens, pl.n_seqs, pl.T, pl.chunk_slots,
+                       w.table, w.seqtab);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Memory scan (Eq. (gla-chunk-gate) applied to S = [Kt | Vt]):
+//     S_n = Diag(exp G_C) S_{n-1} + (s * exp(G_C - G))^T [k | v]
+// ---------------------------------------------------------------------------------------
+template <typename T, int M, int NS> struct ScanLds {
+    static constexpr int PAD = Atom<T>::kPad;
+    static constexpr int ldg = M + 4;
+    static constexpr int ldw = kChunk + PAD;
+    static constexpr size_t oG = 0;
+    static constexpr size_t oS = oG + sizeof(float) * kChunk * ldg;
+    static constexpr size_t oTot = oS + sizeof(float) * kChunk * ldg;
+    static constexpr size_t oW = oTot + sizeof(float) * kThreads;
+    static constexpr size_t oX = oW + sizeof(T) * M * ldw;
+    static constexpr size_t bytes = oX + sizeof(T) * NS * ldw;
+};
+
+template <typename T, int M, int NS>
+__global__ __launch_bounds__(kThreads) void scan_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v,
+                                                            const T *__restrict__ k, const T *__restrict__ v,
+                                                            const float *__restrict__ g,
+                                                            const float *__restrict__ K0, const float *__restrict__ V0,
+                                                            float *__restrict__ S, float *__restrict__ KT,
+                                                            float *__restrict__ VT)
+{
+    using L = ScanLds<T, M, NS>;
+    constexpr int MI = M / 16, NI = NS / 64;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *Gs = reinterpret_cast<float *>(smem + L::oG);
+    float *Ss = reinterpret_cast<float *>(smem + L::oS);
+    float *tot = reinterpret_cast<float *>(smem + L::oTot);
+    T *We = reinterpret_cast<T *>(smem + L::oW);   // [M][ldw]  We[i][t] = s_t[i] exp(G_C[i] - G_t[i])
+    T *XT = reinterpret_cast<T *>(smem + L::oX);   // [NS][ldw] XT[c][t] = x_t[c]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g4 = (lane >> 4) * 4;
+    const int h = blockIdx.y, s = blockIdx.z;
+    const int D = d_k + d_v;
+    const int col0 = blockIdx.x * NS;          // column of S this workgroup starts at
+    const bool isK = col0 < d_k;
+    const T *src = isK ? k : v;
+    const int dsrc = isK ? d_k : d_v;
+    const int c0 = isK ? col0 : col0 - d_k;    // column inside k or v
+
+    int chunk0, nch, tok0, ntok;
+    seq_lookup(cm, s, chunk0, nch, tok0, ntok);
+
+    // this wave owns columns [wcol, wcol + 16*NI) of the slice, all M rows
+    const int wcol = wave * 16 * NI;
+    f32x4 acc[MI][NI];
+    {
+        const float *S0 = isK ? K0 : V0;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
+                    acc[mi][ni][j] = S0 ? S0[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
+                }
+    }
+    for (int n = 0; n < nch; ++n) {
+        const int t0 = tok0 + n * kChunk;
+        const int len = min(kChunk, ntok - n * kChunk);
+        // memory at the start of this chunk
+        {
+            float *Sc = S + (((size_t)(chunk0 + n) * H + h) * M) * D + col0 + wcol;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) Sc[(size_t)(mi * 16 + g4 + j) * D + ni * 16 + r] = acc[mi][ni][j];
+        }
+        gate_prep<M, kThreads>(Gs, Ss, L::ldg, tot, g + ((size_t)t0 * H + h) * M, (size_t)H * M, len, tid);
+        for (int idx = tid; idx < M * kChunk; idx += kThreads) {
+            const int i = idx % M, t = idx / M;
+            const float w = Ss[t * L::ldg + i] * __expf(Gs[(kChunk - 1) * L::ldg + i] - Gs[t * L::ldg + i]);
+            We[i * L::ldw + t] = from_f32<T>(w);
+        }
+        stage_cols<T, T>(XT, L::ldw, src + ((size_t)t0 * H + h) * dsrc + c0, (size_t)H * dsrc, kChunk, NS, len, tid,
+                         kThreads);
+        __syncthreads();
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float dec = __expf(Gs[(kChunk - 1) * L::ldg + mi * 16 + g4 + j]);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dec;
+            }
+        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, kChunk, lane);
+        __syncthreads();
+    }
+    float *ST = isK ? KT : VT;
+    if (ST) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
+                    ST[(((size_t)s * H + h) * M + i) * dsrc + c] = acc[mi][ni][j];
+                }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Chunk-parallel output kernel.
+// ---------------------------------------------------------------------------------------
+template <typename T, int M> struct OutLds {
+    static constexpr int PAD = Atom<T>::kPad;
+    static constexpr int KM = (M < 32) ? 32 : M;                // slots padded to the contraction depth
+    static constexpr int KS = (sizeof(T) == 2) ? 64 : 32;       // d_k slice streamed per step
+    static constexpr int NS = (sizeof(T) == 2) ? 128 : 64;      // d_v slice per output step
+    static constexpr int ldg = M + 4;
+    static constexpr int lda = kChunk + PAD;   // As, VT
+    static constexpr int ldp = KM + PAD;       // Ps, SvT
+    static constexpr int ldq = KS + PAD;       // Qs, Ks, Sts
+    static constexpr int ldo = NS + PAD;       // Os
+    static constexpr size_t oG = 0;
+    static constexpr size_t oS = oG + sizeof(float) * kChunk * ldg;
+    static constexpr size_t oTot = oS + sizeof(float) * kChunk * ldg;
+    static constexpr size_t oA = oTot + sizeof(float) * kThreads;
+    static constexpr size_t oP = oA + sizeof(T) * kChunk * lda;
+    static constexpr size_t oU = oP + sizeof(T) * kChunk * ldp;
+    // phase 1 view of the union
+    static constexpr size_t oQ = oU;
+    static constexpr size_t oK = oQ + sizeof(T) * kChunk * ldq;
+    static constexpr size_t oSt = oK + sizeof(T) * kChunk * ldq;
+    static constexpr size_t end1 = oSt + sizeof(T) * M * ldq;
+    // phase 4 view of the union
+    static constexpr size_t oSvT = oU;
+    static constexpr size_t oVT = oSvT + sizeof(T) * NS * ldp;
+    static constexpr size_t oO = oVT + sizeof(T) * NS * lda;
+    static constexpr size_t end4 = oO + sizeof(T) * kChunk * ldo;
+    static constexpr size_t bytes = end1 > end4 ? end1 : end4;
+};
+
+template <typename T, int M>
+__global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
+                                                           const T *__restrict__ q, const T *__restrict__ k,
+                                                           const T *__restrict__ v, const float *__restrict__ g,
+                                                           const float *__restrict__ S, T *__restrict__ o,
+                                                           float *__restrict__ z_saved)
+{
+    using L = OutLds<T, M>;
+    constexpr int MI = M / 16;
+    constexpr int CI = kChunk / 16;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *Gs = reinterpret_cast<float *>(smem + L::oG);
+    float *Ss = reinterpret_cast<float *>(smem + L::oS);
+    float *tot = reinterpret_cast<float *>(smem + L::oTot);
+    T *As = reinterpret_cast<T *>(smem + L::oA);      // [C][lda]  A = QK^T masked, later A2
+    T *Ps = reinterpret_cast<T *>(smem + L::oP);      // [C][ldp]  gated softmax weights
+    T *Qs = reinterpret_cast<T *>(smem + L::oQ);
+    T *Ks = reinterpret_cast<T *>(smem + L::oK);
+    T *Sts = reinterpret_cast<T *>(smem + L::oSt);
+    T *SvT = reinterpret_cast<T *>(smem + L::oSvT);
+    T *VT = reinterpret_cast<T *>(smem + L::oVT);
+    T *Os = reinterpret_cast<T *>(smem + L::oO);
+
+    ChunkInfo ci;
+    if (!chunk_lookup(cm, blockIdx.x, ci)) return;
+    const int h = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = lane & 15, gq = lane >> 4, g4 = gq * 4, g8 = gq * 8;
+    const int D = d_k + d_v;
+    const size_t tokh = (size_t)ci.tok0 * H + h;
+    const float *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;   // memory at chunk start [M][D]
+
+    gate_prep<M, kThreads>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
+
+    // ---- phase 1: A = Q K^T and the inter-chunk scores Q Kt^T, streamed over d_k
+    f32x4 accA[1][CI], accZ[1][MI];
+    zero_acc(accA);
+    zero_acc(accZ);
+    for (int ks = 0; ks < d_k; ks += L::KS) {
+        stage_rows<T, T>(Qs, L::ldq, q + tokh * d_k + ks, (size_t)H * d_k, kChunk, L::KS, ci.len, tid, kThreads);
+        stage_rows<T, T>(Ks, L::ldq, k + tokh * d_k + ks, (size_t)H * d_k, kChunk, L::KS, ci.len, tid, kThreads);
+        stage_rows<T, float>(Sts, L::ldq, Sc + ks, (size_t)D, M, L::KS, M, tid, kThreads);
+        __syncthreads();
+        gemm_nt<T, 1, CI>(accA, Qs + (16 * w) * L::ldq, L::ldq, Ks, L::ldq, L::KS, lane);
+        gemm_nt<T, 1, MI>(accZ, Qs + (16 * w) * L::ldq, L::ldq, Sts, L::ldq, L::KS, lane);
+        __syncthreads();
+    }
+
+    // ---- phase 2: gated intra-chunk scores, softmax, gated pass-2 weights (wave w = row block w)
+    const int rowb = 16 * w;                   // first row of this wave's block
+    const int kend = rowb + 16;                // tokens this block may look at
+#pragma unroll
+    for (int ni = 0; ni < CI; ++ni)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = rowb + g4 + j, rr = ni * 16 + r;
+            As[t * L::lda + rr] = from_f32<T>(rr <= t ? accA[0][ni][j] : 0.f);
+        }
+    __syncthreads();
+    f32x4 accI[1][MI];
+    zero_acc(accI);
+    for (int k0 = 0; k0 < kend; k0 += 32) {
+        const typename Atom<T>::Frag a = Atom<T>::load(As + (rowb + r) * L::lda + k0 + g8);
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) {
+            const int i = ni * 16 + r;
+            const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
+            typename Atom<T>::Frag b;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int kk = k0 + g8 + e;
+                float val = 0.f;
+                if (kk < kend) val = Ss[kk * L::ldg + i] * __expf(fminf(gref - Gs[kk * L::ldg + i], kExpClamp));
+                b[e] = from_f32<T>(val);
+            }
+            Atom<T>::mma(accI[0][ni], a, b);
+        }
+    }
+    float p[MI][4];
+    float rmax[4], rsum[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni) {
+        const int i = ni * 16 + r;
+        const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = rowb + g4 + j;
+            const float G = Gs[t * L::ldg + i];
+            const float z = scale * (__expf(G) * accZ[0][ni][j] + __expf(G - gref) * accI[0][ni][j]);
+            p[ni][j] = z;
+            rmax[j] = fmaxf(rmax[j], z);
+            if (z_saved && t < ci.len) z_saved[(tokh + (size_t)t * H) * M + i] = z;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { rmax[j] = row16_max(rmax[j]); rsum[j] = 0.f; }
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(p[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni) {
+        const int i = ni * 16 + r;
+        const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = rowb + g4 + j;
+            p[ni][j] *= rsum[j];
+            Ps[t * L::ldp + i] = from_f32<T>(p[ni][j] * __expf(Gs[t * L::ldg + i] - gref));
+        }
+    }
+    if (M < L::KM) {   // zero the padded slot columns
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Ps[(rowb + g4 + j) * L::ldp + M + r] = from_f32<T>(0.f);
+    }
+    __syncthreads();
+    // A2[t][r] = sum_i p_t[i] s_r[i] exp(G_t[i] - G_r[i]) for r <= t, row block w, column blocks <= w
+    {
+        f32x4 acc2[1][CI];
+        zero_acc(acc2);
+        for (int k0 = 0; k0 < L::KM; k0 += 32) {
+            const typename Atom<T>::Frag a = Atom<T>::load(Ps + (rowb + r) * L::ldp + k0 + g8);
+#pragma unroll
+            for (int ni = 0; ni < CI; ++ni) {
+                if (ni > w) continue;
+                const int rr = ni * 16 + r;
+                typename Atom<T>::Frag b;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int i = k0 + g8 + e;
+                    float val = 0.f;
+                    if (i < M) {
+                        const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
+                        val = Ss[rr * L::ldg + i] * __expf(fminf(gref - Gs[rr * L::ldg + i], kExpClamp));
+                    }
+                    b[e] = from_f32<T>(val);
+                }
+                Atom<T>::mma(acc2[0][ni], a, b);
+            }
+        }
+#pragma unroll
+        for (int ni = 0; ni < CI; ++ni) {
+            if (ni > w) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int t = rowb + g4 + j, rr = ni * 16 + r;
+                As[t * L::lda + rr] = from_f32<T>(rr <= t ? acc2[0][ni][j] : 0.f);
+            }
+        }
+    }
+    // inter-chunk pass-2 weights p * exp(G)
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni) {
+        const int i = ni * 16 + r;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = rowb + g4 + j;
+            Ps[t * L::ldp + i] = from_f32<T>(p[ni][j] * __expf(Gs[t * L::ldg + i]));
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 4: o = [p exp(G) | A2] [Vt ; V], streamed over d_v
+    for (int cs = 0; cs < d_v; cs += L::NS) {
+        const int ncols = min(L::NS, d_v - cs);
+        stage_cols<T, float>(SvT, L::ldp, Sc + d_k + cs, (size_t)D, M, ncols, M, tid, kThreads);
+        if (M < L::KM) {
+            for (int idx = tid; idx < ncols * (L::KM - M); idx += kThreads)
+                SvT[(idx / (L::KM - M)) * L::ldp + M + idx % (L::KM - M)] = from_f32<T>(0.f);
+        }
+        stage_cols<T, T>(VT, L::lda, v + tokh * d_v + cs, (size_t)H * d_v, kChunk, ncols, ci.len, tid, kThreads);
+        __syncthreads();
+        if (32 * w < ncols) {
+            f32x4 acc[CI][2];
+            zero_acc(acc);
+            gemm_nt<T, CI, 2>(acc, Ps, L::ldp, SvT + (32 * w) * L::ldp, L::ldp, L::KM, lane);
+            gemm_nt<T, CI, 2>(acc, As, L::lda, VT + (32 * w) * L::lda, L::lda, kChunk, lane);
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        Os[(mi * 16 + g4 + j) * L::ldo + 32 * w + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+        }
+        __syncthreads();
+        const int vpr = ncols >> 3;
+        for (int idx = tid; idx < kChunk * vpr; idx += kThreads) {
+            const int t = idx / vpr, c = (idx - t * vpr) << 3;
+            if (t < ci.len) {
+                const T *srcp = Os + t * L::ldo + c;
+                T *dstp = o + (tokh + (size_t)t * H) * d_v + cs + c;
+                if (sizeof(T) == 2) {
+                    *reinterpret_cast<f32x4 *>(dstp) = *reinterpret_cast<const f32x4 *>(srcp);
+                } else {
+                    *reinterpret_cast<f32x4 *>(dstp) = *reinterpret_cast<const f32x4 *>(srcp);
+                    *reinterpret_cast<f32x4 *>(dstp + 4) = *reinterpret_cast<const f32x4 *>(srcp + 4);
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------
+template <typename T, int M, int NS>
+static hipError_t run_scan_fwd(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
+                               const float *K0, const float *V0, float *S, float *KT, float *VT, hipStream_t st)
+{
+    auto kern = scan_fwd_kernel<T, M, NS>;
+    const size_t lds = ScanLds<T, M, NS>::bytes;
+    GSA_HIP_TRY(allow_lds(kern, lds));
+    dim3 grid((pl.d_k + pl.d_v) / NS, pl.H, pl.n_seqs);
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)k, (const T *)v, g,
+                       K0, V0, S, KT, VT);
+    return hipGetLastError();
+}
+
+template <typename T, int M>
+hipError_t launch_scan_fwd_tm(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
+                              const float *K0, const float *V0, float *S, float *KT, float *VT, hipStream_t st)
+{
+    // 128-column slices when both widths allow it and the grid still covers the chip
+    const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
+                      ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
+    if (wide) return run_scan_fwd<T, M, 128>(pl, cm, k, v, g, K0, V0, S, KT, VT, st);
+    return run_scan_fwd<T, M, 64>(pl, cm, k, v, g, K0, V0, S, KT, VT, st);
+}
+
+template <typename T, int M>
+static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, const void *k, const void *v,
+                                const float *g, const float *K0, const float *V0, void *o, float *z_saved, float *KT,
+                                float *VT, hipStream_t st)
+{
+    const ChunkMap cm = make_chunk_map(pl, w);
+    GSA_HIP_TRY((launch_scan_fwd_tm<T, M>(pl, cm, k, v, g, K0, V0, w.S, KT, VT, st)));
+    auto kern = out_fwd_kernel<T, M>;
+    const size_t lds = OutLds<T, M>::bytes;
+    GSA_HIP_TRY(allow_lds(kern, lds));
+    dim3 grid(pl.chunk_slots, pl.H);
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
+                       (const T *)k, (const T *)v, g, w.S, (T *)o, z_saved);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_fwd_t(const Plan &pl, const Work &w, const void *q, const void *k, const void *v,
+                               const float *g, const float *K0, const float *V0, void *o, float *z_saved, float *KT,
+                               float *VT, hipStream_t st)
+{
+    switch (pl.m) {
+    case 16: return launch_fwd_tm<T, 16>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    case 32: return launch_fwd_tm<T, 32>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    case 64: return launch_fwd_tm<T, 64>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    default: return launch_fwd_tm<T, 128>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    }
+}
+
+hipError_t launch_fwd(const Plan &pl, const Work &w, const void *q, const void *k, const void *v, const float *g,
+                      const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT, hipStream_t st)
+{
+    if (pl.chunk_slots == 0 || pl.tokens == 0) return hipSuccess;
+    GSA_HIP_TRY(launch_prepare(pl, w, st));
+    if (pl.dtype == 0) return launch_fwd_t<float>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    return launch_fwd_t<bf16_t>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+}
+
+// explicit instantiations used by the backward translation unit (state recomputation)
+#define GSA_INST_SCAN(T, M)                                                                                         \
+    template hipError_t launch_scan_fwd_tm<T, M>(const Plan &, const ChunkMap &, const void *, const void *,         \
+                                                 const float *, const float *, const float *, float *, float *,       \
+                                                 float *, hipStream_t);
+GSA_INST_SCAN(float, 16) GSA_INST_SCAN(float, 32) GSA_INST_SCAN(float, 64) GSA_INST_SCAN(float, 128)
+GSA_INST_SCAN(bf16_t, 16) GSA_INST_SCAN(bf16_t, 32) GSA_INST_SCAN(bf16_t, 64) GSA_INST_SCAN(bf16_t, 128)
+
+}  // namespace gsa
