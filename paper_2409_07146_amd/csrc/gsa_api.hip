@@ -36,8 +36,9 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     pl->dtype = p->dtype; pl->scale = p->scale; pl->cu_seqlens = p->cu_seqlens;
     pl->n_seqs = p->cu_seqlens ? p->n_seqs : p->B;
     pl->tokens = tokens;
-    const int64_t slots = p->cu_seqlens ? ((int64_t)p->T / gsa::kChunk + p->n_seqs)
-                                        : (int64_t)p->B * ((p->T + gsa::kChunk - 1) / gsa::kChunk);
+    pl->chunk = gsa::chunk_of_dtype(p->dtype);
+    const int64_t slots = p->cu_seqlens ? ((int64_t)p->T / pl->chunk + p->n_seqs)
+                                        : (int64_t)p->B * ((p->T + pl->chunk - 1) / pl->chunk);
     if (slots > 0x3fffffff) return GSA_ERR_SHAPE;
     pl->chunk_slots = (int32_t)slots;
     const size_t state = (size_t)slots * p->H * p->m * (size_t)(p->d_k + p->d_v) * sizeof(float);
@@ -47,6 +48,7 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     pl->off_seqtab = off; off += align_up(p->cu_seqlens ? (size_t)p->n_seqs * 4 * sizeof(int32_t) : 0);
     pl->off_S = off;      off += align_up(state);
     pl->total_fwd = off;
+    pl->off_SF = off;     off += align_up((size_t)pl->n_seqs * p->H * p->m * (size_t)(p->d_k + p->d_v) * sizeof(float));
     pl->off_E = off;      off += align_up(state);
     pl->off_dz = off;     off += align_up(tokm);
     pl->off_dgf = off;    off += align_up(tokm);
@@ -61,6 +63,7 @@ Work make_work(const Plan &pl, void *ws)
     w.table = reinterpret_cast<int32_t *>(b + pl.off_table);
     w.seqtab = reinterpret_cast<int32_t *>(b + pl.off_seqtab);
     w.S = reinterpret_cast<float *>(b + pl.off_S);
+    w.SF = reinterpret_cast<float *>(b + pl.off_SF);
     w.E = reinterpret_cast<float *>(b + pl.off_E);
     w.dz = reinterpret_cast<float *>(b + pl.off_dz);
     w.dgf = reinterpret_cast<float *>(b + pl.off_dgf);

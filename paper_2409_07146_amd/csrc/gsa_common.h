@@ -20,7 +20,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kWave = 64;
-constexpr int kChunk = 64;          // tokens per chunk (C in Appendix A)
 constexpr int kSub = 16;            // row block inside a chunk sharing one gate reference
 constexpr float kGateFloor = -30.f; // log-gates below this are treated as this
 constexpr float kExpClamp = 80.f;   // largest exponent a factored gate may carry in fp32
@@ -67,6 +66,15 @@ template <> struct Atom<float> {
         for (int e = 0; e < 8; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], c, 0, 0, 0);
     }
 };
+
+// Chunk geometry per element type: one wave per 16-token row block.  fp32 tiles are
+// twice as large in LDS, so the fp32 path uses half the chunk.
+template <typename T> struct Geo {
+    static constexpr int C = (sizeof(T) == 2) ? 64 : 32;   // tokens per chunk
+    static constexpr int NW = C / kSub;                    // waves per workgroup
+    static constexpr int NT = NW * kWave;                  // threads per workgroup
+};
+inline int chunk_of_dtype(int dtype) { return dtype == 0 ? Geo<float>::C : Geo<bf16_t>::C; }
 
 // acc[MI][NI] += A[16*mi + r][k] * B[16*ni + r][k] summed over k in [0,K), K a multiple of 32.
 // A and B are LDS tiles stored [row][k] with row strides lda, ldb (elements).
@@ -178,7 +186,8 @@ struct ChunkMap {
     const int32_t *table;   // packed: [4 * n_chunk_slots] = {seq, tok0, len, index in seq}; batch: NULL
     const int32_t *seq_tab; // packed: [4 * n_seqs] = {first chunk id, number of chunks, first token, tokens}
     int32_t T;              // batch: tokens per sequence
-    int32_t chunks_per_seq; // batch: ceil(T / kChunk)
+    int32_t chunk;          // tokens per chunk (C in Appendix A)
+    int32_t chunks_per_seq; // batch: ceil(T / chunk)
     int32_t n_chunk_slots;  // upper bound on the number of chunks (grid size)
 };
 
@@ -195,9 +204,9 @@ __device__ __forceinline__ bool chunk_lookup(const ChunkMap &cm, int c, ChunkInf
     }
     ci.seq = c / cm.chunks_per_seq;
     ci.idx = c - ci.seq * cm.chunks_per_seq;
-    const int off = ci.idx * kChunk;
+    const int off = ci.idx * cm.chunk;
     ci.tok0 = ci.seq * cm.T + off;
-    ci.len = min(kChunk, cm.T - off);
+    ci.len = min(cm.chunk, cm.T - off);
     return true;
 }
 
@@ -223,16 +232,15 @@ __device__ __forceinline__ void seq_lookup(const ChunkMap &cm, int s, int &chunk
 //   Gs[t][i] = sum_{j<=t} max(g_j[i], floor)      chunk-local inclusive cumulative log gate
 //   Ss[t][i] = 1 - exp(g_t[i])                    write intensity (0 on padded rows)
 // Rows t >= len are padded with g = 0.  Needs blockDim.x = NT threads, NT % M == 0,
-// (kChunk * M) % (4 * NT) == 0, and `tot` scratch of (NT/M) * M floats.
-// Ends with a __syncthreads().
+// C % (NT/M) == 0, and `tot` scratch of NT floats.  Ends with a __syncthreads().
 // ----------------------------------------------------------------------------
-template <int M, int NT>
+template <int M, int NT, int C>
 __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *tot, const float *g, size_t gld,
                                           int len, int tid)
 {
     constexpr int P = NT / M;            // token partitions
-    constexpr int TP = kChunk / P;       // tokens per partition
-    static_assert(NT % M == 0 && kChunk % P == 0, "gate_prep partitioning");
+    constexpr int TP = C / P;            // tokens per partition
+    static_assert(NT % M == 0 && C % P == 0, "gate_prep partitioning");
     const int i = tid % M, part = tid / M;
     float run = 0.f;
 #pragma unroll 4

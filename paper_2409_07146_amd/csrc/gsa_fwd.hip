@@ -20,17 +20,15 @@
 // second is <= 1 for every earlier block and bounded by the decay inside one 16-token
 // block on the diagonal.  If that bound exceeds e^80 (not reachable with the paper's gate
 // parameterisation) the diagonal block is evaluated pairwise without factoring.
+#include "gsa_chunk.h"
 #include "gsa_launch.h"
 
 namespace gsa {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
-
 // ---------------------------------------------------------------------------------------
 // Packed form: build the chunk table from the device-side sequence offsets.
 // ---------------------------------------------------------------------------------------
-__global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T, int chunk_slots,
+__global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T, int kChunk, int chunk_slots,
                                int32_t *__restrict__ table, int32_t *__restrict__ seqtab)
 {
     __shared__ int total;
@@ -69,8 +67,8 @@ __global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T
 hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
 {
     if (!pl.cu_seqlens) return hipSuccess;
-    hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(256), 0, st, pl.cu_seqlens, pl.n_seqs, pl.T, pl.chunk_slots,
-                       w.table, w.seqtab);
+    hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(256), 0, st, pl.cu_seqlens, pl.n_seqs, pl.T, pl.chunk,
+                       pl.chunk_slots, w.table, w.seqtab);
     return hipGetLastError();
 }
 
@@ -79,27 +77,30 @@ hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
 //     S_n = Diag(exp G_C) S_{n-1} + (s * exp(G_C - G))^T [k | v]
 // ---------------------------------------------------------------------------------------
 template <typename T, int M, int NS> struct ScanLds {
+    static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int ldg = M + 4;
-    static constexpr int ldw = kChunk + PAD;
+    static constexpr int ldw = C + PAD;
     static constexpr size_t oG = 0;
-    static constexpr size_t oS = oG + sizeof(float) * kChunk * ldg;
-    static constexpr size_t oTot = oS + sizeof(float) * kChunk * ldg;
-    static constexpr size_t oW = oTot + sizeof(float) * kThreads;
+    static constexpr size_t oS = oG + sizeof(float) * C * ldg;
+    static constexpr size_t oTot = oS + sizeof(float) * C * ldg;
+    static constexpr size_t oW = oTot + sizeof(float) * Geo<T>::NT;
     static constexpr size_t oX = oW + sizeof(T) * M * ldw;
     static constexpr size_t bytes = oX + sizeof(T) * NS * ldw;
 };
 
 template <typename T, int M, int NS>
-__global__ __launch_bounds__(kThreads) void scan_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v,
-                                                            const T *__restrict__ k, const T *__restrict__ v,
-                                                            const float *__restrict__ g,
-                                                            const float *__restrict__ K0, const float *__restrict__ V0,
-                                                            float *__restrict__ S, float *__restrict__ KT,
-                                                            float *__restrict__ VT)
+__global__ __launch_bounds__(Geo<T>::NT) void scan_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v,
+                                                              const T *__restrict__ k, const T *__restrict__ v,
+                                                              const float *__restrict__ g,
+                                                              const float *__restrict__ K0,
+                                                              const float *__restrict__ V0, float *__restrict__ S,
+                                                              float *__restrict__ KT, float *__restrict__ VT,
+                                                              float *__restrict__ SF)
 {
     using L = ScanLds<T, M, NS>;
-    constexpr int MI = M / 16, NI = NS / 64;
+    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
+    constexpr int MI = M / 16, NI = NS / (16 * NW);
     extern __shared__ __align__(16) unsigned char smem[];
     float *Gs = reinterpret_cast<float *>(smem + L::oG);
     float *Ss = reinterpret_cast<float *>(smem + L::oS);
@@ -136,8 +137,8 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(ChunkMap cm, int H, 
                 }
     }
     for (int n = 0; n < nch; ++n) {
-        const int t0 = tok0 + n * kChunk;
-        const int len = min(kChunk, ntok - n * kChunk);
+        const int t0 = tok0 + n * C;
+        const int len = min(C, ntok - n * C);
         // memory at the start of this chunk
         {
             float *Sc = S + (((size_t)(chunk0 + n) * H + h) * M) * D + col0 + wcol;
@@ -148,82 +149,87 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(ChunkMap cm, int H, 
 #pragma unroll
                     for (int j = 0; j < 4; ++j) Sc[(size_t)(mi * 16 + g4 + j) * D + ni * 16 + r] = acc[mi][ni][j];
         }
-        gate_prep<M, kThreads>(Gs, Ss, L::ldg, tot, g + ((size_t)t0 * H + h) * M, (size_t)H * M, len, tid);
-        for (int idx = tid; idx < M * kChunk; idx += kThreads) {
+        gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + ((size_t)t0 * H + h) * M, (size_t)H * M, len, tid);
+        for (int idx = tid; idx < M * C; idx += NT) {
             const int i = idx % M, t = idx / M;
-            const float w = Ss[t * L::ldg + i] * __expf(Gs[(kChunk - 1) * L::ldg + i] - Gs[t * L::ldg + i]);
+            const float w = Ss[t * L::ldg + i] * __expf(Gs[(C - 1) * L::ldg + i] - Gs[t * L::ldg + i]);
             We[i * L::ldw + t] = from_f32<T>(w);
         }
-        stage_cols<T, T>(XT, L::ldw, src + ((size_t)t0 * H + h) * dsrc + c0, (size_t)H * dsrc, kChunk, NS, len, tid,
-                         kThreads);
+        stage_cols<T, T>(XT, L::ldw, src + ((size_t)t0 * H + h) * dsrc + c0, (size_t)H * dsrc, C, NS, len, tid, NT);
         __syncthreads();
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float dec = __expf(Gs[(kChunk - 1) * L::ldg + mi * 16 + g4 + j]);
+                const float dec = __expf(Gs[(C - 1) * L::ldg + mi * 16 + g4 + j]);
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dec;
             }
-        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, kChunk, lane);
+        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, C, lane);
         __syncthreads();
     }
+    // memories after the last token: the caller's output and/or the joint copy the backward uses
     float *ST = isK ? KT : VT;
-    if (ST) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
-                    ST[(((size_t)s * H + h) * M + i) * dsrc + c] = acc[mi][ni][j];
-                }
-    }
+            for (int j = 0; j < 4; ++j) {
+                const int i = mi * 16 + g4 + j, c = wcol + ni * 16 + r;
+                if (ST) ST[(((size_t)s * H + h) * M + i) * dsrc + c0 + c] = acc[mi][ni][j];
+                if (SF) SF[(((size_t)s * H + h) * M + i) * D + col0 + c] = acc[mi][ni][j];
+            }
 }
 
 // ---------------------------------------------------------------------------------------
 // Chunk-parallel output kernel.
 // ---------------------------------------------------------------------------------------
 template <typename T, int M> struct OutLds {
+    static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int KM = (M < 32) ? 32 : M;                // slots padded to the contraction depth
     static constexpr int KS = (sizeof(T) == 2) ? 64 : 32;       // d_k slice streamed per step
     static constexpr int NS = (sizeof(T) == 2) ? 128 : 64;      // d_v slice per output step
     static constexpr int ldg = M + 4;
-    static constexpr int lda = kChunk + PAD;   // As, VT
+    static constexpr int lda = C + PAD;        // As, VT
     static constexpr int ldp = KM + PAD;       // Ps, SvT
     static constexpr int ldq = KS + PAD;       // Qs, Ks, Sts
     static constexpr int ldo = NS + PAD;       // Os
     static constexpr size_t oG = 0;
-    static constexpr size_t oS = oG + sizeof(float) * kChunk * ldg;
-    static constexpr size_t oTot = oS + sizeof(float) * kChunk * ldg;
-    static constexpr size_t oA = oTot + sizeof(float) * kThreads;
-    static constexpr size_t oP = oA + sizeof(T) * kChunk * lda;
-    static constexpr size_t oU = oP + sizeof(T) * kChunk * ldp;
+    static constexpr size_t oS = oG + sizeof(float) * C * ldg;
+    static constexpr size_t oTot = oS + sizeof(float) * C * ldg;
+    static constexpr size_t oA = oTot + sizeof(float) * Geo<T>::NT;
+    static constexpr size_t oP = oA + sizeof(T) * C * lda;
+    static constexpr size_t oU = oP + sizeof(T) * C * ldp;
     // phase 1 view of the union
     static constexpr size_t oQ = oU;
-    static constexpr size_t oK = oQ + sizeof(T) * kChunk * ldq;
-    static constexpr size_t oSt = oK + sizeof(T) * kChunk * ldq;
+    static constexpr size_t oK = oQ + sizeof(T) * C * ldq;
+    static constexpr size_t oSt = oK + sizeof(T) * C * ldq;
     static constexpr size_t end1 = oSt + sizeof(T) * M * ldq;
+    // phase 2 view (only when a block takes the unfactored path): fp32 softmax weights
+    static constexpr size_t oPf = oU;
+    static constexpr size_t end2 = oPf + sizeof(float) * C * ldg;
     // phase 4 view of the union
     static constexpr size_t oSvT = oU;
     static constexpr size_t oVT = oSvT + sizeof(T) * NS * ldp;
     static constexpr size_t oO = oVT + sizeof(T) * NS * lda;
-    static constexpr size_t end4 = oO + sizeof(T) * kChunk * ldo;
-    static constexpr size_t bytes = end1 > end4 ? end1 : end4;
+    static constexpr size_t end4 = oO + sizeof(T) * C * ldo;
+    static constexpr size_t e12 = end1 > end2 ? end1 : end2;
+    static constexpr size_t bytes = e12 > end4 ? e12 : end4;
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
-                                                           const T *__restrict__ q, const T *__restrict__ k,
-                                                           const T *__restrict__ v, const float *__restrict__ g,
-                                                           const float *__restrict__ S, T *__restrict__ o,
-                                                           float *__restrict__ z_saved)
+__global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
+                                                             const T *__restrict__ q, const T *__restrict__ k,
+                                                             const T *__restrict__ v, const float *__restrict__ g,
+                                                             const float *__restrict__ S, T *__restrict__ o,
+                                                             float *__restrict__ z_saved)
 {
     using L = OutLds<T, M>;
-    constexpr int MI = M / 16;
-    constexpr int CI = kChunk / 16;
+    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
+    constexpr int MI = M / 16, CI = C / 16;
+    constexpr int NIo = L::NS / (16 * NW);     // output column atoms per wave
     extern __shared__ __align__(16) unsigned char smem[];
     float *Gs = reinterpret_cast<float *>(smem + L::oG);
     float *Ss = reinterpret_cast<float *>(smem + L::oS);
@@ -233,6 +239,7 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
     T *Qs = reinterpret_cast<T *>(smem + L::oQ);
     T *Ks = reinterpret_cast<T *>(smem + L::oK);
     T *Sts = reinterpret_cast<T *>(smem + L::oSt);
+    float *Pf = reinterpret_cast<float *>(smem + L::oPf);
     T *SvT = reinterpret_cast<T *>(smem + L::oSvT);
     T *VT = reinterpret_cast<T *>(smem + L::oVT);
     T *Os = reinterpret_cast<T *>(smem + L::oO);
@@ -241,70 +248,30 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
     if (!chunk_lookup(cm, blockIdx.x, ci)) return;
     const int h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int r = lane & 15, gq = lane >> 4, g4 = gq * 4, g8 = gq * 8;
+    const int r = lane & 15, g4 = (lane >> 4) * 4;
     const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const float *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;   // memory at chunk start [M][D]
+    const int rowb = 16 * w;                                        // this wave's row block
 
-    gate_prep<M, kThreads>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
+    gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
 
-    // ---- phase 1: A = Q K^T and the inter-chunk scores Q Kt^T, streamed over d_k
-    f32x4 accA[1][CI], accZ[1][MI];
-    zero_acc(accA);
-    zero_acc(accZ);
-    for (int ks = 0; ks < d_k; ks += L::KS) {
-        stage_rows<T, T>(Qs, L::ldq, q + tokh * d_k + ks, (size_t)H * d_k, kChunk, L::KS, ci.len, tid, kThreads);
-        stage_rows<T, T>(Ks, L::ldq, k + tokh * d_k + ks, (size_t)H * d_k, kChunk, L::KS, ci.len, tid, kThreads);
-        stage_rows<T, float>(Sts, L::ldq, Sc + ks, (size_t)D, M, L::KS, M, tid, kThreads);
-        __syncthreads();
-        gemm_nt<T, 1, CI>(accA, Qs + (16 * w) * L::ldq, L::ldq, Ks, L::ldq, L::KS, lane);
-        gemm_nt<T, 1, MI>(accZ, Qs + (16 * w) * L::ldq, L::ldq, Sts, L::ldq, L::KS, lane);
-        __syncthreads();
-    }
-
-    // ---- phase 2: gated intra-chunk scores, softmax, gated pass-2 weights (wave w = row block w)
-    const int rowb = 16 * w;                   // first row of this wave's block
-    const int kend = rowb + 16;                // tokens this block may look at
-#pragma unroll
-    for (int ni = 0; ni < CI; ++ni)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int t = rowb + g4 + j, rr = ni * 16 + r;
-            As[t * L::lda + rr] = from_f32<T>(rr <= t ? accA[0][ni][j] : 0.f);
-        }
-    __syncthreads();
-    f32x4 accI[1][MI];
-    zero_acc(accI);
-    for (int k0 = 0; k0 < kend; k0 += 32) {
-        const typename Atom<T>::Frag a = Atom<T>::load(As + (rowb + r) * L::lda + k0 + g8);
-#pragma unroll
-        for (int ni = 0; ni < MI; ++ni) {
-            const int i = ni * 16 + r;
-            const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
-            typename Atom<T>::Frag b;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int kk = k0 + g8 + e;
-                float val = 0.f;
-                if (kk < kend) val = Ss[kk * L::ldg + i] * __expf(fminf(gref - Gs[kk * L::ldg + i], kExpClamp));
-                b[e] = from_f32<T>(val);
-            }
-            Atom<T>::mma(accI[0][ni], a, b);
-        }
-    }
+    // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
     float p[MI][4];
+    bool unsafe;
+    gated_scores<T, M, C, L::KS>(p, unsafe, Gs, Ss, L::ldg, As, L::lda, Qs, Ks, Sts, L::ldq, q + tokh * d_k,
+                                 k + tokh * d_k, (size_t)H * d_k, d_k, Sc, (size_t)D, ci.len, tid);
+    // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) {
         const int i = ni * 16 + r;
-        const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
-            const float G = Gs[t * L::ldg + i];
-            const float z = scale * (__expf(G) * accZ[0][ni][j] + __expf(G - gref) * accI[0][ni][j]);
+            const float z = scale * p[ni][j];
             p[ni][j] = z;
             rmax[j] = fmaxf(rmax[j], z);
             if (z_saved && t < ci.len) z_saved[(tokh + (size_t)t * H) * M + i] = z;
@@ -318,15 +285,17 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
         for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(p[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
+    // ---- pass 2 weights: P-bar = p * exp(G - Gref) as the operand of the pair-weight contraction
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) {
         const int i = ni * 16 + r;
-        const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
+        const float gref = rowb ? Gs[(rowb - 1) * L::ldg + i] : 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
             p[ni][j] *= rsum[j];
             Ps[t * L::ldp + i] = from_f32<T>(p[ni][j] * __expf(Gs[t * L::ldg + i] - gref));
+            if (unsafe) Pf[t * L::ldg + i] = p[ni][j];
         }
     }
     if (M < L::KM) {   // zero the padded slot columns
@@ -334,29 +303,15 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
         for (int j = 0; j < 4; ++j) Ps[(rowb + g4 + j) * L::ldp + M + r] = from_f32<T>(0.f);
     }
     __syncthreads();
-    // A2[t][r] = sum_i p_t[i] s_r[i] exp(G_t[i] - G_r[i]) for r <= t, row block w, column blocks <= w
     {
-        f32x4 acc2[1][CI];
-        zero_acc(acc2);
-        for (int k0 = 0; k0 < L::KM; k0 += 32) {
-            const typename Atom<T>::Frag a = Atom<T>::load(Ps + (rowb + r) * L::ldp + k0 + g8);
+        // A2[t][r] = sum_i p_t[i] s_r[i] exp(G_t[i] - G_r[i]) for r <= t; overwrites this block's rows of As
+        f32x4 acc2[CI];
+        pair_weights<T, M, C, L::KM>(acc2, Ps, L::ldp, Gs, Ss, L::ldg, unsafe, lane, w);
+        if (unsafe) {
+            const f32x4 ex = pair_weights_exact<M>(Pf, L::ldg, Gs, Ss, L::ldg, lane, rowb);
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) {
-                if (ni > w) continue;
-                const int rr = ni * 16 + r;
-                typename Atom<T>::Frag b;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int i = k0 + g8 + e;
-                    float val = 0.f;
-                    if (i < M) {
-                        const float gref = (w == 0) ? 0.f : Gs[(rowb - 1) * L::ldg + i];
-                        val = Ss[rr * L::ldg + i] * __expf(fminf(gref - Gs[rr * L::ldg + i], kExpClamp));
-                    }
-                    b[e] = from_f32<T>(val);
-                }
-                Atom<T>::mma(acc2[0][ni], a, b);
-            }
+            for (int ni = 0; ni < CI; ++ni)
+                if (ni == w) acc2[ni] = ex;
         }
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) {
@@ -364,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int t = rowb + g4 + j, rr = ni * 16 + r;
-                As[t * L::lda + rr] = from_f32<T>(rr <= t ? acc2[0][ni][j] : 0.f);
+                As[t * L::lda + rr] = from_f32<T>(rr <= t ? acc2[ni][j] : 0.f);
             }
         }
     }
@@ -380,44 +335,32 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
     }
     __syncthreads();
 
-    // ---- phase 4: o = [p exp(G) | A2] [Vt ; V], streamed over d_v
+    // ---- o = [p exp(G) | A2] [Vt ; V], streamed over d_v (Eq. (gla-chunk) with the gate on the slot/key side)
     for (int cs = 0; cs < d_v; cs += L::NS) {
         const int ncols = min(L::NS, d_v - cs);
-        stage_cols<T, float>(SvT, L::ldp, Sc + d_k + cs, (size_t)D, M, ncols, M, tid, kThreads);
+        stage_cols<T, float>(SvT, L::ldp, Sc + d_k + cs, (size_t)D, M, ncols, M, tid, NT);
         if (M < L::KM) {
-            for (int idx = tid; idx < ncols * (L::KM - M); idx += kThreads)
+            for (int idx = tid; idx < ncols * (L::KM - M); idx += NT)
                 SvT[(idx / (L::KM - M)) * L::ldp + M + idx % (L::KM - M)] = from_f32<T>(0.f);
         }
-        stage_cols<T, T>(VT, L::lda, v + tokh * d_v + cs, (size_t)H * d_v, kChunk, ncols, ci.len, tid, kThreads);
+        stage_cols<T, T>(VT, L::lda, v + tokh * d_v + cs, (size_t)H * d_v, C, ncols, ci.len, tid, NT);
         __syncthreads();
-        if (32 * w < ncols) {
-            f32x4 acc[CI][2];
+        const int wcol = 16 * NIo * w;
+        if (wcol < ncols) {
+            f32x4 acc[CI][NIo];
             zero_acc(acc);
-            gemm_nt<T, CI, 2>(acc, Ps, L::ldp, SvT + (32 * w) * L::ldp, L::ldp, L::KM, lane);
-            gemm_nt<T, CI, 2>(acc, As, L::lda, VT + (32 * w) * L::lda, L::lda, kChunk, lane);
+            gemm_nt<T, CI, NIo>(acc, Ps, L::ldp, SvT + wcol * L::ldp, L::ldp, L::KM, lane);
+            gemm_nt<T, CI, NIo>(acc, As, L::lda, VT + wcol * L::lda, L::lda, C, lane);
 #pragma unroll
             for (int mi = 0; mi < CI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
+                for (int ni = 0; ni < NIo; ++ni)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        Os[(mi * 16 + g4 + j) * L::ldo + 32 * w + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+                        Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
         }
         __syncthreads();
-        const int vpr = ncols >> 3;
-        for (int idx = tid; idx < kChunk * vpr; idx += kThreads) {
-            const int t = idx / vpr, c = (idx - t * vpr) << 3;
-            if (t < ci.len) {
-                const T *srcp = Os + t * L::ldo + c;
-                T *dstp = o + (tokh + (size_t)t * H) * d_v + cs + c;
-                if (sizeof(T) == 2) {
-                    *reinterpret_cast<f32x4 *>(dstp) = *reinterpret_cast<const f32x4 *>(srcp);
-                } else {
-                    *reinterpret_cast<f32x4 *>(dstp) = *reinterpret_cast<const f32x4 *>(srcp);
-                    *reinterpret_cast<f32x4 *>(dstp + 4) = *reinterpret_cast<const f32x4 *>(srcp + 4);
-                }
-            }
-        }
+        store_tile<T>(o + tokh * d_v + cs, (size_t)H * d_v, Os, L::ldo, C, ncols, ci.len, tid, NT);
         __syncthreads();
     }
 }
@@ -427,26 +370,28 @@ __global__ __launch_bounds__(kThreads) void out_fwd_kernel(ChunkMap cm, int H, i
 // ---------------------------------------------------------------------------------------
 template <typename T, int M, int NS>
 static hipError_t run_scan_fwd(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
-                               const float *K0, const float *V0, float *S, float *KT, float *VT, hipStream_t st)
+                               const float *K0, const float *V0, float *S, float *KT, float *VT, float *SF,
+                               hipStream_t st)
 {
     auto kern = scan_fwd_kernel<T, M, NS>;
     const size_t lds = ScanLds<T, M, NS>::bytes;
     GSA_HIP_TRY(allow_lds(kern, lds));
     dim3 grid((pl.d_k + pl.d_v) / NS, pl.H, pl.n_seqs);
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)k, (const T *)v, g,
-                       K0, V0, S, KT, VT);
+    hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)k, (const T *)v, g,
+                       K0, V0, S, KT, VT, SF);
     return hipGetLastError();
 }
 
 template <typename T, int M>
 hipError_t launch_scan_fwd_tm(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
-                              const float *K0, const float *V0, float *S, float *KT, float *VT, hipStream_t st)
+                              const float *K0, const float *V0, float *S, float *KT, float *VT, float *SF,
+                              hipStream_t st)
 {
     // 128-column slices when both widths allow it and the grid still covers the chip
     const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
                       ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
-    if (wide) return run_scan_fwd<T, M, 128>(pl, cm, k, v, g, K0, V0, S, KT, VT, st);
-    return run_scan_fwd<T, M, 64>(pl, cm, k, v, g, K0, V0, S, KT, VT, st);
+    if (wide) return run_scan_fwd<T, M, 128>(pl, cm, k, v, g, K0, V0, S, KT, VT, SF, st);
+    return run_scan_fwd<T, M, 64>(pl, cm, k, v, g, K0, V0, S, KT, VT, SF, st);
 }
 
 template <typename T, int M>
@@ -455,12 +400,12 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
                                 float *VT, hipStream_t st)
 {
     const ChunkMap cm = make_chunk_map(pl, w);
-    GSA_HIP_TRY((launch_scan_fwd_tm<T, M>(pl, cm, k, v, g, K0, V0, w.S, KT, VT, st)));
+    GSA_HIP_TRY((launch_scan_fwd_tm<T, M>(pl, cm, k, v, g, K0, V0, w.S, KT, VT, nullptr, st)));
     auto kern = out_fwd_kernel<T, M>;
     const size_t lds = OutLds<T, M>::bytes;
     GSA_HIP_TRY(allow_lds(kern, lds));
     dim3 grid(pl.chunk_slots, pl.H);
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
+    hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
                        (const T *)k, (const T *)v, g, w.S, (T *)o, z_saved);
     return hipGetLastError();
 }
@@ -473,26 +418,25 @@ static hipError_t launch_fwd_t(const Plan &pl, const Work &w, const void *q, con
     switch (pl.m) {
     case 16: return launch_fwd_tm<T, 16>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     case 32: return launch_fwd_tm<T, 32>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
-    case 64: return launch_fwd_tm<T, 64>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
-    default: return launch_fwd_tm<T, 128>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    default: return launch_fwd_tm<T, 64>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     }
 }
 
 hipError_t launch_fwd(const Plan &pl, const Work &w, const void *q, const void *k, const void *v, const float *g,
                       const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT, hipStream_t st)
 {
-    if (pl.chunk_slots == 0 || pl.tokens == 0) return hipSuccess;
+    if (pl.tokens == 0) return hipSuccess;
     GSA_HIP_TRY(launch_prepare(pl, w, st));
     if (pl.dtype == 0) return launch_fwd_t<float>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     return launch_fwd_t<bf16_t>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
 }
 
-// explicit instantiations used by the backward translation unit (state recomputation)
+// explicit instantiations used by the backward translation unit (memory recomputation)
 #define GSA_INST_SCAN(T, M)                                                                                         \
     template hipError_t launch_scan_fwd_tm<T, M>(const Plan &, const ChunkMap &, const void *, const void *,         \
                                                  const float *, const float *, const float *, float *, float *,       \
-                                                 float *, hipStream_t);
-GSA_INST_SCAN(float, 16) GSA_INST_SCAN(float, 32) GSA_INST_SCAN(float, 64) GSA_INST_SCAN(float, 128)
-GSA_INST_SCAN(bf16_t, 16) GSA_INST_SCAN(bf16_t, 32) GSA_INST_SCAN(bf16_t, 64) GSA_INST_SCAN(bf16_t, 128)
+                                                 float *, float *, hipStream_t);
+GSA_INST_SCAN(float, 16) GSA_INST_SCAN(float, 32) GSA_INST_SCAN(float, 64)
+GSA_INST_SCAN(bf16_t, 16) GSA_INST_SCAN(bf16_t, 32) GSA_INST_SCAN(bf16_t, 64)
 
 }  // namespace gsa

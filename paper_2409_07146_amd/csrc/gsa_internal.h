@@ -13,9 +13,10 @@ struct Plan {
     const int32_t *cu_seqlens;  // device, or NULL
     int32_t n_seqs;             // sequences (B in batch form)
     int64_t tokens;             // B*T
+    int32_t chunk;              // tokens per chunk for this dtype
     int32_t chunk_slots;        // upper bound on chunks (exact in batch form)
     // workspace offsets in bytes (256-byte aligned); 0-sized parts share an offset
-    size_t off_table, off_seqtab, off_S, off_E, off_dz, off_dgf, total_fwd, total_bwd;
+    size_t off_table, off_seqtab, off_S, off_SF, off_E, off_dz, off_dgf, total_fwd, total_bwd;
 };
 
 // Workspace views handed to the launchers.
@@ -23,7 +24,8 @@ struct Work {
     int32_t *table;   // [4*chunk_slots] packed form only
     int32_t *seqtab;  // [4*n_seqs]     packed form only
     float *S;         // [chunk_slots][H][m][d_k+d_v] memories at the start of each chunk
-    float *E;         // same shape: gradient of the memories at the end of each chunk
+    float *SF;        // [n_seqs][H][m][d_k+d_v] memories after the last token (backward only)
+    float *E;         // same shape as S: gradient of the memories at the end of each chunk
     float *dz;        // [tokens][H][m]
     float *dgf;       // [tokens][H][m]
 };

@@ -12,7 +12,8 @@ inline ChunkMap make_chunk_map(const Plan &pl, const Work &w)
     cm.table = packed ? w.table : nullptr;
     cm.seq_tab = packed ? w.seqtab : nullptr;
     cm.T = pl.T;
-    cm.chunks_per_seq = (pl.T + kChunk - 1) / kChunk;
+    cm.chunk = pl.chunk;
+    cm.chunks_per_seq = (pl.T + pl.chunk - 1) / pl.chunk;
     cm.n_chunk_slots = pl.chunk_slots;
     return cm;
 }
