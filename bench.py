@@ -1,0 +1,166 @@
+"""Benchmark of the GSA hot path on one MI355X.
+
+A step is one forward + backward of the operator over the 1.3B-layer batch
+(B=8, T=2048, H=4, d_k=d_v=512, m=64, bf16, 16384 tokens), inputs resident in HBM.
+Prints ONE JSON line: throughput, the roofline of the dominant kernel (measured with
+HIP events inside the library on the launch stream), the decode step's bandwidth, and
+the fp64 CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def per_token_bytes(cfg, esz):
+    """Compulsory HBM bytes per token (all H heads) of forward and backward: every input read
+    once, every output written once; chunk memories and other workspace traffic not counted."""
+    H, dk, dv, m = cfg.H, cfg.d_k, cfg.d_v, cfg.m
+    fwd = H * ((2 * dk + dv) * esz + m * 4 + dv * esz + m * 4)             # q,k,v,g -> o,z
+    bwd = H * ((2 * dk + 2 * dv) * esz + 2 * m * 4 + (2 * dk + dv) * esz + m * 4)   # q,k,v,dO,g,z -> dq,dk,dv,dg
+    return fwd, bwd
+
+
+def per_token_head_flops(cfg, C=64):
+    """Executed matrix-core FLOPs per (token, head) at chunk size C, and the chunk-free
+    algorithmic count (recurrent form)."""
+    dk, dv, m = cfg.d_k, cfg.d_v, cfg.m
+    D = dk + dv
+    fwd = 2 * C * D + 4 * C * m + 4 * m * D
+    bwd = 5 * 2 * C * D + 12 * C * m + 10 * m * D   # recompute scan, dz, reverse scan, main kernel
+    alg_fwd, alg_bwd = 4 * m * D, 8 * m * D
+    return fwd, bwd, alg_fwd, alg_bwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="layer_1p3b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the operator has no cross-GPU path); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd import synth
+
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.workload]
+    x = synth.make_inputs(cfg)
+    put = lambda t: None if t is None else t.to(dev)
+    q, k, v, g, dO, cu = (put(x[n]) for n in ("q", "k", "v", "g", "dO", "cu_seqlens"))
+    prob = gsa.make_problem(q, v, g, 1.0, cu)
+    ws = gsa.alloc_workspace(prob, True, dev)
+
+    def step():
+        o, z, _, _ = gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws)
+        return gsa.gsa_bwd(q, k, v, g, z, dO, cu_seqlens=cu, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens = cfg.tokens
+    tok_s = tokens / (dt / args.steps)
+
+    # per-kernel durations, HIP events on the launch stream (second pass, same work)
+    gsa.gsa_profile_reset()
+    gsa.gsa_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = gsa.gsa_profile_read()
+    gsa.gsa_profile_enable(False)
+    kern_ms = {n: ms / max(cnt, 1) for n, (ms, cnt) in prof.items() if cnt}
+    esz = 2 if cfg.dtype == "bf16" else 4
+    fwd_b, bwd_b = per_token_bytes(cfg, esz)
+    alg_bytes = {"out_fwd_kernel": fwd_b * tokens, "bwd_main_kernel": bwd_b * tokens}
+    dom = max((n for n in kern_ms if n in alg_bytes), key=lambda n: kern_ms[n])
+    achieved = alg_bytes[dom] / (kern_ms[dom] * 1e-3) / 1e9
+    ffl, bfl, aff, abf = per_token_head_flops(cfg)
+    exec_flops = (ffl + bfl) * tokens * cfg.H
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(kern_ms[dom], 4),
+                "algorithmic_bytes_per_launch": alg_bytes[dom]}
+
+    # decode step: 512 steps at batch 64 (one state set, then rotating over 8 state sets)
+    dd = synth.DECODE
+    di = synth.make_decode_inputs(dd["B"], dd["H"], dd["d_k"], dd["d_v"], dd["m"], 4, state_std=dd["state_std"],
+                                  seed=dd["seed"])
+    nsets = 8
+    Ks = [di["K"].to(dev).clone() for _ in range(nsets)]
+    Vs = [di["V"].to(dev).clone() for _ in range(nsets)]
+    dq_, dk_, dv_, dg_ = (di[n].to(dev) for n in ("q", "k", "v", "g"))
+    od = torch.empty_like(dv_[0])
+    state_bytes = 2 * 4 * dd["B"] * dd["H"] * dd["m"] * (dd["d_k"] + dd["d_v"])
+    dec = {}
+    for label, sets in (("one_state_set", 1), ("rotating_8_state_sets", nsets)):
+        for i in range(20):
+            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.decode_steps):
+            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / args.decode_steps * 1e6
+        dec[label] = {"us_per_step": round(us, 2), "GB_per_s": round(state_bytes / us / 1e3, 1),
+                      "frac_hbm_peak": round(state_bytes / us / 1e3 / HBM_PEAK_GBS, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import build as obuild
+        obuild.build(force=False)
+        from oracle import gsa_oracle
+        f64 = lambda t: None if t is None else t.double().numpy()
+        cun = None if x["cu_seqlens"] is None else x["cu_seqlens"].numpy()
+        qn, kn, vn, gn, dn = (f64(x[n]) for n in ("q", "k", "v", "g", "dO"))
+        t0 = time.perf_counter()
+        gsa_oracle.fwd(qn, kn, vn, gn, cu_seqlens=cun)
+        gsa_oracle.bwd(qn, kn, vn, gn, dn, cu_seqlens=cun)
+        cdt = time.perf_counter() - t0
+        cpu = {"value": round(tokens / cdt, 1), "unit": "tokens/s", "cores": gsa_oracle.num_threads(),
+               "kind": "oracle", "sample": "the whole %s batch (%d tokens), fp64 forward + backward, one repetition, "
+               "%.1f s" % (cfg.name, tokens, cdt)}
+
+    out = {
+        "metric": "gsa_layer_fwd_bwd_tokens_per_s", "value": round(tok_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d T=%d H=%d d_k=%d d_v=%d m=%d fwd+bwd%s" % (
+            cfg.name, cfg.B, cfg.T, cfg.H, cfg.d_k, cfg.d_v, cfg.m,
+            "" if cfg.cu_seqlens is None else " packed %s" % (list(cfg.cu_seqlens),)),
+            "tokens_per_step": tokens, "chunk": 64},
+        "roofline": roofline,
+        "path": {"executed_tflops": round(exec_flops / (ms_per_step * 1e-3) / 1e12, 2),
+                 "frac_mfma_bf16_peak": round(exec_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                 "algorithmic_GB_per_s": round((fwd_b + bwd_b) * tokens / (ms_per_step * 1e-3) / 1e9, 1),
+                 "frac_hbm_peak": round((fwd_b + bwd_b) * tokens / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                 "kernel_ms": {n: round(ms, 4) for n, ms in kern_ms.items()}},
+        "decode": dec,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -25,8 +25,9 @@
  *     its memories in place, that is its contract).
  *   - Errors are return codes; arguments are validated on the host before any
  *     device work is enqueued, and a failed call enqueues nothing.
- *   - Supported shapes: m in {16, 32, 64, 128}; d_k and d_v multiples of 64, at most
- *     1024; H, B, T >= 1 (T = 0 is accepted and does nothing).
+ *   - Supported shapes: m in {16, 32, 64} (the decode step also takes 128); d_k and d_v
+ *     multiples of 64, at most 1024; H, B >= 1; T >= 0 (T = 0 does nothing).  Anything
+ *     else returns GSA_ERR_UNSUPPORTED.
  */
 #ifndef GSA_H
 #define GSA_H
@@ -126,6 +127,19 @@ gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32
                            int32_t dtype, float scale,
                            const void *q, const void *k, const void *v, const float *g,
                            float *K_state, float *V_state, void *o, void *stream);
+
+/*
+ * Per-kernel timing for roofline measurements (diagnostics; not part of the operator).
+ * While enabled, every kernel the library launches is bracketed by a pair of HIP events
+ * recorded on the caller's stream.  gsa_profile_read waits for the recorded events and
+ * returns, for kernel slot `index` (0 .. n-1; GSA_ERR_SHAPE past the end), its name, the
+ * milliseconds accumulated since the last reset and the number of launches.  The name
+ * points to static storage.  Enabling costs two event records per launch; timed
+ * throughput runs keep it off.
+ */
+gsa_status gsa_profile_enable(int on);
+gsa_status gsa_profile_reset(void);
+gsa_status gsa_profile_read(int32_t index, const char **name, double *ms, int64_t *launches);
 
 #ifdef __cplusplus
 }

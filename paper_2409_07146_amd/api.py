@@ -145,3 +145,25 @@ def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None):
     if rc != 0:
         raise GsaError(rc, "gsa_decode_step")
     return o
+
+
+def gsa_profile_enable(on: bool) -> None:
+    _lib.load().gsa_profile_enable(int(bool(on)))
+
+
+def gsa_profile_reset() -> None:
+    _lib.load().gsa_profile_reset()
+
+
+def gsa_profile_read():
+    """Returns {kernel name: (milliseconds, launches)} accumulated since the last reset."""
+    lib = _lib.load()
+    out = {}
+    i = 0
+    while True:
+        name, ms, n = ctypes.c_char_p(), ctypes.c_double(), ctypes.c_int64()
+        if lib.gsa_profile_read(i, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(n)) != 0:
+            break
+        out[name.value.decode()] = (ms.value, n.value)
+        i += 1
+    return out

@@ -641,6 +641,7 @@ static hipError_t run_scan_bwd(const Plan &pl, const ChunkMap &cm, const void *q
     const size_t lds = RScanLds<T, M, NS>::bytes;
     GSA_HIP_TRY(allow_lds(kern, lds));
     dim3 grid((pl.d_k + pl.d_v) / NS, pl.H, pl.n_seqs);
+    KernelTimer kt(kSlotScanBwd, st);
     hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
                        (const T *)dO, g, z, dz, dKT, dVT, E, dK0, dV0);
     return hipGetLastError();
@@ -661,6 +662,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         auto kern = bwd_dz_kernel<T, M>;
         const size_t lds = DzLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
+        KernelTimer kt(kSlotBwdDz, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)v,
                            (const T *)dO, g, z, w.S, w.dz, w.dgf);
         GSA_HIP_TRY(hipGetLastError());
@@ -677,6 +679,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         auto kern = bwd_main_kernel<T, M>;
         const size_t lds = MainLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
+        KernelTimer kt(kSlotBwdMain, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
                            (const T *)k, (const T *)v, (const T *)dO, g, z, w.dz, w.dgf, w.S, w.SF, w.E, (T *)dq,
                            (T *)dk, (T *)dv, dg);

@@ -178,6 +178,7 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    KernelTimer kt(kSlotDecode, st);
     hipLaunchKernelGGL(kern, dim3(BH), dim3(kDecThreads), lds, st, d_k, d_v, scale, (const T *)q, (const T *)k,
                        (const T *)v, g, K, V, (T *)o);
     return hipGetLastError();

@@ -67,6 +67,7 @@ __global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T
 hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
 {
     if (!pl.cu_seqlens) return hipSuccess;
+    KernelTimer kt(kSlotPrepare, st);
     hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(256), 0, st, pl.cu_seqlens, pl.n_seqs, pl.T, pl.chunk,
                        pl.chunk_slots, w.table, w.seqtab);
     return hipGetLastError();
@@ -377,6 +378,7 @@ static hipError_t run_scan_fwd(const Plan &pl, const ChunkMap &cm, const void *k
     const size_t lds = ScanLds<T, M, NS>::bytes;
     GSA_HIP_TRY(allow_lds(kern, lds));
     dim3 grid((pl.d_k + pl.d_v) / NS, pl.H, pl.n_seqs);
+    KernelTimer kt(kSlotScanFwd, st);
     hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)k, (const T *)v, g,
                        K0, V0, S, KT, VT, SF);
     return hipGetLastError();
@@ -405,6 +407,7 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
     const size_t lds = OutLds<T, M>::bytes;
     GSA_HIP_TRY(allow_lds(kern, lds));
     dim3 grid(pl.chunk_slots, pl.H);
+    KernelTimer kt(kSlotOutFwd, st);
     hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
                        (const T *)k, (const T *)v, g, w.S, (T *)o, z_saved);
     return hipGetLastError();

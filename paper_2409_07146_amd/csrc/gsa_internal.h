@@ -30,6 +30,23 @@ struct Work {
     float *dgf;       // [tokens][H][m]
 };
 
+// Kernel slots of the optional per-kernel event timing (gsa_profile_*).
+enum KernelSlot { kSlotPrepare = 0, kSlotScanFwd, kSlotOutFwd, kSlotBwdDz, kSlotScanBwd, kSlotBwdMain, kSlotDecode,
+                  kNumKernelSlots };
+
+// Brackets one kernel launch with events on its stream when timing is enabled; otherwise a no-op.
+class KernelTimer {
+public:
+    KernelTimer(int slot, hipStream_t st);
+    ~KernelTimer();
+    KernelTimer(const KernelTimer &) = delete;
+    KernelTimer &operator=(const KernelTimer &) = delete;
+private:
+    int slot_;
+    hipStream_t st_;
+    void *start_;
+};
+
 hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st);
 
 hipError_t launch_fwd(const Plan &pl, const Work &w, const void *q, const void *k, const void *v, const float *g,

@@ -1,0 +1,108 @@
+// Optional per-kernel timing with HIP events on the caller's stream (diagnostics for
+// roofline measurements).  Disabled by default: then a KernelTimer costs one relaxed load.
+#include "../../include/gsa.h"
+#include "gsa_internal.h"
+
+#include <atomic>
+#include <mutex>
+#include <utility>
+#include <vector>
+
+namespace gsa {
+
+namespace {
+std::atomic<int> g_enabled{0};
+std::mutex g_mu;
+struct Slot {
+    const char *name;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
+    std::vector<hipEvent_t> pool;
+    double ms = 0.0;
+    int64_t launches = 0;
+};
+Slot g_slots[kNumKernelSlots] = {{"prepare_kernel"}, {"scan_fwd_kernel"}, {"out_fwd_kernel"}, {"bwd_dz_kernel"},
+                                 {"scan_bwd_kernel"}, {"bwd_main_kernel"}, {"decode_kernel"}};
+
+hipEvent_t take_event(Slot &s)
+{
+    if (!s.pool.empty()) { hipEvent_t e = s.pool.back(); s.pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void drain(Slot &s)
+{
+    for (auto &pr : s.pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+            s.ms += ms;
+            s.launches += 1;
+        }
+        s.pool.push_back(pr.first);
+        s.pool.push_back(pr.second);
+    }
+    s.pending.clear();
+}
+}  // namespace
+
+KernelTimer::KernelTimer(int slot, hipStream_t st) : slot_(-1), st_(st), start_(nullptr)
+{
+    if (!g_enabled.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipEvent_t e = take_event(g_slots[slot]);
+    if (!e) return;
+    if (hipEventRecord(e, st) != hipSuccess) { g_slots[slot].pool.push_back(e); return; }
+    slot_ = slot;
+    start_ = e;
+}
+
+KernelTimer::~KernelTimer()
+{
+    if (slot_ < 0) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Slot &s = g_slots[slot_];
+    hipEvent_t e = take_event(s);
+    if (!e || hipEventRecord(e, st_) != hipSuccess) {
+        if (e) s.pool.push_back(e);
+        s.pool.push_back(static_cast<hipEvent_t>(start_));
+        return;
+    }
+    s.pending.emplace_back(static_cast<hipEvent_t>(start_), e);
+}
+
+}  // namespace gsa
+
+extern "C" {
+
+gsa_status gsa_profile_enable(int on)
+{
+    gsa::g_enabled.store(on ? 1 : 0, std::memory_order_relaxed);
+    return GSA_OK;
+}
+
+gsa_status gsa_profile_reset(void)
+{
+    std::lock_guard<std::mutex> lk(gsa::g_mu);
+    for (auto &s : gsa::g_slots) {
+        gsa::drain(s);
+        s.ms = 0.0;
+        s.launches = 0;
+    }
+    return GSA_OK;
+}
+
+gsa_status gsa_profile_read(int32_t index, const char **name, double *ms, int64_t *launches)
+{
+    if (index < 0 || index >= gsa::kNumKernelSlots) return GSA_ERR_SHAPE;
+    if (!name || !ms || !launches) return GSA_ERR_NULL;
+    std::lock_guard<std::mutex> lk(gsa::g_mu);
+    gsa::Slot &s = gsa::g_slots[index];
+    gsa::drain(s);
+    *name = s.name;
+    *ms = s.ms;
+    *launches = s.launches;
+    return GSA_OK;
+}
+
+}  // extern "C"
