@@ -41,14 +41,19 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
                                         : (int64_t)p->B * ((p->T + pl->chunk - 1) / pl->chunk);
     if (slots > 0x3fffffff) return GSA_ERR_SHAPE;
     pl->chunk_slots = (int32_t)slots;
-    const size_t state = (size_t)slots * p->H * p->m * (size_t)(p->d_k + p->d_v) * sizeof(float);
+    const size_t esz = p->dtype == GSA_BF16 ? 2 : 4;
+    const size_t state = (size_t)slots * p->H * p->m * (size_t)(p->d_k + p->d_v) * esz;
+    const size_t wts = (size_t)slots * p->H * p->m * (size_t)pl->chunk * esz;
     const size_t tokm = (size_t)tokens * p->H * p->m * sizeof(float);
     size_t off = 0;
     pl->off_table = off;  off += align_up(p->cu_seqlens ? (size_t)slots * 4 * sizeof(int32_t) : 0);
     pl->off_seqtab = off; off += align_up(p->cu_seqlens ? (size_t)p->n_seqs * 4 * sizeof(int32_t) : 0);
+    pl->off_Wf = off;     off += align_up(wts);
+    pl->off_dec = off;    off += align_up((size_t)slots * p->H * p->m * sizeof(float));
     pl->off_S = off;      off += align_up(state);
     pl->total_fwd = off;
-    pl->off_SF = off;     off += align_up((size_t)pl->n_seqs * p->H * p->m * (size_t)(p->d_k + p->d_v) * sizeof(float));
+    pl->off_SF = off;     off += align_up((size_t)pl->n_seqs * p->H * p->m * (size_t)(p->d_k + p->d_v) * esz);
+    pl->off_Wr = off;     off += align_up(2 * wts);
     pl->off_E = off;      off += align_up(state);
     pl->off_dz = off;     off += align_up(tokm);
     pl->off_dgf = off;    off += align_up(tokm);
@@ -62,9 +67,12 @@ Work make_work(const Plan &pl, void *ws)
     Work w;
     w.table = reinterpret_cast<int32_t *>(b + pl.off_table);
     w.seqtab = reinterpret_cast<int32_t *>(b + pl.off_seqtab);
-    w.S = reinterpret_cast<float *>(b + pl.off_S);
-    w.SF = reinterpret_cast<float *>(b + pl.off_SF);
-    w.E = reinterpret_cast<float *>(b + pl.off_E);
+    w.Wf = b + pl.off_Wf;
+    w.dec = reinterpret_cast<float *>(b + pl.off_dec);
+    w.S = b + pl.off_S;
+    w.SF = b + pl.off_SF;
+    w.Wr = b + pl.off_Wr;
+    w.E = b + pl.off_E;
     w.dz = reinterpret_cast<float *>(b + pl.off_dz);
     w.dgf = reinterpret_cast<float *>(b + pl.off_dgf);
     return w;

@@ -21,18 +21,13 @@
 // of the chunk-end memory with its gradient, which both scans already hold.  That keeps
 // rounding errors from accumulating along the sequence.
 //
-// Kernels: scan_fwd (recompute chunk-start memories; nothing but z was saved by the
-// forward), bwd_dz (chunk-parallel: dp, dz), scan_bwd (reverse scan over column slices:
-// E), bwd_main (chunk-parallel: everything else).
+// Kernels: gate + forward scan (gsa_scan.hip; recompute chunk-start memories, since nothing
+// but z was saved by the forward), bwd_dz (chunk-parallel: dp, dz, weights of the reverse
+// scan), reverse scan (gsa_scan.hip: E), bwd_main (chunk-parallel: everything else).
 #include "gsa_chunk.h"
 #include "gsa_launch.h"
 
 namespace gsa {
-
-template <typename T, int M>
-hipError_t launch_scan_fwd_tm(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
-                              const float *K0, const float *V0, float *S, float *KT, float *VT, float *SF,
-                              hipStream_t st);
 
 // ---------------------------------------------------------------------------------------
 // dz kernel
@@ -56,8 +51,9 @@ template <typename T, int M>
 __global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, int d_k, int d_v,
                                                             const T *__restrict__ v, const T *__restrict__ dO,
                                                             const float *__restrict__ g, const float *__restrict__ z,
-                                                            const float *__restrict__ S, float *__restrict__ dz,
-                                                            float *__restrict__ dgf)
+                                                            const T *__restrict__ S, float scale,
+                                                            float *__restrict__ dz, float *__restrict__ dgf,
+                                                            T *__restrict__ Wr)
 {
     using L = DzLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
@@ -78,7 +74,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, 
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const float *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;
+    const T *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;
     const int rowb = 16 * w;
 
     gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
@@ -111,133 +107,31 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, 
         for (int j = 0; j < 4; ++j) { p[ni][j] *= rsum[j]; pdp[j] += p[ni][j] * dp[ni][j]; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) pdp[j] = row16_sum(pdp[j]);
+    // dz, dgf for the main kernel; gate-weighted transposes (scale*dz*exp G, p*exp G) for the reverse scan
+    T *Wk = Wr + ((size_t)blockIdx.x * H + h) * 2 * M * C, *Wv = Wk + M * C;
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
+    for (int ni = 0; ni < MI; ++ni) {
+        const int i = ni * 16 + r;
+        T wk[4], wv[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
-            if (t >= ci.len) continue;
-            const float dzv = p[ni][j] * (dp[ni][j] - pdp[j]);
-            const size_t off = (tokh + (size_t)t * H) * M + ni * 16 + r;
-            dz[off] = dzv;
-            dgf[off] = zv[ni][j] * dzv + p[ni][j] * dp[ni][j];
-        }
-}
-
-// ---------------------------------------------------------------------------------------
-// Reverse scan of the memory gradient over column slices.
-// ---------------------------------------------------------------------------------------
-template <typename T, int M, int NS> struct RScanLds {
-    static constexpr int C = Geo<T>::C;
-    static constexpr int PAD = Atom<T>::kPad;
-    static constexpr int ldg = M + 4, ldw = C + PAD;
-    static constexpr size_t oG = 0;
-    static constexpr size_t oS = oG + sizeof(float) * C * ldg;
-    static constexpr size_t oP = oS + sizeof(float) * C * ldg;
-    static constexpr size_t oTot = oP + sizeof(float) * C * ldg;
-    static constexpr size_t oW = oTot + sizeof(float) * Geo<T>::NT;
-    static constexpr size_t oX = oW + sizeof(T) * M * ldw;
-    static constexpr size_t bytes = oX + sizeof(T) * NS * ldw;
-};
-
-template <typename T, int M, int NS>
-__global__ __launch_bounds__(Geo<T>::NT) void scan_bwd_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
-                                                              const T *__restrict__ q, const T *__restrict__ dO,
-                                                              const float *__restrict__ g, const float *__restrict__ z,
-                                                              const float *__restrict__ dz,
-                                                              const float *__restrict__ dKT,
-                                                              const float *__restrict__ dVT, float *__restrict__ E,
-                                                              float *__restrict__ dK0, float *__restrict__ dV0)
-{
-    using L = RScanLds<T, M, NS>;
-    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
-    constexpr int MI = M / 16, NI = NS / (16 * NW);
-    extern __shared__ __align__(16) unsigned char smem[];
-    float *Gs = reinterpret_cast<float *>(smem + L::oG);
-    float *Ss = reinterpret_cast<float *>(smem + L::oS);
-    float *Pf = reinterpret_cast<float *>(smem + L::oP);   // [C][ldg] p (value columns) or dz (key columns)
-    float *tot = reinterpret_cast<float *>(smem + L::oTot);
-    T *We = reinterpret_cast<T *>(smem + L::oW);           // [M][ldw]  We[i][t] = w_t[i] exp(G_t[i])
-    T *XT = reinterpret_cast<T *>(smem + L::oX);           // [NS][ldw] XT[c][t] = x_t[c]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 15, g4 = (lane >> 4) * 4;
-    const int h = blockIdx.y, s = blockIdx.z;
-    const int D = d_k + d_v;
-    const int col0 = blockIdx.x * NS;
-    const bool isK = col0 < d_k;
-    const T *src = isK ? q : dO;
-    const int dsrc = isK ? d_k : d_v;
-    const int c0 = isK ? col0 : col0 - d_k;
-    const float mult = isK ? scale : 1.f;
-
-    int chunk0, nch, tok0, ntok;
-    seq_lookup(cm, s, chunk0, nch, tok0, ntok);
-    const int wcol = wave * 16 * NI;
-    f32x4 acc[MI][NI];
-    {
-        const float *ET = isK ? dKT : dVT;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
-                    acc[mi][ni][j] = ET ? ET[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
-                }
-    }
-    for (int n = nch - 1; n >= 0; --n) {
-        const int t0 = tok0 + n * C;
-        const int len = min(C, ntok - n * C);
-        const size_t tokh = (size_t)t0 * H + h;
-        {
-            float *Ec = E + (((size_t)(chunk0 + n) * H + h) * M) * D + col0 + wcol;
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) Ec[(size_t)(mi * 16 + g4 + j) * D + ni * 16 + r] = acc[mi][ni][j];
-        }
-        gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, len, tid);
-        if (isK) {
-            const int t = tid >> 2, sub = tid & 3;
-#pragma unroll
-            for (int u = 0; u < M / 4; ++u)
-                Pf[t * L::ldg + sub + 4 * u] = (t < len) ? dz[(tokh + (size_t)t * H) * M + sub + 4 * u] : 0.f;
-        } else {
-            softmax_rows<M, C>(Pf, nullptr, L::ldg, z + tokh * M, nullptr, (size_t)H * M, len, tid);
-        }
-        __syncthreads();
-        for (int idx = tid; idx < M * C; idx += NT) {
-            const int i = idx % M, t = idx / M;
-            We[i * L::ldw + t] = from_f32<T>(mult * Pf[t * L::ldg + i] * __expf(Gs[t * L::ldg + i]));
-        }
-        stage_cols<T, T>(XT, L::ldw, src + tokh * dsrc + c0, (size_t)H * dsrc, C, NS, len, tid, NT);
-        __syncthreads();
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float dec = __expf(Gs[(C - 1) * L::ldg + mi * 16 + g4 + j]);
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dec;
+            const bool live = t < ci.len;
+            const float dzv = live ? p[ni][j] * (dp[ni][j] - pdp[j]) : 0.f;
+            const float eg = __expf(Gs[t * L::ldg + i]);
+            wk[j] = from_f32<T>(scale * dzv * eg);
+            wv[j] = from_f32<T>(live ? p[ni][j] * eg : 0.f);
+            if (live) {
+                const size_t off = (tokh + (size_t)t * H) * M + i;
+                dz[off] = dzv;
+                dgf[off] = zv[ni][j] * dzv + p[ni][j] * dp[ni][j];
             }
-        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, C, lane);
-        __syncthreads();
-    }
-    float *E0 = isK ? dK0 : dV0;
-    if (E0) {
+        }
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
-                    E0[(((size_t)s * H + h) * M + i) * dsrc + c] = acc[mi][ni][j];
-                }
+        for (int j = 0; j < 4; ++j) {
+            Wk[i * C + rowb + g4 + j] = wk[j];
+            Wv[i * C + rowb + g4 + j] = wv[j];
+        }
     }
 }
 
@@ -281,10 +175,10 @@ template <typename T, int M> struct MainLds {
     static constexpr size_t bytes = end1 > end2 ? end1 : end2;
 };
 
-// Stage E[M][KS] (fp32 rows, stride ld) into Es as T while accumulating the row-wise inner
-// product with Send (same layout) into part[]: thread handles rows (tid + NT*it) / (KS/8).
+// Stage E[M][KS] (rows of T, stride ld) into Es while accumulating the row-wise inner product
+// with Send (same layout) into part[]: thread handles rows (tid + NT*it) / (KS/8).
 template <typename T, int M, int KS, int NT, int ITS>
-__device__ __forceinline__ void stage_E_dot(T *Es, int ldq, const float *Eg, const float *Sendg, size_t ld,
+__device__ __forceinline__ void stage_E_dot(T *Es, int ldq, const T *Eg, const T *Sendg, size_t ld,
                                             float (&part)[ITS], int tid)
 {
     constexpr int vpr = KS / 8;
@@ -293,25 +187,25 @@ __device__ __forceinline__ void stage_E_dot(T *Es, int ldq, const float *Eg, con
         const int idx = tid + NT * it;
         if (idx < M * vpr) {
             const int i = idx / vpr, c = (idx - i * vpr) << 3;
-            Vec8<float> e, s;
+            Raw8<T> e, s;
             e.load(Eg + (size_t)i * ld + c);
             s.load(Sendg + (size_t)i * ld + c);
             float d = 0.f;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) d += e.v[u] * s.v[u];
+            for (int u = 0; u < 8; ++u) d += to_f32(e.get(u)) * to_f32(s.get(u));
             part[it] += d;
-            store8<T>(Es + i * ldq + c, e.v);
+            e.store(Es + i * ldq + c);
         }
     }
 }
 
 // One output pass of phase 3:  out = s_tok * (A_tok B_tok) + s_slot * (A_slot B_slot), written
 // to global rows.  A_tok [C][lda] contracts over the chunk's tokens with rows of `xtok`
-// ([len][ncols_total], element type T); A_slot [C][ldp] contracts over slots with fp32 rows of
-// `xslot` ([M][.], row stride ldslot).
+// ([len][ncols_total], element type T); A_slot [C][ldp] contracts over slots with rows of
+// `xslot` ([M][.] rows of T, row stride ldslot).
 template <typename T, int M>
 __device__ __forceinline__ void grad_pass(T *dst, size_t ld_dst, int dcols, const T *A_tok, const T *A_slot,
-                                          const T *xtok, size_t ld_tok, const float *xslot, size_t ld_slot,
+                                          const T *xtok, size_t ld_tok, const T *xslot, size_t ld_slot,
                                           float s_tok, float s_slot, T *Bt, T *Bs, T *Os, int len, int tid)
 {
     using L = MainLds<T, M>;
@@ -322,7 +216,7 @@ __device__ __forceinline__ void grad_pass(T *dst, size_t ld_dst, int dcols, cons
     for (int cs = 0; cs < dcols; cs += L::NS) {
         const int ncols = min(L::NS, dcols - cs);
         stage_cols<T, T>(Bt, L::lda, xtok + cs, ld_tok, C, ncols, len, tid, NT);
-        stage_cols<T, float>(Bs, L::ldp, xslot + cs, ld_slot, M, ncols, M, tid, NT);
+        stage_cols<T, T>(Bs, L::ldp, xslot + cs, ld_slot, M, ncols, M, tid, NT);
         if (M < L::KM) {
             for (int idx = tid; idx < ncols * (L::KM - M); idx += NT)
                 Bs[(idx / (L::KM - M)) * L::ldp + M + idx % (L::KM - M)] = from_f32<T>(0.f);
@@ -354,8 +248,8 @@ template <typename T, int M>
 __global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
     ChunkMap cm, int H, int d_k, int d_v, float scale, const T *__restrict__ q, const T *__restrict__ k,
     const T *__restrict__ v, const T *__restrict__ dO, const float *__restrict__ g, const float *__restrict__ z,
-    const float *__restrict__ dz, const float *__restrict__ dgf, const float *__restrict__ S,
-    const float *__restrict__ SF, const float *__restrict__ E, T *__restrict__ dq, T *__restrict__ dk,
+    const float *__restrict__ dz, const float *__restrict__ dgf, const T *__restrict__ S,
+    const T *__restrict__ SF, const T *__restrict__ E, T *__restrict__ dq, T *__restrict__ dk,
     T *__restrict__ dv, float *__restrict__ dg)
 {
     using L = MainLds<T, M>;
@@ -390,11 +284,11 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const float *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;       // memory at chunk start
-    const float *Ec = E + (((size_t)blockIdx.x * H + h) * M) * D;       // memory gradient at chunk end
+    const T *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;           // memory at chunk start
+    const T *Ec = E + (((size_t)blockIdx.x * H + h) * M) * D;           // memory gradient at chunk end
     int chunk0, nch, stok0, sntok;
     seq_lookup(cm, ci.seq, chunk0, nch, stok0, sntok);
-    const float *Send = (ci.idx + 1 < nch) ? Sc + (size_t)H * M * D     // next chunk's start memory
+    const T *Send = (ci.idx + 1 < nch) ? Sc + (size_t)H * M * D     // next chunk's start memory
                                            : SF + (((size_t)ci.seq * H + h) * M) * D;
     const int rowb = 16 * w;
 
@@ -632,21 +526,6 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
-template <typename T, int M, int NS>
-static hipError_t run_scan_bwd(const Plan &pl, const ChunkMap &cm, const void *q, const void *dO, const float *g,
-                               const float *z, const float *dz, const float *dKT, const float *dVT, float *E,
-                               float *dK0, float *dV0, hipStream_t st)
-{
-    auto kern = scan_bwd_kernel<T, M, NS>;
-    const size_t lds = RScanLds<T, M, NS>::bytes;
-    GSA_HIP_TRY(allow_lds(kern, lds));
-    dim3 grid((pl.d_k + pl.d_v) / NS, pl.H, pl.n_seqs);
-    KernelTimer kt(kSlotScanBwd, st);
-    hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
-                       (const T *)dO, g, z, dz, dKT, dVT, E, dK0, dV0);
-    return hipGetLastError();
-}
-
 template <typename T, int M>
 static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, const void *k, const void *v,
                                 const float *g, const float *K0, const float *V0, const float *z, const void *dO,
@@ -655,24 +534,26 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
 {
     const ChunkMap cm = make_chunk_map(pl, w);
     // 1. recompute the chunk-start memories (and the memories after the last token)
-    GSA_HIP_TRY((launch_scan_fwd_tm<T, M>(pl, cm, k, v, g, K0, V0, w.S, nullptr, nullptr, w.SF, st)));
+    GSA_HIP_TRY(launch_gates(pl, w, g, st));
+    {
+        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false};
+        GSA_HIP_TRY(launch_scan(pl, w, io, st));
+    }
     dim3 grid(pl.chunk_slots, pl.H);
-    // 2. dp, dz
+    // 2. dp, dz and the weights of the reverse scan
     {
         auto kern = bwd_dz_kernel<T, M>;
         const size_t lds = DzLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         KernelTimer kt(kSlotBwdDz, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)v,
-                           (const T *)dO, g, z, w.S, w.dz, w.dgf);
+                           (const T *)dO, g, z, (const T *)w.S, pl.scale, w.dz, w.dgf, (T *)w.Wr);
         GSA_HIP_TRY(hipGetLastError());
     }
     // 3. reverse scan of the memory gradient
     {
-        const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
-                          ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
-        if (wide) GSA_HIP_TRY((run_scan_bwd<T, M, 128>(pl, cm, q, dO, g, z, w.dz, dKT, dVT, w.E, dK0, dV0, st)));
-        else GSA_HIP_TRY((run_scan_bwd<T, M, 64>(pl, cm, q, dO, g, z, w.dz, dKT, dVT, w.E, dK0, dV0, st)));
+        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true};
+        GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     // 4. everything chunk-local
     {
@@ -681,7 +562,8 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         GSA_HIP_TRY(allow_lds(kern, lds));
         KernelTimer kt(kSlotBwdMain, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
-                           (const T *)k, (const T *)v, (const T *)dO, g, z, w.dz, w.dgf, w.S, w.SF, w.E, (T *)dq,
+                           (const T *)k, (const T *)v, (const T *)dO, g, z, w.dz, w.dgf, (const T *)w.S, (const T *)w.SF,
+                           (const T *)w.E, (T *)dq,
                            (T *)dk, (T *)dv, dg);
         GSA_HIP_TRY(hipGetLastError());
     }

@@ -44,13 +44,13 @@ __device__ __forceinline__ bool block_unsafe(const float *Gs, int ldg, int rowb,
 // i.e. the inter-chunk plus intra-chunk parts of one gated pass whose gate sits on the
 // slot side (pass 1 of Eq. (gsa-2pass) with X=q, Y=k, St=Kt; its mirror in the backward
 // with X=dO, Y=v, St=Vt).  X, Y: [len][d] rows in global memory (row stride ldx elements);
-// St: [M][d] fp32 rows (stride ldst).  LDS: Gs, Ss filled by gate_prep; As [C][lda] is
+// St: [M][d] rows of T (stride ldst).  LDS: Gs, Ss filled by gate_prep; As [C][lda] is
 // left holding the causally masked X Y^T rounded to T; Xs, Ys [C][ldq] and Sts [M][ldq]
 // are staging for d-slices of KS columns.  All threads of the workgroup must call it.
 template <typename T, int M, int C, int KS>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, const float *Gs, const float *Ss,
                                              int ldg, T *As, int lda, T *Xs, T *Ys, T *Sts, int ldq, const T *X,
-                                             const T *Y, size_t ldx, int d, const float *St, size_t ldst, int len,
+                                             const T *Y, size_t ldx, int d, const T *St, size_t ldst, int len,
                                              int tid)
 {
     constexpr int MI = M / 16, CI = C / 16, NT = Geo<T>::NT;
@@ -66,7 +66,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
     for (int ks = 0; ks < d; ks += KS) {
         stage_rows<T, T>(Xs, ldq, X + ks, ldx, C, KS, len, tid, NT);
         stage_rows<T, T>(Ys, ldq, Y + ks, ldx, C, KS, len, tid, NT);
-        stage_rows<T, float>(Sts, ldq, St + ks, ldst, M, KS, M, tid, NT);
+        stage_rows<T, T>(Sts, ldq, St + ks, ldst, M, KS, M, tid, NT);
         __syncthreads();
 #pragma unroll
         for (int k0 = 0; k0 < KS; k0 += 32) {

@@ -139,6 +139,32 @@ template <> __device__ __forceinline__ void store8<float>(float *dst, const floa
     *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{v[4], v[5], v[6], v[7]};
 }
 
+// Eight elements held as loaded (no conversion): the unit of register prefetching.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    bf16x8 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const bf16x8 *>(p); }
+    __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<bf16x8 *>(p) = v; }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.f;
+    }
+    __device__ __forceinline__ bf16_t get(int e) const { return v[e]; }
+};
+template <> struct Raw8<float> {
+    f32x4 lo, hi;
+    __device__ __forceinline__ void load(const float *p) {
+        lo = *reinterpret_cast<const f32x4 *>(p);
+        hi = *reinterpret_cast<const f32x4 *>(p + 4);
+    }
+    __device__ __forceinline__ void store(float *p) const {
+        *reinterpret_cast<f32x4 *>(p) = lo;
+        *reinterpret_cast<f32x4 *>(p + 4) = hi;
+    }
+    __device__ __forceinline__ void zero() { lo = f32x4{0.f, 0.f, 0.f, 0.f}; hi = lo; }
+    __device__ __forceinline__ float get(int e) const { return e < 4 ? lo[e] : hi[e - 4]; }
+};
+
 // dst[r][c] = src[r][c]   (dst row stride ld)
 template <typename T, typename Tin>
 __device__ __forceinline__ void stage_rows(T *dst, int ld, const Tin *src, size_t gld, int rows, int cols,

@@ -5,10 +5,10 @@
 // intensity, so they are carried as ONE memory S = [Kt | Vt] of shape
 // [m x (d_k+d_v)]:
 //
-//   scan_fwd_kernel   one workgroup per (sequence, head, column slice of S) walks the
-//                     chunks in order, keeps its slice of S in matrix-core accumulators
-//                     and writes the memory at the START of every chunk to the workspace
-//                     (the only sequential part; column slices are independent).
+//   gate_kernel +     (gsa_scan.hip) one workgroup per (sequence, head, column slice of S)
+//   scan_kernel       walks the chunks in order, keeps its slice of S in matrix-core
+//                     accumulators and writes the memory at the START of every chunk to the
+//                     workspace (the only sequential part; column slices are independent).
 //   out_fwd_kernel    one workgroup per (chunk, head): pass-1 scores z (inter-chunk term
 //                     from the stored memory + gated intra-chunk term), softmax over the
 //                     slots in registers, pass-2 output o.  z and p never round-trip HBM
@@ -74,116 +74,6 @@ hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------------
-// Memory scan (Eq. (gla-chunk-gate) applied to S = [Kt | Vt]):
-//     S_n = Diag(exp G_C) S_{n-1} + (s * exp(G_C - G))^T [k | v]
-// ---------------------------------------------------------------------------------------
-template <typename T, int M, int NS> struct ScanLds {
-    static constexpr int C = Geo<T>::C;
-    static constexpr int PAD = Atom<T>::kPad;
-    static constexpr int ldg = M + 4;
-    static constexpr int ldw = C + PAD;
-    static constexpr size_t oG = 0;
-    static constexpr size_t oS = oG + sizeof(float) * C * ldg;
-    static constexpr size_t oTot = oS + sizeof(float) * C * ldg;
-    static constexpr size_t oW = oTot + sizeof(float) * Geo<T>::NT;
-    static constexpr size_t oX = oW + sizeof(T) * M * ldw;
-    static constexpr size_t bytes = oX + sizeof(T) * NS * ldw;
-};
-
-template <typename T, int M, int NS>
-__global__ __launch_bounds__(Geo<T>::NT) void scan_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v,
-                                                              const T *__restrict__ k, const T *__restrict__ v,
-                                                              const float *__restrict__ g,
-                                                              const float *__restrict__ K0,
-                                                              const float *__restrict__ V0, float *__restrict__ S,
-                                                              float *__restrict__ KT, float *__restrict__ VT,
-                                                              float *__restrict__ SF)
-{
-    using L = ScanLds<T, M, NS>;
-    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
-    constexpr int MI = M / 16, NI = NS / (16 * NW);
-    extern __shared__ __align__(16) unsigned char smem[];
-    float *Gs = reinterpret_cast<float *>(smem + L::oG);
-    float *Ss = reinterpret_cast<float *>(smem + L::oS);
-    float *tot = reinterpret_cast<float *>(smem + L::oTot);
-    T *We = reinterpret_cast<T *>(smem + L::oW);   // [M][ldw]  We[i][t] = s_t[i] exp(G_C[i] - G_t[i])
-    T *XT = reinterpret_cast<T *>(smem + L::oX);   // [NS][ldw] XT[c][t] = x_t[c]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 15, g4 = (lane >> 4) * 4;
-    const int h = blockIdx.y, s = blockIdx.z;
-    const int D = d_k + d_v;
-    const int col0 = blockIdx.x * NS;          // column of S this workgroup starts at
-    const bool isK = col0 < d_k;
-    const T *src = isK ? k : v;
-    const int dsrc = isK ? d_k : d_v;
-    const int c0 = isK ? col0 : col0 - d_k;    // column inside k or v
-
-    int chunk0, nch, tok0, ntok;
-    seq_lookup(cm, s, chunk0, nch, tok0, ntok);
-
-    // this wave owns columns [wcol, wcol + 16*NI) of the slice, all M rows
-    const int wcol = wave * 16 * NI;
-    f32x4 acc[MI][NI];
-    {
-        const float *S0 = isK ? K0 : V0;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
-                    acc[mi][ni][j] = S0 ? S0[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
-                }
-    }
-    for (int n = 0; n < nch; ++n) {
-        const int t0 = tok0 + n * C;
-        const int len = min(C, ntok - n * C);
-        // memory at the start of this chunk
-        {
-            float *Sc = S + (((size_t)(chunk0 + n) * H + h) * M) * D + col0 + wcol;
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) Sc[(size_t)(mi * 16 + g4 + j) * D + ni * 16 + r] = acc[mi][ni][j];
-        }
-        gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + ((size_t)t0 * H + h) * M, (size_t)H * M, len, tid);
-        for (int idx = tid; idx < M * C; idx += NT) {
-            const int i = idx % M, t = idx / M;
-            const float w = Ss[t * L::ldg + i] * __expf(Gs[(C - 1) * L::ldg + i] - Gs[t * L::ldg + i]);
-            We[i * L::ldw + t] = from_f32<T>(w);
-        }
-        stage_cols<T, T>(XT, L::ldw, src + ((size_t)t0 * H + h) * dsrc + c0, (size_t)H * dsrc, C, NS, len, tid, NT);
-        __syncthreads();
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float dec = __expf(Gs[(C - 1) * L::ldg + mi * 16 + g4 + j]);
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dec;
-            }
-        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, C, lane);
-        __syncthreads();
-    }
-    // memories after the last token: the caller's output and/or the joint copy the backward uses
-    float *ST = isK ? KT : VT;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = mi * 16 + g4 + j, c = wcol + ni * 16 + r;
-                if (ST) ST[(((size_t)s * H + h) * M + i) * dsrc + c0 + c] = acc[mi][ni][j];
-                if (SF) SF[(((size_t)s * H + h) * M + i) * D + col0 + c] = acc[mi][ni][j];
-            }
-}
-
-// ---------------------------------------------------------------------------------------
 // Chunk-parallel output kernel.
 // ---------------------------------------------------------------------------------------
 template <typename T, int M> struct OutLds {
@@ -224,7 +114,7 @@ template <typename T, int M>
 __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
                                                              const T *__restrict__ q, const T *__restrict__ k,
                                                              const T *__restrict__ v, const float *__restrict__ g,
-                                                             const float *__restrict__ S, T *__restrict__ o,
+                                                             const T *__restrict__ S, T *__restrict__ o,
                                                              float *__restrict__ z_saved)
 {
     using L = OutLds<T, M>;
@@ -252,7 +142,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const float *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;   // memory at chunk start [M][D]
+    const T *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;       // memory at chunk start [M][D]
     const int rowb = 16 * w;                                        // this wave's row block
 
     gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
@@ -339,7 +229,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
     // ---- o = [p exp(G) | A2] [Vt ; V], streamed over d_v (Eq. (gla-chunk) with the gate on the slot/key side)
     for (int cs = 0; cs < d_v; cs += L::NS) {
         const int ncols = min(L::NS, d_v - cs);
-        stage_cols<T, float>(SvT, L::ldp, Sc + d_k + cs, (size_t)D, M, ncols, M, tid, NT);
+        stage_cols<T, T>(SvT, L::ldp, Sc + d_k + cs, (size_t)D, M, ncols, M, tid, NT);
         if (M < L::KM) {
             for (int idx = tid; idx < ncols * (L::KM - M); idx += NT)
                 SvT[(idx / (L::KM - M)) * L::ldp + M + idx % (L::KM - M)] = from_f32<T>(0.f);
@@ -369,47 +259,22 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
-template <typename T, int M, int NS>
-static hipError_t run_scan_fwd(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
-                               const float *K0, const float *V0, float *S, float *KT, float *VT, float *SF,
-                               hipStream_t st)
-{
-    auto kern = scan_fwd_kernel<T, M, NS>;
-    const size_t lds = ScanLds<T, M, NS>::bytes;
-    GSA_HIP_TRY(allow_lds(kern, lds));
-    dim3 grid((pl.d_k + pl.d_v) / NS, pl.H, pl.n_seqs);
-    KernelTimer kt(kSlotScanFwd, st);
-    hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)k, (const T *)v, g,
-                       K0, V0, S, KT, VT, SF);
-    return hipGetLastError();
-}
-
-template <typename T, int M>
-hipError_t launch_scan_fwd_tm(const Plan &pl, const ChunkMap &cm, const void *k, const void *v, const float *g,
-                              const float *K0, const float *V0, float *S, float *KT, float *VT, float *SF,
-                              hipStream_t st)
-{
-    // 128-column slices when both widths allow it and the grid still covers the chip
-    const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
-                      ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
-    if (wide) return run_scan_fwd<T, M, 128>(pl, cm, k, v, g, K0, V0, S, KT, VT, SF, st);
-    return run_scan_fwd<T, M, 64>(pl, cm, k, v, g, K0, V0, S, KT, VT, SF, st);
-}
-
 template <typename T, int M>
 static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, const void *k, const void *v,
                                 const float *g, const float *K0, const float *V0, void *o, float *z_saved, float *KT,
                                 float *VT, hipStream_t st)
 {
     const ChunkMap cm = make_chunk_map(pl, w);
-    GSA_HIP_TRY((launch_scan_fwd_tm<T, M>(pl, cm, k, v, g, K0, V0, w.S, KT, VT, nullptr, st)));
+    GSA_HIP_TRY(launch_gates(pl, w, g, st));
+    const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false};
+    GSA_HIP_TRY(launch_scan(pl, w, io, st));
     auto kern = out_fwd_kernel<T, M>;
     const size_t lds = OutLds<T, M>::bytes;
     GSA_HIP_TRY(allow_lds(kern, lds));
     dim3 grid(pl.chunk_slots, pl.H);
     KernelTimer kt(kSlotOutFwd, st);
     hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
-                       (const T *)k, (const T *)v, g, w.S, (T *)o, z_saved);
+                       (const T *)k, (const T *)v, g, (const T *)w.S, (T *)o, z_saved);
     return hipGetLastError();
 }
 
@@ -433,13 +298,5 @@ hipError_t launch_fwd(const Plan &pl, const Work &w, const void *q, const void *
     if (pl.dtype == 0) return launch_fwd_t<float>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     return launch_fwd_t<bf16_t>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
 }
-
-// explicit instantiations used by the backward translation unit (memory recomputation)
-#define GSA_INST_SCAN(T, M)                                                                                         \
-    template hipError_t launch_scan_fwd_tm<T, M>(const Plan &, const ChunkMap &, const void *, const void *,         \
-                                                 const float *, const float *, const float *, float *, float *,       \
-                                                 float *, float *, hipStream_t);
-GSA_INST_SCAN(float, 16) GSA_INST_SCAN(float, 32) GSA_INST_SCAN(float, 64)
-GSA_INST_SCAN(bf16_t, 16) GSA_INST_SCAN(bf16_t, 32) GSA_INST_SCAN(bf16_t, 64)
 
 }  // namespace gsa

@@ -1,0 +1,307 @@
+// The sequential part of Gated Slot Attention: carrying the joint slot memory S = [Kt | Vt]
+// (forward) and its gradient E (backward) across chunks (paper, Appendix A,
+// Eq. (gla-chunk-gate); Algorithm 1, the two "for n" loops).
+//
+// Both recurrences have the same shape,
+//     acc <- Diag(dec_n) acc + W_n X_n          W_n [m x C] gate-weighted, X_n [C x columns]
+// with a snapshot of acc taken BEFORE the update of chunk n.  Forward: W = s*exp(G_C-G),
+// X = [k | v], snapshots = memory at chunk start.  Reverse: W = scale*dz*exp(G) (key
+// columns) or p*exp(G) (value columns), X = [q | dO], snapshots = memory gradient at chunk
+// end.  Nothing in W depends on acc, so the weights are produced by chunk-parallel kernels
+// (gate_kernel here, bwd_dz_kernel for the reverse scan) and the sequential loop only
+// copies tiles, multiplies and stores:
+//
+//   * one workgroup per (sequence, head, column slice); the slice of acc lives in MFMA
+//     accumulators for the whole sequence;
+//   * the tiles of chunk n+1 are prefetched into registers while chunk n is multiplied;
+//   * snapshots leave through an LDS tile so that global stores are full rows;
+//   * workgroups that share (sequence, head) — and therefore W and dec — are mapped to
+//     the same XCD so those re-reads hit its L2.
+#include "gsa_chunk.h"
+#include "gsa_launch.h"
+
+namespace gsa {
+
+// ---------------------------------------------------------------------------------------
+// Gate weights of the forward scan (chunk-parallel).
+// ---------------------------------------------------------------------------------------
+template <typename T, int M>
+__global__ __launch_bounds__(Geo<T>::NT) void gate_kernel(ChunkMap cm, int H, const float *__restrict__ g,
+                                                          T *__restrict__ Wf, float *__restrict__ dec)
+{
+    constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
+    constexpr int ldg = M + 4;
+    __shared__ float Gs[C * ldg];
+    __shared__ float Ss[C * ldg];
+    __shared__ float tot[NT];
+    ChunkInfo ci;
+    if (!chunk_lookup(cm, blockIdx.x, ci)) return;
+    const int h = blockIdx.y, tid = threadIdx.x;
+    const size_t ch = (size_t)blockIdx.x * H + h;
+    gate_prep<M, NT, C>(Gs, Ss, ldg, tot, g + ((size_t)ci.tok0 * H + h) * M, (size_t)H * M, ci.len, tid);
+    T *W = Wf + ch * M * C;
+    for (int idx = tid; idx < M * C; idx += NT) {
+        const int i = idx / C, t = idx - i * C;
+        W[idx] = from_f32<T>(Ss[t * ldg + i] * __expf(Gs[(C - 1) * ldg + i] - Gs[t * ldg + i]));
+    }
+    if (tid < M) dec[ch * M + tid] = __expf(Gs[(C - 1) * ldg + tid]);
+}
+
+// ---------------------------------------------------------------------------------------
+// The scan.
+// ---------------------------------------------------------------------------------------
+template <typename T> struct ScanArgs {
+    const T *W;            // [chunk][H][parts][M][C]
+    int w_parts;           // 1 (forward) or 2 (reverse: key part, value part)
+    const float *dec;      // [chunk][H][M]
+    const T *xk, *xv;      // token tensors feeding the key / value columns
+    const float *initK, *initV;   // [n_seqs][H][M][d] or NULL
+    T *snap;               // [chunk][H][M][D]
+    float *outK, *outV;    // [n_seqs][H][M][d] or NULL: acc after the last chunk
+    T *outJ;               // [n_seqs][H][M][D] or NULL: the same, joint layout, element type T
+};
+
+template <typename T, int M, int NS> struct ScanLds {
+    static constexpr int C = Geo<T>::C;
+    static constexpr int PAD = Atom<T>::kPad;
+    static constexpr int ldw = C + PAD;      // We [M][ldw], XT [NS][ldw]
+    static constexpr int lds = NS + PAD;     // snapshot tile [M][lds]
+    static constexpr size_t oW = 0;
+    static constexpr size_t oX = oW + sizeof(T) * M * ldw;
+    static constexpr size_t oSn = oX + sizeof(T) * NS * ldw;
+    static constexpr size_t bytes = oSn + sizeof(T) * M * lds;
+};
+
+template <typename T, int M, int NS, bool REVERSE>
+__global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, int d_k, int d_v, int n_seqs,
+                                                          ScanArgs<T> a)
+{
+    using L = ScanLds<T, M, NS>;
+    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
+    constexpr int MI = M / 16, NI = NS / (16 * NW);
+    constexpr int WVEC = M * C / 8, XVEC = C * NS / 8, SVEC = M * NS / 8;
+    constexpr int WV = (WVEC + NT - 1) / NT, XV = (XVEC + NT - 1) / NT, SV = (SVEC + NT - 1) / NT;
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *We = reinterpret_cast<T *>(smem + L::oW);
+    T *XT = reinterpret_cast<T *>(smem + L::oX);
+    T *Sn = reinterpret_cast<T *>(smem + L::oSn);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g4 = (lane >> 4) * 4;
+    const int D = d_k + d_v;
+    const int nsl = D / NS;
+    // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs; give each
+    // XCD a contiguous range of logical ids so that the slices of one (sequence, head) share an L2
+    int total = nsl * H * n_seqs, bid = blockIdx.x;
+    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
+    const int slice = bid % nsl, sh = bid / nsl;
+    const int h = sh % H, s = sh / H;
+    const int col0 = slice * NS;
+    const bool isK = col0 < d_k;
+    const T *src = isK ? a.xk : a.xv;
+    const int dsrc = isK ? d_k : d_v;
+    const int c0 = isK ? col0 : col0 - d_k;
+    const size_t wpart = (a.w_parts == 2 && !isK) ? (size_t)M * C : 0;
+
+    int chunk0, nch, tok0, ntok;
+    seq_lookup(cm, s, chunk0, nch, tok0, ntok);
+    const int wcol = wave * 16 * NI;
+
+    f32x4 acc[MI][NI];
+    {
+        const float *S0 = isK ? a.initK : a.initV;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
+                    acc[mi][ni][j] = S0 ? S0[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
+                }
+    }
+
+    Raw8<T> wreg[WV], xreg[XV];
+    float decr[MI][4];
+    auto fetch = [&](int n) {
+        const size_t ch = (size_t)(chunk0 + n) * H + h;
+        const T *Wg = a.W + ch * a.w_parts * M * C + wpart;
+#pragma unroll
+        for (int u = 0; u < WV; ++u) {
+            const int idx = tid + NT * u;
+            if (idx < WVEC) wreg[u].load(Wg + (size_t)idx * 8);
+        }
+        const int len = min(C, ntok - n * C);
+        const T *Xg = src + ((size_t)(tok0 + n * C) * H + h) * dsrc + c0;
+#pragma unroll
+        for (int u = 0; u < XV; ++u) {
+            const int idx = tid + NT * u;
+            const int row = idx / (NS / 8), cg = idx - row * (NS / 8);
+            if (idx < XVEC && row < len) xreg[u].load(Xg + (size_t)row * H * dsrc + cg * 8);
+            else xreg[u].zero();
+        }
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) decr[mi][j] = a.dec[ch * M + mi * 16 + g4 + j];
+    };
+    auto snapshot_to_lds = [&]() {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+    };
+    auto snapshot_to_global = [&](T *dst) {   // dst: [M][D] rows, this slice starts at column col0
+#pragma unroll
+        for (int u = 0; u < SV; ++u) {
+            const int idx = tid + NT * u;
+            if (idx < SVEC) {
+                const int i = idx / (NS / 8), cg = idx - i * (NS / 8);
+                Raw8<T> x;
+                x.load(Sn + i * L::lds + cg * 8);
+                x.store(dst + (size_t)i * D + col0 + cg * 8);
+            }
+        }
+    };
+
+    if (nch > 0) fetch(REVERSE ? nch - 1 : 0);
+    for (int it = 0; it < nch; ++it) {
+        const int n = REVERSE ? nch - 1 - it : it;
+        // staged registers -> LDS (W as is, X transposed), accumulator snapshot -> LDS
+#pragma unroll
+        for (int u = 0; u < WV; ++u) {
+            const int idx = tid + NT * u;
+            if (idx < WVEC) {
+                const int i = idx / (C / 8), tg = idx - i * (C / 8);
+                wreg[u].store(We + i * L::ldw + tg * 8);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < XV; ++u) {
+            const int idx = tid + NT * u;
+            if (idx < XVEC) {
+                const int row = idx / (NS / 8), cg = idx - row * (NS / 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) XT[(cg * 8 + e) * L::ldw + row] = xreg[u].get(e);
+            }
+        }
+        snapshot_to_lds();
+        float dcur[MI][4];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dcur[mi][j] = decr[mi][j];
+        __syncthreads();
+        if (it + 1 < nch) fetch(REVERSE ? n - 1 : n + 1);
+        snapshot_to_global(a.snap + (((size_t)(chunk0 + n) * H + h) * M) * D);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dcur[mi][j];
+        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, C, lane);
+        __syncthreads();
+    }
+    // accumulator after the last chunk
+    float *ST = isK ? a.outK : a.outV;
+    if (ST) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
+                    ST[(((size_t)s * H + h) * M + i) * dsrc + c] = acc[mi][ni][j];
+                }
+    }
+    if (a.outJ) {
+        snapshot_to_lds();
+        __syncthreads();
+        snapshot_to_global(a.outJ + (((size_t)s * H + h) * M) * D);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------
+template <typename T, int M>
+static hipError_t launch_gates_tm(const Plan &pl, const Work &w, const float *g, hipStream_t st)
+{
+    const ChunkMap cm = make_chunk_map(pl, w);
+    KernelTimer kt(kSlotGates, st);
+    hipLaunchKernelGGL((gate_kernel<T, M>), dim3(pl.chunk_slots, pl.H), dim3(Geo<T>::NT), 0, st, cm, pl.H, g,
+                       (T *)w.Wf, w.dec);
+    return hipGetLastError();
+}
+
+hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, hipStream_t st)
+{
+#define GSA_GATES(T)                                                   \
+    switch (pl.m) {                                                    \
+    case 16: return launch_gates_tm<T, 16>(pl, w, g, st);              \
+    case 32: return launch_gates_tm<T, 32>(pl, w, g, st);              \
+    default: return launch_gates_tm<T, 64>(pl, w, g, st);              \
+    }
+    if (pl.dtype == 0) { GSA_GATES(float) }
+    GSA_GATES(bf16_t)
+#undef GSA_GATES
+}
+
+template <typename T, int M, int NS, bool REVERSE>
+static hipError_t run_scan(const Plan &pl, const ChunkMap &cm, const ScanArgs<T> &a, hipStream_t st)
+{
+    auto kern = scan_kernel<T, M, NS, REVERSE>;
+    const size_t lds = ScanLds<T, M, NS>::bytes;
+    GSA_HIP_TRY(allow_lds(kern, lds));
+    const int total = (pl.d_k + pl.d_v) / NS * pl.H * pl.n_seqs;
+    KernelTimer kt(REVERSE ? kSlotScanBwd : kSlotScanFwd, st);
+    hipLaunchKernelGGL(kern, dim3(total), dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.n_seqs, a);
+    return hipGetLastError();
+}
+
+template <typename T, int M>
+static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io, hipStream_t st)
+{
+    const ChunkMap cm = make_chunk_map(pl, w);
+    ScanArgs<T> a;
+    a.W = static_cast<const T *>(io.reverse ? w.Wr : w.Wf);
+    a.w_parts = io.reverse ? 2 : 1;
+    a.dec = w.dec;
+    a.xk = static_cast<const T *>(io.xk);
+    a.xv = static_cast<const T *>(io.xv);
+    a.initK = io.initK;
+    a.initV = io.initV;
+    a.snap = static_cast<T *>(io.reverse ? w.E : w.S);
+    a.outK = io.outK;
+    a.outV = io.outV;
+    a.outJ = static_cast<T *>(io.outJ);
+    // 128-column slices when both widths allow it and the grid still covers the chip
+    const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
+                      ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
+    if (io.reverse) {
+        if (wide) return run_scan<T, M, 128, true>(pl, cm, a, st);
+        return run_scan<T, M, 64, true>(pl, cm, a, st);
+    }
+    if (wide) return run_scan<T, M, 128, false>(pl, cm, a, st);
+    return run_scan<T, M, 64, false>(pl, cm, a, st);
+}
+
+hipError_t launch_scan(const Plan &pl, const Work &w, const ScanIo &io, hipStream_t st)
+{
+#define GSA_SCAN(T)                                                   \
+    switch (pl.m) {                                                   \
+    case 16: return launch_scan_tm<T, 16>(pl, w, io, st);             \
+    case 32: return launch_scan_tm<T, 32>(pl, w, io, st);             \
+    default: return launch_scan_tm<T, 64>(pl, w, io, st);             \
+    }
+    if (pl.dtype == 0) { GSA_SCAN(float) }
+    GSA_SCAN(bf16_t)
+#undef GSA_SCAN
+}
+
+}  // namespace gsa
