@@ -81,7 +81,7 @@ template <typename T, int M> struct OutLds {
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int KM = (M < 32) ? 32 : M;                // slots padded to the contraction depth
     static constexpr int KS = (sizeof(T) == 2) ? 64 : 32;       // d_k slice streamed per step
-    static constexpr int NS = (sizeof(T) == 2) ? 128 : 64;      // d_v slice per output step
+    static constexpr int NS = 64;                               // d_v slice per output step
     static constexpr int ldg = M + 4;
     static constexpr int lda = C + PAD;        // As, VT
     static constexpr int ldp = KM + PAD;       // Ps, SvT
@@ -89,10 +89,11 @@ template <typename T, int M> struct OutLds {
     static constexpr int ldo = NS + PAD;       // Os
     static constexpr size_t oG = 0;
     static constexpr size_t oS = oG + sizeof(float) * C * ldg;
-    static constexpr size_t oTot = oS + sizeof(float) * C * ldg;
-    static constexpr size_t oA = oTot + sizeof(float) * Geo<T>::NT;
+    static constexpr size_t oA = oS + sizeof(float) * C * ldg;
     static constexpr size_t oP = oA + sizeof(T) * C * lda;
     static constexpr size_t oU = oP + sizeof(T) * C * ldp;
+    // gate_prep's scratch (dead before the first staging write)
+    static constexpr size_t oTot = oU;
     // phase 1 view of the union
     static constexpr size_t oQ = oU;
     static constexpr size_t oK = oQ + sizeof(T) * C * ldq;
