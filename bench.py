@@ -93,7 +93,19 @@ def main():
     kern_ms = {n: ms / max(cnt, 1) for n, (ms, cnt) in prof.items() if cnt}
     esz = 2 if cfg.dtype == "bf16" else 4
     fwd_b, bwd_b = per_token_bytes(cfg, esz)
-    alg_bytes = {"out_fwd_kernel": fwd_b * tokens, "bwd_main_kernel": bwd_b * tokens}
+    # algorithmic bytes of each kernel per launch: the API tensors it must read or write once
+    # (workspace traffic -- chunk memories, small per-chunk matrices -- is not counted)
+    H, dk, dv, m = cfg.H, cfg.d_k, cfg.d_v, cfg.m
+    per_tok = {
+        "scan_fwd_kernel": H * (dk + dv) * esz,
+        "chunk_fwd_kernel": H * (2 * dk * esz + 8 * m),
+        "apply_fwd_kernel": H * 2 * dv * esz,
+        "chunk_dz_kernel": H * (2 * dv * esz + 8 * m),
+        "scan_bwd_kernel": H * (dk + dv) * esz,
+        "chunk_intra_kernel": H * ((2 * dk + dv) * esz + 12 * m),
+        "apply_bwd_kernel": H * 2 * (2 * dk + dv) * esz,
+    }
+    alg_bytes = {n: b * tokens for n, b in per_tok.items()}
     dom = max((n for n in kern_ms if n in alg_bytes), key=lambda n: kern_ms[n])
     achieved = alg_bytes[dom] / (kern_ms[dom] * 1e-3) / 1e9
     ffl, bfl, aff, abf = per_token_head_flops(cfg)

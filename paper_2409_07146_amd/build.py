@@ -8,11 +8,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgsa.so")
-SOURCES = ["gsa_api.hip", "gsa_fwd.hip", "gsa_bwd.hip", "gsa_scan.hip", "gsa_decode.hip",
+SOURCES = ["gsa_api.hip", "gsa_fwd.hip", "gsa_bwd.hip", "gsa_scan.hip", "gsa_apply.hip", "gsa_decode.hip",
            "gsa_profile.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes"]
+         "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes", "-Wno-pass-failed"]
 
 
 def _hipcc():

@@ -42,19 +42,32 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     if (slots > 0x3fffffff) return GSA_ERR_SHAPE;
     pl->chunk_slots = (int32_t)slots;
     const size_t esz = p->dtype == GSA_BF16 ? 2 : 4;
-    const size_t state = (size_t)slots * p->H * p->m * (size_t)(p->d_k + p->d_v) * esz;
-    const size_t wts = (size_t)slots * p->H * p->m * (size_t)pl->chunk * esz;
-    const size_t tokm = (size_t)tokens * p->H * p->m * sizeof(float);
+    const size_t M = p->m, dk = p->d_k, dv = p->d_v, D = dk + dv, C = pl->chunk, KM = M < 32 ? 32 : M;
+    const size_t ch = (size_t)slots * p->H;                 // (chunk, head) records
+    // memory snapshots: forward keeps Kt natural and Vt transposed; the backward's recomputation
+    // keeps both natural plus Kt transposed; the memory gradient is kept in all four forms
+    pl->layS_fwd = {(long long)(M * D), 0, -1, -1, (long long)(M * dk)};
+    pl->layS_bwd = {(long long)(M * (D + dk)), 0, (long long)(M * dk), (long long)(M * D), -1};
+    pl->layE = {(long long)(2 * M * D), 0, (long long)(M * dk), (long long)(M * D), (long long)(M * D + M * dk)};
+    pl->laySF = {(long long)(M * D), 0, (long long)(M * dk), -1, -1};
+    const size_t tokm = (size_t)tokens * p->H * M * sizeof(float);
     size_t off = 0;
     pl->off_table = off;  off += align_up(p->cu_seqlens ? (size_t)slots * 4 * sizeof(int32_t) : 0);
     pl->off_seqtab = off; off += align_up(p->cu_seqlens ? (size_t)p->n_seqs * 4 * sizeof(int32_t) : 0);
-    pl->off_Wf = off;     off += align_up(wts);
-    pl->off_dec = off;    off += align_up((size_t)slots * p->H * p->m * sizeof(float));
-    pl->off_S = off;      off += align_up(state);
-    pl->total_fwd = off;
-    pl->off_SF = off;     off += align_up((size_t)pl->n_seqs * p->H * p->m * (size_t)(p->d_k + p->d_v) * esz);
-    pl->off_Wr = off;     off += align_up(2 * wts);
-    pl->off_E = off;      off += align_up(state);
+    pl->off_Wf = off;     off += align_up(ch * M * C * esz);
+    pl->off_dec = off;    off += align_up(ch * M * sizeof(float));
+    pl->off_tA = off;     off += align_up(ch * C * C * esz);
+    pl->off_tP = off;     off += align_up(ch * C * KM * esz);
+    pl->off_S = off;
+    pl->total_fwd = off + align_up(ch * M * D * esz);
+    off += align_up(ch * M * (D + dk) * esz);
+    pl->off_SF = off;     off += align_up((size_t)pl->n_seqs * p->H * M * D * esz);
+    pl->off_Wr = off;     off += align_up(ch * 2 * M * C * esz);
+    pl->off_E = off;      off += align_up(ch * 2 * M * D * esz);
+    pl->off_tBT = off;    off += align_up(ch * C * C * esz);
+    pl->off_tA2T = off;   off += align_up(ch * C * C * esz);
+    pl->off_tAvT = off;   off += align_up(ch * C * C * esz);
+    pl->off_tSbe = off;   off += align_up(ch * C * KM * esz);
     pl->off_dz = off;     off += align_up(tokm);
     pl->off_dgf = off;    off += align_up(tokm);
     pl->total_bwd = off;
@@ -70,9 +83,15 @@ Work make_work(const Plan &pl, void *ws)
     w.Wf = b + pl.off_Wf;
     w.dec = reinterpret_cast<float *>(b + pl.off_dec);
     w.S = b + pl.off_S;
+    w.tA = b + pl.off_tA;
+    w.tP = b + pl.off_tP;
     w.SF = b + pl.off_SF;
     w.Wr = b + pl.off_Wr;
     w.E = b + pl.off_E;
+    w.tBT = b + pl.off_tBT;
+    w.tA2T = b + pl.off_tA2T;
+    w.tAvT = b + pl.off_tAvT;
+    w.tSbe = b + pl.off_tSbe;
     w.dz = reinterpret_cast<float *>(b + pl.off_dz);
     w.dgf = reinterpret_cast<float *>(b + pl.off_dgf);
     return w;

@@ -1,0 +1,171 @@
+// The wide contractions of Gated Slot Attention: every output of width d_k or d_v is
+//
+//     out[C x cols] = s_tok * A_tok[C x C] X[C x cols]  +  s_slot * A_slot[C x m] St[m x cols]
+//
+// per (chunk, head): the intra-chunk term contracts a small token-by-token matrix with a token
+// tensor of the chunk, the inter-chunk term contracts a small token-by-slot matrix with a slot
+// memory (paper, Appendix A, Eq. (gla-chunk): intra and inter parts).  The small matrices are
+// produced by the chunk kernels and are tiny next to the [tokens x d] tensors, so this kernel
+// is where the bytes move:
+//
+//     forward  o  = A2   V  + (p e^G)      Vt_start
+//     backward dq = Bm   K  + (dz e^G)     Kt_start      (both scaled)
+//              dk = Bm^T Q  + (s e^{G_C-G}) E_k           (first term scaled)
+//              dv = A2^T dO + (s e^{G_C-G}) E_v
+//
+// One workgroup per (column slice, chunk, head, output).  LDS holds only the transposed token
+// tile (contraction over tokens needs token-fastest operands; the tile is written with an XOR
+// swizzle so the transposing stores spread over all banks) and is reused for the output tile.
+// The small matrices and the slot memories (stored transposed by the scans) are read as
+// fragments straight from global memory.  ~18 KB of LDS per workgroup, so many workgroups
+// are resident per CU and their loads overlap.
+#include "gsa_chunk.h"
+#include "gsa_launch.h"
+
+namespace gsa {
+
+template <typename T> struct ApplyOne {
+    const T *A_tok;       // [chunk][H][C][C]
+    const T *A_slot;      // [chunk][H][C][KM]
+    const T *xtok;        // [tokens][H][d]
+    const T *xslotT;      // record base + block offset: [d][M] per (chunk, head)
+    long long xs_stride;  // elements per (chunk, head) record
+    T *out;               // [tokens][H][d]
+    int d;
+    float s_tok, s_slot;
+};
+template <typename T> struct ApplyArgs { ApplyOne<T> one[3]; };
+
+template <typename T, int M> struct ApplyLds {
+    static constexpr int C = Geo<T>::C;
+    static constexpr int PAD = Atom<T>::kPad;
+    static constexpr int NS = (sizeof(T) == 2) ? 128 : 64;
+    static constexpr int lda = C + PAD, ldo = NS + PAD;
+    static constexpr size_t szX = sizeof(T) * NS * lda, szO = sizeof(T) * C * ldo;
+    static constexpr size_t bytes = szX > szO ? szX : szO;
+};
+
+template <typename T, int M>
+__global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, ApplyArgs<T> args)
+{
+    using L = ApplyLds<T, M>;
+    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
+    constexpr int KM = (M < 32) ? 32 : M;
+    constexpr int CI = C / 16, NIo = L::NS / (16 * NW);
+    __shared__ __align__(16) unsigned char smem[L::bytes];
+    T *XT = reinterpret_cast<T *>(smem);
+    T *Os = reinterpret_cast<T *>(smem);
+
+    ChunkInfo ci;
+    if (!chunk_lookup(cm, blockIdx.y, ci)) return;
+    const int h = blockIdx.z % H, which = blockIdx.z / H;
+    const ApplyOne<T> &a = args.one[which];
+    const int cs = blockIdx.x * L::NS;
+    if (cs >= a.d) return;
+    const int ncols = min(L::NS, a.d - cs);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
+    const size_t ch = (size_t)blockIdx.y * H + h;
+    const size_t tokh = (size_t)ci.tok0 * H + h;
+    const int wcol = 16 * NIo * w;
+    const bool active = wcol < ncols;
+
+    TokTile<T, C, L::NS, NT> tt;
+    tt.load(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);
+
+    // inter-chunk term first: its operands come straight from global memory
+    f32x4 acc2[CI][NIo];
+    zero_acc(acc2);
+    if (active) {
+        const T *As = a.A_slot + ch * C * KM;
+        const T *Bs = a.xslotT + ch * a.xs_stride + (size_t)cs * M;
+#pragma unroll
+        for (int k0 = 0; k0 < KM; k0 += 32) {
+            typename Atom<T>::Frag af[CI], bf[NIo];
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(As + (mi * 16 + r) * KM + k0 + g8);
+#pragma unroll
+            for (int ni = 0; ni < NIo; ++ni)
+                bf[ni] = gfrag<T>(Bs + (size_t)(wcol + ni * 16 + r) * M + k0 + g8, k0 + g8 < M);
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc2[mi][ni], af[mi], bf[ni]);
+        }
+    }
+    tt.store_transposed(XT, L::lda, ncols, tid);
+    __syncthreads();
+    f32x4 acc1[CI][NIo];
+    zero_acc(acc1);
+    if (active) {
+        const T *At = a.A_tok + ch * C * C;
+#pragma unroll
+        for (int k0 = 0; k0 < C; k0 += 32) {
+            typename Atom<T>::Frag af[CI], bf[NIo];
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(At + (mi * 16 + r) * C + k0 + g8);
+#pragma unroll
+            for (int ni = 0; ni < NIo; ++ni)
+                bf[ni] = Atom<T>::load(XT + xt_off<C>(wcol + ni * 16 + r, k0 + g8, L::lda));
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc1[mi][ni], af[mi], bf[ni]);
+        }
+    }
+    __syncthreads();   // the token tile is dead: its space becomes the output tile
+    if (active) {
+#pragma unroll
+        for (int mi = 0; mi < CI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NIo; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] =
+                        from_f32<T>(a.s_tok * acc1[mi][ni][j] + a.s_slot * acc2[mi][ni][j]);
+    }
+    __syncthreads();
+    store_tile<T>(a.out + tokh * a.d + cs, (size_t)H * a.d, Os, L::ldo, C, ncols, ci.len, tid, NT);
+}
+
+template <typename T, int M>
+static hipError_t launch_apply_tm(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st)
+{
+    const ChunkMap cm = make_chunk_map(pl, w);
+    ApplyArgs<T> args;
+    int dmax = 0;
+    for (int i = 0; i < 3; ++i) {
+        const ApplyIo &s = io[i < n ? i : 0];
+        ApplyOne<T> &o = args.one[i];
+        o.A_tok = static_cast<const T *>(s.A_tok);
+        o.A_slot = static_cast<const T *>(s.A_slot);
+        o.xtok = static_cast<const T *>(s.xtok);
+        o.xslotT = static_cast<const T *>(s.xslot_rec) + s.xslot_off;
+        o.xs_stride = s.xslot_stride;
+        o.out = static_cast<T *>(s.out);
+        o.d = s.d;
+        o.s_tok = s.s_tok;
+        o.s_slot = s.s_slot;
+        if (i < n && s.d > dmax) dmax = s.d;
+    }
+    constexpr int NS = ApplyLds<T, M>::NS;
+    dim3 grid((dmax + NS - 1) / NS, pl.chunk_slots, pl.H * n);
+    KernelTimer kt(slot, st);
+    hipLaunchKernelGGL((apply_kernel<T, M>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st)
+{
+#define GSA_APPLY(T)                                                        \
+    switch (pl.m) {                                                         \
+    case 16: return launch_apply_tm<T, 16>(pl, w, io, n, slot, st);         \
+    case 32: return launch_apply_tm<T, 32>(pl, w, io, n, slot, st);         \
+    default: return launch_apply_tm<T, 64>(pl, w, io, n, slot, st);         \
+    }
+    if (pl.dtype == 0) { GSA_APPLY(float) }
+    GSA_APPLY(bf16_t)
+#undef GSA_APPLY
+}
+
+}  // namespace gsa

@@ -21,9 +21,10 @@
 // of the chunk-end memory with its gradient, which both scans already hold.  That keeps
 // rounding errors from accumulating along the sequence.
 //
-// Kernels: gate + forward scan (gsa_scan.hip; recompute chunk-start memories, since nothing
-// but z was saved by the forward), bwd_dz (chunk-parallel: dp, dz, weights of the reverse
-// scan), reverse scan (gsa_scan.hip: E), bwd_main (chunk-parallel: everything else).
+// Kernels of one backward call: gate + forward scan (gsa_scan.hip; recompute the chunk-start
+// memories, since nothing but z was saved by the forward), chunk_dz (chunk-parallel: dp, dz,
+// weights of the reverse scan), reverse scan (gsa_scan.hip: E), chunk_intra (chunk-parallel:
+// Bm, A2, ds, dg and the small operand matrices), apply (gsa_apply.hip: dq, dk, dv).
 #include "gsa_chunk.h"
 #include "gsa_launch.h"
 
@@ -35,25 +36,23 @@ namespace gsa {
 template <typename T, int M> struct DzLds {
     static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
-    static constexpr int KS = (sizeof(T) == 2) ? 64 : 32;
-    static constexpr int ldg = M + 4, lda = C + PAD, ldq = KS + PAD;
+    static constexpr int ldg = M + 4, lda = C + PAD;
     static constexpr size_t oG = 0;
     static constexpr size_t oS = oG + sizeof(float) * C * ldg;
-    static constexpr size_t oTot = oS + sizeof(float) * C * ldg;
-    static constexpr size_t oA = oTot + sizeof(float) * Geo<T>::NT;
-    static constexpr size_t oX = oA + sizeof(T) * C * lda;
-    static constexpr size_t oY = oX + sizeof(T) * C * ldq;
-    static constexpr size_t oSt = oY + sizeof(T) * C * ldq;
-    static constexpr size_t bytes = oSt + sizeof(T) * M * ldq;
+    static constexpr size_t oA = oS + sizeof(float) * C * ldg;
+    static constexpr size_t oTot = oA;   // gate_prep's scratch, dead before As is written
+    static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
+                                                                                  : sizeof(float) * Geo<T>::NT;
+    static constexpr size_t bytes = oA + szA;
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, int d_k, int d_v,
-                                                            const T *__restrict__ v, const T *__restrict__ dO,
-                                                            const float *__restrict__ g, const float *__restrict__ z,
-                                                            const T *__restrict__ S, float scale,
-                                                            float *__restrict__ dz, float *__restrict__ dgf,
-                                                            T *__restrict__ Wr)
+__global__ __launch_bounds__(Geo<T>::NT) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
+                                                              const T *__restrict__ v, const T *__restrict__ dO,
+                                                              const float *__restrict__ g, const float *__restrict__ z,
+                                                              const T *__restrict__ S, StateLayout lay,
+                                                              float *__restrict__ dz, float *__restrict__ dgf,
+                                                              T *__restrict__ Wr, T *__restrict__ tAvT)
 {
     using L = DzLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
@@ -63,25 +62,22 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, 
     float *Ss = reinterpret_cast<float *>(smem + L::oS);
     float *tot = reinterpret_cast<float *>(smem + L::oTot);
     T *As = reinterpret_cast<T *>(smem + L::oA);
-    T *Xs = reinterpret_cast<T *>(smem + L::oX);
-    T *Ys = reinterpret_cast<T *>(smem + L::oY);
-    T *Sts = reinterpret_cast<T *>(smem + L::oSt);
 
     ChunkInfo ci;
     if (!chunk_lookup(cm, blockIdx.x, ci)) return;
     const int h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4;
-    const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const T *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;
+    const size_t ch = (size_t)blockIdx.x * H + h;
+    const T *Vn = S + ch * lay.stride + lay.oVn;      // value memory at chunk start [M][d_v]
     const int rowb = 16 * w;
 
     gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
     float dp[MI][4];
     bool unsafe;
-    gated_scores<T, M, C, L::KS>(dp, unsafe, Gs, Ss, L::ldg, As, L::lda, Xs, Ys, Sts, L::ldq, dO + tokh * d_v,
-                                 v + tokh * d_v, (size_t)H * d_v, d_v, Sc + d_k, (size_t)D, ci.len, tid);
+    gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, As, L::lda, dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v,
+                          d_v, Vn, (size_t)d_v, ci.len, tid);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -107,8 +103,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, 
         for (int j = 0; j < 4; ++j) { p[ni][j] *= rsum[j]; pdp[j] += p[ni][j] * dp[ni][j]; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) pdp[j] = row16_sum(pdp[j]);
-    // dz, dgf for the main kernel; gate-weighted transposes (scale*dz*exp G, p*exp G) for the reverse scan
-    T *Wk = Wr + ((size_t)blockIdx.x * H + h) * 2 * M * C, *Wv = Wk + M * C;
+    // dz, dgf for the intra kernel; gate-weighted transposes (scale*dz*exp G, p*exp G) for the reverse scan
+    T *Wk = Wr + ch * 2 * M * C, *Wv = Wk + M * C;
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) {
         const int i = ni * 16 + r;
@@ -133,129 +129,76 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_dz_kernel(ChunkMap cm, int H, 
             Wv[i * C + rowb + g4 + j] = wv[j];
         }
     }
+    // the causally masked (dO_t . v_r), transposed, for the intra kernel's ds contraction
+    T *dAv = tAvT + ch * C * C;
+    for (int idx = tid; idx < C * C / 8; idx += NT) {
+        const int rr = idx / (C / 8), t8 = (idx - rr * (C / 8)) * 8;
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = to_f32(As[(t8 + e) * L::lda + rr]);
+        store8<T>(dAv + rr * C + t8, x);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
-// Main chunk-parallel gradient kernel.
+// Intra-chunk gradient kernel.
 // ---------------------------------------------------------------------------------------
-template <typename T, int M> struct MainLds {
+template <typename T> __device__ __forceinline__ float frag_dot(const typename Atom<T>::Frag &a,
+                                                                const typename Atom<T>::Frag &b)
+{
+    float d = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d += to_f32(a[e]) * to_f32(b[e]);
+    return d;
+}
+
+// four consecutive elements of one row, from fp32
+__device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d)
+{
+    bf16x4 x;
+    x[0] = (bf16_t)a; x[1] = (bf16_t)b; x[2] = (bf16_t)c; x[3] = (bf16_t)d;
+    *reinterpret_cast<bf16x4 *>(p) = x;
+}
+__device__ __forceinline__ void store4(float *p, float a, float b, float c, float d)
+{
+    *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
+}
+
+template <typename T, int M> struct IntraLds {
     static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int KM = (M < 32) ? 32 : M;
-    static constexpr int KS = (sizeof(T) == 2) ? 64 : 32;     // contraction slice in phase 1
-    static constexpr int NS = (sizeof(T) == 2) ? 128 : 32;    // output column slice in phase 3
-    static constexpr int ldg = M + 4, lda = C + PAD, ldp = KM + PAD, ldq = KS + PAD, ldo = NS + PAD;
-    // region F: fp32 tiles Gs, Ss, Pf, Df; reused by the phase-3 staging
-    static constexpr size_t szF = 4 * sizeof(float) * C * ldg;
+    static constexpr int ldg = M + 4, lda = C + PAD;
     static constexpr size_t oG = 0;
     static constexpr size_t oS = oG + sizeof(float) * C * ldg;
     static constexpr size_t oPf = oS + sizeof(float) * C * ldg;
     static constexpr size_t oDf = oPf + sizeof(float) * C * ldg;
-    static constexpr size_t oBt = 0;                                   // [NS][lda] token-contraction operand
-    static constexpr size_t oBs = oBt + sizeof(T) * NS * lda;          // [NS][ldp] slot-contraction operand
-    static constexpr size_t oO = oBs + sizeof(T) * NS * ldp;           // [C][ldo]  output tile
-    static constexpr size_t sz3 = oO + sizeof(T) * C * ldo;
-    static constexpr size_t oTot = szF > sz3 ? szF : sz3;
-    static constexpr size_t oCarry = oTot + sizeof(float) * Geo<T>::NT;
-    // region T: operand tiles that live until the end
-    static constexpr size_t oBm = oCarry + sizeof(float) * 128;
-    static constexpr size_t oBmT = oBm + sizeof(T) * C * lda;
-    static constexpr size_t oA2T = oBmT + sizeof(T) * C * lda;
-    static constexpr size_t oDZe = oA2T + sizeof(T) * C * lda;
-    static constexpr size_t oSbe = oDZe + sizeof(T) * C * ldp;
-    // region U: phase-1 staging, then the transposed score matrices
-    static constexpr size_t oU = oSbe + sizeof(T) * C * ldp;
-    static constexpr size_t oX = oU;
-    static constexpr size_t oY = oX + sizeof(T) * C * ldq;
-    static constexpr size_t oE = oY + sizeof(T) * C * ldq;
-    static constexpr size_t end1 = oE + sizeof(T) * M * ldq;
-    static constexpr size_t oAT = oU;
-    static constexpr size_t oAvT = oAT + sizeof(T) * C * lda;
-    static constexpr size_t end2 = oAvT + sizeof(T) * C * lda;
-    static constexpr size_t bytes = end1 > end2 ? end1 : end2;
+    static constexpr size_t oAT = oDf + sizeof(float) * C * ldg;
+    static constexpr size_t oTot = oAT;   // gate_prep's and the suffix sum's scratch (ATs is dead by then)
+    static constexpr size_t szAT = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
+                                                                                   : sizeof(float) * Geo<T>::NT;
+    static constexpr size_t oCarry = oAT + szAT;
+    static constexpr size_t bytes = oCarry + sizeof(float) * 128;
 };
 
-// Stage E[M][KS] (rows of T, stride ld) into Es while accumulating the row-wise inner product
-// with Send (same layout) into part[]: thread handles rows (tid + NT*it) / (KS/8).
-template <typename T, int M, int KS, int NT, int ITS>
-__device__ __forceinline__ void stage_E_dot(T *Es, int ldq, const T *Eg, const T *Sendg, size_t ld,
-                                            float (&part)[ITS], int tid)
-{
-    constexpr int vpr = KS / 8;
-#pragma unroll
-    for (int it = 0; it < ITS; ++it) {
-        const int idx = tid + NT * it;
-        if (idx < M * vpr) {
-            const int i = idx / vpr, c = (idx - i * vpr) << 3;
-            Raw8<T> e, s;
-            e.load(Eg + (size_t)i * ld + c);
-            s.load(Sendg + (size_t)i * ld + c);
-            float d = 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) d += to_f32(e.get(u)) * to_f32(s.get(u));
-            part[it] += d;
-            e.store(Es + i * ldq + c);
-        }
-    }
-}
+template <typename T> struct IntraArgs {
+    const T *q, *k, *v;
+    const float *g, *z, *dz, *dgf;
+    const T *S, *SF, *E;
+    StateLayout layS, laySF, layE;
+    const T *tAvT;
+    float *dg;
+    T *tB, *tBT, *tA2T, *tDZe, *tSbe;
+};
 
-// One output pass of phase 3:  out = s_tok * (A_tok B_tok) + s_slot * (A_slot B_slot), written
-// to global rows.  A_tok [C][lda] contracts over the chunk's tokens with rows of `xtok`
-// ([len][ncols_total], element type T); A_slot [C][ldp] contracts over slots with rows of
-// `xslot` ([M][.] rows of T, row stride ldslot).
 template <typename T, int M>
-__device__ __forceinline__ void grad_pass(T *dst, size_t ld_dst, int dcols, const T *A_tok, const T *A_slot,
-                                          const T *xtok, size_t ld_tok, const T *xslot, size_t ld_slot,
-                                          float s_tok, float s_slot, T *Bt, T *Bs, T *Os, int len, int tid)
+__global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
+                                                                 IntraArgs<T> a)
 {
-    using L = MainLds<T, M>;
+    using L = IntraLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
-    constexpr int CI = C / 16, NIo = L::NS / (16 * NW);
-    const int lane = tid & 63, w = tid >> 6;
-    const int r = lane & 15, g4 = (lane >> 4) * 4;
-    for (int cs = 0; cs < dcols; cs += L::NS) {
-        const int ncols = min(L::NS, dcols - cs);
-        stage_cols<T, T>(Bt, L::lda, xtok + cs, ld_tok, C, ncols, len, tid, NT);
-        stage_cols<T, T>(Bs, L::ldp, xslot + cs, ld_slot, M, ncols, M, tid, NT);
-        if (M < L::KM) {
-            for (int idx = tid; idx < ncols * (L::KM - M); idx += NT)
-                Bs[(idx / (L::KM - M)) * L::ldp + M + idx % (L::KM - M)] = from_f32<T>(0.f);
-        }
-        __syncthreads();
-        const int wcol = 16 * NIo * w;
-        if (wcol < ncols) {
-            f32x4 a1[CI][NIo], a2[CI][NIo];
-            zero_acc(a1);
-            zero_acc(a2);
-            gemm_nt<T, CI, NIo>(a1, A_tok, L::lda, Bt + wcol * L::lda, L::lda, C, lane);
-            gemm_nt<T, CI, NIo>(a2, A_slot, L::ldp, Bs + wcol * L::ldp, L::ldp, L::KM, lane);
-#pragma unroll
-            for (int mi = 0; mi < CI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NIo; ++ni)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] =
-                            from_f32<T>(s_tok * a1[mi][ni][j] + s_slot * a2[mi][ni][j]);
-        }
-        __syncthreads();
-        store_tile<T>(dst + cs, ld_dst, Os, L::ldo, C, ncols, len, tid, NT);
-        __syncthreads();
-    }
-}
-
-template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
-    ChunkMap cm, int H, int d_k, int d_v, float scale, const T *__restrict__ q, const T *__restrict__ k,
-    const T *__restrict__ v, const T *__restrict__ dO, const float *__restrict__ g, const float *__restrict__ z,
-    const float *__restrict__ dz, const float *__restrict__ dgf, const T *__restrict__ S,
-    const T *__restrict__ SF, const T *__restrict__ E, T *__restrict__ dq, T *__restrict__ dk,
-    T *__restrict__ dv, float *__restrict__ dg)
-{
-    using L = MainLds<T, M>;
-    constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
-    constexpr int MI = M / 16, CI = C / 16;
-    constexpr int ITS = (M * (L::KS / 8) + NT - 1) / NT;
+    constexpr int MI = M / 16, CI = C / 16, KM = L::KM;
+    constexpr int NCP = (MI + NW - 1) / NW;   // slot blocks whose carry this wave accumulates
     extern __shared__ __align__(16) unsigned char smem[];
     float *Gs = reinterpret_cast<float *>(smem + L::oG);
     float *Ss = reinterpret_cast<float *>(smem + L::oS);
@@ -263,117 +206,179 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
     float *Df = reinterpret_cast<float *>(smem + L::oDf);    // dz, later dGam
     float *tot = reinterpret_cast<float *>(smem + L::oTot);
     float *carry = reinterpret_cast<float *>(smem + L::oCarry);
-    T *Bms = reinterpret_cast<T *>(smem + L::oBm);           // [t][r]
-    T *BmTs = reinterpret_cast<T *>(smem + L::oBmT);         // [r][t]
-    T *A2Ts = reinterpret_cast<T *>(smem + L::oA2T);         // [r][t]
-    T *DZe = reinterpret_cast<T *>(smem + L::oDZe);          // [t][i] dz exp(G)
-    T *Sbe = reinterpret_cast<T *>(smem + L::oSbe);          // [r][i] s exp(G_C - G)
-    T *Xs = reinterpret_cast<T *>(smem + L::oX);
-    T *Ys = reinterpret_cast<T *>(smem + L::oY);
-    T *Es = reinterpret_cast<T *>(smem + L::oE);
-    T *ATs = reinterpret_cast<T *>(smem + L::oAT);           // [r][t] (q_t . k_r) for t >= r
-    T *AvTs = reinterpret_cast<T *>(smem + L::oAvT);         // [r][t] (dO_t . v_r) for t >= r
-    T *Bt = reinterpret_cast<T *>(smem + L::oBt);
-    T *Bs = reinterpret_cast<T *>(smem + L::oBs);
-    T *Os = reinterpret_cast<T *>(smem + L::oO);
+    T *ATs = reinterpret_cast<T *>(smem + L::oAT);           // [r][t] (q_t . k_r) for t >= r; later Bm [t][r]
 
     ChunkInfo ci;
     if (!chunk_lookup(cm, blockIdx.x, ci)) return;
     const int h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
-    const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const T *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;           // memory at chunk start
-    const T *Ec = E + (((size_t)blockIdx.x * H + h) * M) * D;           // memory gradient at chunk end
+    const size_t ch = (size_t)blockIdx.x * H + h;
+    const T *EK = a.E + ch * a.layE.stride + a.layE.oKn;     // memory gradient at chunk end, natural
+    const T *EV = a.E + ch * a.layE.stride + a.layE.oVn;
     int chunk0, nch, stok0, sntok;
     seq_lookup(cm, ci.seq, chunk0, nch, stok0, sntok);
-    const T *Send = (ci.idx + 1 < nch) ? Sc + (size_t)H * M * D     // next chunk's start memory
-                                           : SF + (((size_t)ci.seq * H + h) * M) * D;
+    const T *SendK, *SendV;                                  // memory at chunk end, natural
+    if (ci.idx + 1 < nch) {
+        const T *rec = a.S + (ch + H) * a.layS.stride;       // = start of the next chunk
+        SendK = rec + a.layS.oKn;
+        SendV = rec + a.layS.oVn;
+    } else {
+        const T *rec = a.SF + ((size_t)ci.seq * H + h) * a.laySF.stride;
+        SendK = rec + a.laySF.oKn;
+        SendV = rec + a.laySF.oVn;
+    }
+    const T *AvT = a.tAvT + ch * C * C;
     const int rowb = 16 * w;
 
-    gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
-    softmax_rows<M, C>(Pf, Df, L::ldg, z + tokh * M, dz + tokh * M, (size_t)H * M, ci.len, tid);
+    gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, a.g + tokh * M, (size_t)H * M, ci.len, tid);
+    softmax_rows<M, C>(Pf, Df, L::ldg, a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
 
-    // ---- phase 1: contractions over the head dimension
-    f32x4 accA[CI], accAv[CI], accX[MI];
+    // ---- phase 1: contractions over the head dimension, operands straight from global memory
+    //   A[t][r] = q_t . k_r (r <= t),  X[r][i] = <E[i], [k_r | v_r]>,  carry[i] = <E[i], S_end[i]>
+    f32x4 accA[CI], accX[MI];
 #pragma unroll
-    for (int ni = 0; ni < CI; ++ni) { accA[ni] = f32x4{0.f, 0.f, 0.f, 0.f}; accAv[ni] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int ni = 0; ni < CI; ++ni) accA[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) accX[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float cpart[ITS];
+    float cpart[NCP];
 #pragma unroll
-    for (int it = 0; it < ITS; ++it) cpart[it] = 0.f;
-#pragma unroll 1
-    for (int half = 0; half < 2; ++half) {
-        const T *X = half ? dO + tokh * d_v : q + tokh * d_k;
-        const T *Y = half ? v + tokh * d_v : k + tokh * d_k;
-        const int d = half ? d_v : d_k;
-        const int coff = half ? d_k : 0;
-        for (int ks = 0; ks < d; ks += L::KS) {
-            stage_rows<T, T>(Xs, L::ldq, X + ks, (size_t)H * d, C, L::KS, ci.len, tid, NT);
-            stage_rows<T, T>(Ys, L::ldq, Y + ks, (size_t)H * d, C, L::KS, ci.len, tid, NT);
-            stage_E_dot<T, M, L::KS, NT, ITS>(Es, L::ldq, Ec + coff + ks, Send + coff + ks, (size_t)D, cpart, tid);
-            __syncthreads();
-#pragma unroll
-            for (int k0 = 0; k0 < L::KS; k0 += 32) {
-                const typename Atom<T>::Frag aX = Atom<T>::load(Xs + (rowb + r) * L::ldq + k0 + g8);
-                const typename Atom<T>::Frag aY = Atom<T>::load(Ys + (rowb + r) * L::ldq + k0 + g8);
-#pragma unroll
-                for (int ni = 0; ni < CI; ++ni) {
-                    if (ni > w) continue;
-                    const typename Atom<T>::Frag b = Atom<T>::load(Ys + (ni * 16 + r) * L::ldq + k0 + g8);
-                    if (half) Atom<T>::mma(accAv[ni], aX, b);
-                    else Atom<T>::mma(accA[ni], aX, b);
-                }
-#pragma unroll
-                for (int ni = 0; ni < MI; ++ni)
-                    Atom<T>::mma(accX[ni], aY, Atom<T>::load(Es + (ni * 16 + r) * L::ldq + k0 + g8));
-            }
-            __syncthreads();
-        }
-    }
-    // carry[i] = <E[i], S_end[i]>: the sum of dGam over every later chunk of this sequence
+    for (int u = 0; u < NCP; ++u) cpart[u] = 0.f;
+    const bool la = rowb + r < ci.len;
     {
-        constexpr int vpr = L::KS / 8;
+        const T *qa = a.q + (tokh + (size_t)(rowb + r) * H) * d_k + g8;
+        const T *ka = a.k + (tokh + (size_t)(rowb + r) * H) * d_k + g8;
+#pragma unroll 2
+        for (int k0 = 0; k0 < d_k; k0 += 32) {
+            const typename Atom<T>::Frag aQ = gfrag<T>(qa + k0, la);
+            const typename Atom<T>::Frag aK = gfrag<T>(ka + k0, la);
 #pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            float x = cpart[it];
+            for (int ni = 0; ni < CI; ++ni)
+                if (ni <= w)
+                    Atom<T>::mma(accA[ni], aQ,
+                                 gfrag<T>(a.k + (tokh + (size_t)(ni * 16 + r) * H) * d_k + k0 + g8, ni * 16 + r < ci.len));
 #pragma unroll
-            for (int o = 1; o < vpr; o <<= 1) x += __shfl_xor(x, o, 64);
-            const int idx = tid + NT * it;
-            if (idx < M * vpr && (idx % vpr) == 0) carry[idx / vpr] = x;
+            for (int ni = 0; ni < MI; ++ni) {
+                const size_t off = (size_t)(ni * 16 + r) * d_k + k0 + g8;
+                const typename Atom<T>::Frag bE = Atom<T>::load(EK + off);
+                Atom<T>::mma(accX[ni], aK, bE);
+                if (ni % NW == w) cpart[ni / NW] += frag_dot<T>(bE, Atom<T>::load(SendK + off));
+            }
         }
     }
-    // ---- phase 2a: transposed, causally masked score matrices; gate-scaled operand tiles
+    {
+        const T *va = a.v + (tokh + (size_t)(rowb + r) * H) * d_v + g8;
+#pragma unroll 2
+        for (int k0 = 0; k0 < d_v; k0 += 32) {
+            const typename Atom<T>::Frag aV = gfrag<T>(va + k0, la);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) {
+                const size_t off = (size_t)(ni * 16 + r) * d_v + k0 + g8;
+                const typename Atom<T>::Frag bE = Atom<T>::load(EV + off);
+                Atom<T>::mma(accX[ni], aV, bE);
+                if (ni % NW == w) cpart[ni / NW] += frag_dot<T>(bE, Atom<T>::load(SendV + off));
+            }
+        }
+    }
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni) {
+        if (ni % NW != w) continue;
+        float x = cpart[ni / NW];
+        x += __shfl_xor(x, 16, 64);
+        x += __shfl_xor(x, 32, 64);
+        if (lane < 16) carry[ni * 16 + lane] = x;
+    }
+    // ---- phase 2a: transposed masked A into LDS; the slot-side operand tiles of the apply kernel
 #pragma unroll
     for (int ni = 0; ni < CI; ++ni)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j, rr = ni * 16 + r;
-            const bool keep = (ni <= w) && (rr <= t);
-            ATs[rr * L::lda + t] = from_f32<T>(keep ? accA[ni][j] : 0.f);
-            AvTs[rr * L::lda + t] = from_f32<T>(keep ? accAv[ni][j] : 0.f);
+            ATs[rr * L::lda + t] = from_f32<T>((ni <= w && rr <= t) ? accA[ni][j] : 0.f);
         }
-    for (int idx = tid; idx < C * L::KM; idx += NT) {
-        const int t = idx / L::KM, i = idx - t * L::KM;
-        float a = 0.f, b = 0.f;
-        if (i < M) {
-            const float G = Gs[t * L::ldg + i];
-            a = Df[t * L::ldg + i] * __expf(G);
-            b = Ss[t * L::ldg + i] * __expf(Gs[(C - 1) * L::ldg + i] - G);
-        }
-        DZe[t * L::ldp + i] = from_f32<T>(a);
-        Sbe[t * L::ldp + i] = from_f32<T>(b);
-    }
-    __syncthreads();
-    const bool unsafe = block_unsafe<M>(Gs, L::ldg, rowb, lane);
-    // ---- phase 2b: Bm and A2 for row block w
+    __syncthreads();   // Pf, Df, ATs visible to every wave
     {
-        f32x4 accB[CI], acc2[CI];
+        T *dD = a.tDZe + ch * C * KM, *dS = a.tSbe + ch * C * KM;
+        for (int idx = tid; idx < C * KM / 8; idx += NT) {
+            const int t = idx / (KM / 8), i8 = (idx - t * (KM / 8)) * 8;
+            float x[8], y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = i8 + e;
+                x[e] = y[e] = 0.f;
+                if (i < M) {
+                    const float G = Gs[t * L::ldg + i];
+                    x[e] = Df[t * L::ldg + i] * __expf(G);
+                    y[e] = Ss[t * L::ldg + i] * __expf(Gs[(C - 1) * L::ldg + i] - G);
+                }
+            }
+            store8<T>(dD + t * KM + i8, x);
+            store8<T>(dS + t * KM + i8, y);
+        }
+    }
+    const bool unsafe = block_unsafe<M>(Gs, L::ldg, rowb, lane);
+    // ---- phase 2b: write-intensity gradient ds for rows r of block w, then dGam and exp(g)*ds
+    float dGam[MI][4], ads[MI][4];
+    {
+        f32x4 accW[MI];
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) accW[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int tstart = unsafe ? rowb + 16 : rowb;
+        for (int k0 = (tstart & ~31); k0 < C; k0 += 32) {
+            const typename Atom<T>::Frag aA = Atom<T>::load(ATs + (rowb + r) * L::lda + k0 + g8);
+            const typename Atom<T>::Frag aAv = Atom<T>::load(AvT + (rowb + r) * C + k0 + g8);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) {
+                const int i = ni * 16 + r;
+                const float gend = Gs[(rowb + 15) * L::ldg + i];
+                typename Atom<T>::Frag bdz, bp;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int t = k0 + g8 + e;
+                    float x = 0.f, y = 0.f;
+                    if (t >= tstart) {
+                        const float f = __expf(fminf(Gs[t * L::ldg + i] - gend, kExpClamp));
+                        x = scale * Df[t * L::ldg + i] * f;
+                        y = Pf[t * L::ldg + i] * f;
+                    }
+                    bdz[e] = from_f32<T>(x);
+                    bp[e] = from_f32<T>(y);
+                }
+                Atom<T>::mma(accW[ni], aA, bdz);
+                Atom<T>::mma(accW[ni], aAv, bp);
+            }
+        }
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) {
+            const int i = ni * 16 + r;
+            const float gend = Gs[(rowb + 15) * L::ldg + i], GC = Gs[(C - 1) * L::ldg + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int rr = rowb + g4 + j;
+                const float Gr = Gs[rr * L::ldg + i];
+                float ds = __expf(GC - Gr) * accX[ni][j] + __expf(gend - Gr) * accW[ni][j];
+                if (unsafe) {
+                    float sum = 0.f;
+                    for (int t = rr; t < rowb + 16; ++t)
+                        sum += (to_f32(ATs[rr * L::lda + t]) * scale * Df[t * L::ldg + i] +
+                                to_f32(AvT[rr * C + t]) * Pf[t * L::ldg + i]) *
+                               __expf(Gs[t * L::ldg + i] - Gr);
+                    ds += sum;
+                }
+                const float sv = Ss[rr * L::ldg + i];
+                const float f = (rr < ci.len) ? a.dgf[(tokh + (size_t)rr * H) * M + i] : 0.f;
+                dGam[ni][j] = f - sv * ds;
+                ads[ni][j] = (1.f - sv) * ds;
+            }
+        }
+    }
+    // ---- phase 2c: Bm and A2 for row block w
+    f32x4 accB[CI], acc2[CI];
+    {
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) { accB[ni] = f32x4{0.f, 0.f, 0.f, 0.f}; acc2[ni] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-        for (int k0 = 0; k0 < L::KM; k0 += 32) {
+        for (int k0 = 0; k0 < KM; k0 += 32) {
             typename Atom<T>::Frag adz, ap;
             {
                 const int t = rowb + r;
@@ -411,89 +416,51 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
             }
         }
         if (unsafe) {
-            const f32x4 eb = pair_weights_exact<M>(Df, L::ldg, Gs, Ss, L::ldg, lane, rowb);
-            const f32x4 e2 = pair_weights_exact<M>(Pf, L::ldg, Gs, Ss, L::ldg, lane, rowb);
+            const f32x4 eb = pair_weights_exact<M, float>(Df, L::ldg, Gs, Ss, L::ldg, lane, rowb);
+            const f32x4 e2 = pair_weights_exact<M, float>(Pf, L::ldg, Gs, Ss, L::ldg, lane, rowb);
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni)
                 if (ni == w) { accB[ni] = eb; acc2[ni] = e2; }
         }
-#pragma unroll
-        for (int ni = 0; ni < CI; ++ni)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int t = rowb + g4 + j, rr = ni * 16 + r;
-                const bool keep = (ni <= w) && (rr <= t);
-                const T bv = from_f32<T>(keep ? accB[ni][j] : 0.f);
-                Bms[t * L::lda + rr] = bv;
-                BmTs[rr * L::lda + t] = bv;
-                A2Ts[rr * L::lda + t] = from_f32<T>(keep ? acc2[ni][j] : 0.f);
-            }
     }
-    // ---- phase 2c: write-intensity gradient ds for rows r of block w, then dGam and exp(g)*ds
-    float dGam[MI][4], ads[MI][4];
+    __syncthreads();   // every wave is done reading p, dz and the transposed A
     {
-        f32x4 accW[MI];
+        T *dBT = a.tBT + ch * C * C, *dA2T = a.tA2T + ch * C * C;
 #pragma unroll
-        for (int ni = 0; ni < MI; ++ni) accW[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const int tstart = unsafe ? rowb + 16 : rowb;
-        for (int k0 = (tstart & ~31); k0 < C; k0 += 32) {
-            const typename Atom<T>::Frag aA = Atom<T>::load(ATs + (rowb + r) * L::lda + k0 + g8);
-            const typename Atom<T>::Frag aAv = Atom<T>::load(AvTs + (rowb + r) * L::lda + k0 + g8);
-#pragma unroll
-            for (int ni = 0; ni < MI; ++ni) {
-                const int i = ni * 16 + r;
-                const float gend = Gs[(rowb + 15) * L::ldg + i];
-                typename Atom<T>::Frag bdz, bp;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int t = k0 + g8 + e;
-                    float x = 0.f, y = 0.f;
-                    if (t >= tstart) {
-                        const float f = __expf(fminf(Gs[t * L::ldg + i] - gend, kExpClamp));
-                        x = scale * Df[t * L::ldg + i] * f;
-                        y = Pf[t * L::ldg + i] * f;
-                    }
-                    bdz[e] = from_f32<T>(x);
-                    bp[e] = from_f32<T>(y);
-                }
-                Atom<T>::mma(accW[ni], aA, bdz);
-                Atom<T>::mma(accW[ni], aAv, bp);
-            }
-        }
-#pragma unroll
-        for (int ni = 0; ni < MI; ++ni) {
-            const int i = ni * 16 + r;
-            const float gend = Gs[(rowb + 15) * L::ldg + i], GC = Gs[(C - 1) * L::ldg + i];
+        for (int ni = 0; ni < CI; ++ni) {
+            const int rr = ni * 16 + r;
+            float bv[4], av[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int rr = rowb + g4 + j;
-                const float Gr = Gs[rr * L::ldg + i];
-                float ds = __expf(GC - Gr) * accX[ni][j] + __expf(gend - Gr) * accW[ni][j];
-                if (unsafe) {
-                    float sum = 0.f;
-                    for (int t = rr; t < rowb + 16; ++t)
-                        sum += (to_f32(ATs[rr * L::lda + t]) * scale * Df[t * L::ldg + i] +
-                                to_f32(AvTs[rr * L::lda + t]) * Pf[t * L::ldg + i]) *
-                               __expf(Gs[t * L::ldg + i] - Gr);
-                    ds += sum;
-                }
-                const float sv = Ss[rr * L::ldg + i];
-                const float f = (rr < ci.len) ? dgf[(tokh + (size_t)rr * H) * M + i] : 0.f;
-                dGam[ni][j] = f - sv * ds;
-                ads[ni][j] = (1.f - sv) * ds;
+                const int t = rowb + g4 + j;
+                const bool keep = (ni <= w) && (rr <= t);
+                bv[j] = keep ? accB[ni][j] : 0.f;
+                av[j] = keep ? acc2[ni][j] : 0.f;
+                ATs[t * L::lda + rr] = from_f32<T>(bv[j]);     // Bm in natural orientation, staged for a row-wise copy
             }
+            store4(dBT + rr * C + rowb + g4, bv[0], bv[1], bv[2], bv[3]);
+            store4(dA2T + rr * C + rowb + g4, av[0], av[1], av[2], av[3]);
+        }
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int rr = rowb + g4 + j, i = ni * 16 + r;
+                Df[rr * L::ldg + i] = dGam[ni][j];
+                Pf[rr * L::ldg + i] = ads[ni][j];
+            }
+    }
+    __syncthreads();
+    {
+        T *dB = a.tB + ch * C * C;
+        for (int idx = tid; idx < C * C / 8; idx += NT) {
+            const int t = idx / (C / 8), c8 = (idx - t * (C / 8)) * 8;
+            Raw8<T> x;
+            x.load(ATs + t * L::lda + c8);
+            x.store(dB + t * C + c8);
         }
     }
-    __syncthreads();   // every wave is done reading p and dz
-#pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int rr = rowb + g4 + j, i = ni * 16 + r;
-            Df[rr * L::ldg + i] = dGam[ni][j];
-            Pf[rr * L::ldg + i] = ads[ni][j];
-        }
-    __syncthreads();
+    __syncthreads();   // ATs is about to be reused as the suffix sum's scratch
     // ---- phase 2d: dg = (suffix sum of dGam inside the chunk) + carry - exp(g) ds
     {
         constexpr int P = NT / M, TP = C / P;
@@ -510,17 +477,9 @@ __global__ __launch_bounds__(Geo<T>::NT) void bwd_main_kernel(
         for (int pp = part + 1; pp < P; ++pp) off += tot[pp * M + i];
         for (int tt = 0; tt < TP; ++tt) {
             const int t = part * TP + tt;
-            if (t < ci.len) dg[(tokh + (size_t)t * H) * M + i] = Df[t * L::ldg + i] + off - Pf[t * L::ldg + i];
+            if (t < ci.len) a.dg[(tokh + (size_t)t * H) * M + i] = Df[t * L::ldg + i] + off - Pf[t * L::ldg + i];
         }
     }
-    __syncthreads();
-    // ---- phase 3: dq, dk, dv
-    grad_pass<T, M>(dq + tokh * d_k, (size_t)H * d_k, d_k, Bms, DZe, k + tokh * d_k, (size_t)H * d_k, Sc, (size_t)D,
-                    scale, scale, Bt, Bs, Os, ci.len, tid);
-    grad_pass<T, M>(dk + tokh * d_k, (size_t)H * d_k, d_k, BmTs, Sbe, q + tokh * d_k, (size_t)H * d_k, Ec, (size_t)D,
-                    scale, 1.f, Bt, Bs, Os, ci.len, tid);
-    grad_pass<T, M>(dv + tokh * d_v, (size_t)H * d_v, d_v, A2Ts, Sbe, dO + tokh * d_v, (size_t)H * d_v, Ec + d_k,
-                    (size_t)D, 1.f, 1.f, Bt, Bs, Os, ci.len, tid);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -536,38 +495,49 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     // 1. recompute the chunk-start memories (and the memories after the last token)
     GSA_HIP_TRY(launch_gates(pl, w, g, st));
     {
-        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false};
+        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false, pl.layS_bwd, pl.laySF};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     dim3 grid(pl.chunk_slots, pl.H);
     // 2. dp, dz and the weights of the reverse scan
     {
-        auto kern = bwd_dz_kernel<T, M>;
+        auto kern = chunk_dz_kernel<T, M>;
         const size_t lds = DzLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
-        KernelTimer kt(kSlotBwdDz, st);
-        hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, (const T *)v,
-                           (const T *)dO, g, z, (const T *)w.S, pl.scale, w.dz, w.dgf, (T *)w.Wr);
+        KernelTimer kt(kSlotChunkDz, st);
+        hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_v, pl.scale, (const T *)v,
+                           (const T *)dO, g, z, (const T *)w.S, pl.layS_bwd, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT);
         GSA_HIP_TRY(hipGetLastError());
     }
     // 3. reverse scan of the memory gradient
     {
-        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true};
+        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true, pl.layE, pl.laySF};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
-    // 4. everything chunk-local
+    // 4. everything chunk-local except the wide contractions
     {
-        auto kern = bwd_main_kernel<T, M>;
-        const size_t lds = MainLds<T, M>::bytes;
+        auto kern = chunk_intra_kernel<T, M>;
+        const size_t lds = IntraLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
-        KernelTimer kt(kSlotBwdMain, st);
-        hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
-                           (const T *)k, (const T *)v, (const T *)dO, g, z, w.dz, w.dgf, (const T *)w.S, (const T *)w.SF,
-                           (const T *)w.E, (T *)dq,
-                           (T *)dk, (T *)dv, dg);
+        IntraArgs<T> a;
+        a.q = (const T *)q; a.k = (const T *)k; a.v = (const T *)v;
+        a.g = g; a.z = z; a.dz = w.dz; a.dgf = w.dgf;
+        a.S = (const T *)w.S; a.SF = (const T *)w.SF; a.E = (const T *)w.E;
+        a.layS = pl.layS_bwd; a.laySF = pl.laySF; a.layE = pl.layE;
+        a.tAvT = (const T *)w.tAvT;
+        a.dg = dg;
+        a.tB = (T *)w.tA; a.tBT = (T *)w.tBT; a.tA2T = (T *)w.tA2T; a.tDZe = (T *)w.tP; a.tSbe = (T *)w.tSbe;
+        KernelTimer kt(kSlotChunkIntra, st);
+        hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, a);
         GSA_HIP_TRY(hipGetLastError());
     }
-    return hipSuccess;
+    // 5. dq, dk, dv
+    const ApplyIo io[3] = {
+        {w.tA, w.tP, k, w.S, pl.layS_bwd.oKt, pl.layS_bwd.stride, dq, pl.d_k, pl.scale, pl.scale},
+        {w.tBT, w.tSbe, q, w.E, pl.layE.oKt, pl.layE.stride, dk, pl.d_k, pl.scale, 1.f},
+        {w.tA2T, w.tSbe, dO, w.E, pl.layE.oVt, pl.layE.stride, dv, pl.d_v, 1.f, 1.f},
+    };
+    return launch_apply(pl, w, io, 3, kSlotApplyBwd, st);
 }
 
 template <typename T>

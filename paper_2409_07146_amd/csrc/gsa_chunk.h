@@ -44,16 +44,17 @@ __device__ __forceinline__ bool block_unsafe(const float *Gs, int ldg, int rowb,
 // i.e. the inter-chunk plus intra-chunk parts of one gated pass whose gate sits on the
 // slot side (pass 1 of Eq. (gsa-2pass) with X=q, Y=k, St=Kt; its mirror in the backward
 // with X=dO, Y=v, St=Vt).  X, Y: [len][d] rows in global memory (row stride ldx elements);
-// St: [M][d] rows of T (stride ldst).  LDS: Gs, Ss filled by gate_prep; As [C][lda] is
-// left holding the causally masked X Y^T rounded to T; Xs, Ys [C][ldq] and Sts [M][ldq]
-// are staging for d-slices of KS columns.  All threads of the workgroup must call it.
-template <typename T, int M, int C, int KS>
+// St: [M][d] rows of T (stride ldst).  The contraction over d reads its operand fragments
+// straight from global memory (each lane 16 bytes of one row; no LDS, no barriers), so the
+// loads of many k-steps and of several resident workgroups are in flight together.
+// LDS: Gs, Ss filled by gate_prep; As [C][lda] is left holding the causally masked X Y^T
+// rounded to T.  All threads of the workgroup must call it.
+template <typename T, int M, int C>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, const float *Gs, const float *Ss,
-                                             int ldg, T *As, int lda, T *Xs, T *Ys, T *Sts, int ldq, const T *X,
-                                             const T *Y, size_t ldx, int d, const T *St, size_t ldst, int len,
-                                             int tid)
+                                             int ldg, T *As, int lda, const T *X, const T *Y, size_t ldx, int d,
+                                             const T *St, size_t ldst, int len, int tid)
 {
-    constexpr int MI = M / 16, CI = C / 16, NT = Geo<T>::NT;
+    constexpr int MI = M / 16, CI = C / 16;
     const int lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const int rowb = 16 * w;
@@ -63,21 +64,20 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
     for (int ni = 0; ni < CI; ++ni) accA[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) accZ[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < d; ks += KS) {
-        stage_rows<T, T>(Xs, ldq, X + ks, ldx, C, KS, len, tid, NT);
-        stage_rows<T, T>(Ys, ldq, Y + ks, ldx, C, KS, len, tid, NT);
-        stage_rows<T, T>(Sts, ldq, St + ks, ldst, M, KS, M, tid, NT);
-        __syncthreads();
-#pragma unroll
-        for (int k0 = 0; k0 < KS; k0 += 32) {
-            const typename Atom<T>::Frag a = Atom<T>::load(Xs + (rowb + r) * ldq + k0 + g8);
+    {
+        const T *xa = X + (size_t)(rowb + r) * ldx + g8;
+        const bool la = rowb + r < len;
+#pragma unroll 2
+        for (int k0 = 0; k0 < d; k0 += 32) {
+            const typename Atom<T>::Frag a = gfrag<T>(xa + k0, la);
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni)
-                if (ni <= w) Atom<T>::mma(accA[ni], a, Atom<T>::load(Ys + (ni * 16 + r) * ldq + k0 + g8));
+                if (ni <= w)
+                    Atom<T>::mma(accA[ni], a, gfrag<T>(Y + (size_t)(ni * 16 + r) * ldx + k0 + g8, ni * 16 + r < len));
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(accZ[ni], a, Atom<T>::load(Sts + (ni * 16 + r) * ldq + k0 + g8));
+            for (int ni = 0; ni < MI; ++ni)
+                Atom<T>::mma(accZ[ni], a, Atom<T>::load(St + (size_t)(ni * 16 + r) * ldst + k0 + g8));
         }
-        __syncthreads();
     }
     // causally masked X Y^T, as an operand
 #pragma unroll
@@ -169,9 +169,9 @@ __device__ __forceinline__ void pair_weights(f32x4 (&acc)[C / 16], const T *Wa, 
 
 // Diagonal atom of the pair-weight matrix without factoring:
 //   out[j] = sum_i Wf[t][i] s_r[i] exp(G_t[i] - G_r[i])   for r = rowb + lane%16 <= t, else 0
-// Wf: fp32 LDS tile [C][ldw] of the ungated weights.
-template <int M>
-__device__ __forceinline__ f32x4 pair_weights_exact(const float *Wf, int ldw, const float *Gs, const float *Ss, int ldg,
+// Wf: LDS tile [C][ldw] of the ungated weights (fp32 or T).
+template <int M, typename TW>
+__device__ __forceinline__ f32x4 pair_weights_exact(const TW *Wf, int ldw, const float *Gs, const float *Ss, int ldg,
                                                     int lane, int rowb)
 {
     const int r = lane & 15, g4 = (lane >> 4) * 4;
@@ -183,7 +183,7 @@ __device__ __forceinline__ f32x4 pair_weights_exact(const float *Wf, int ldw, co
         if (rr > t) continue;
         float sum = 0.f;
         for (int i = 0; i < M; ++i)
-            sum += Wf[t * ldw + i] * Ss[rr * ldg + i] * __expf(Gs[t * ldg + i] - Gs[rr * ldg + i]);
+            sum += to_f32(Wf[t * ldw + i]) * Ss[rr * ldg + i] * __expf(Gs[t * ldg + i] - Gs[rr * ldg + i]);
         out[j] = sum;
     }
     return out;

@@ -10,6 +10,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "gsa_layout.h"
+
 namespace gsa {
 
 typedef __bf16 bf16_t;
@@ -288,6 +290,62 @@ __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *
     }
     __syncthreads();
 }
+
+// Fragment straight from global memory: 8 consecutive elements of one row; zero if !live.
+template <typename T>
+__device__ __forceinline__ typename Atom<T>::Frag gfrag(const T *p, bool live)
+{
+    if (live) return Atom<T>::load(p);
+    return Atom<T>::zero();
+}
+
+// ----------------------------------------------------------------------------
+// Transposed token tile in LDS: XT[c][t] for c < ncols, t < C, row stride C + kPad,
+// with the 8-token blocks of row c XOR-swizzled by (c/8) so that the transposing writes
+// (one thread owns two adjacent tokens of 8 consecutive columns) spread over all banks
+// and fragment reads stay 16-byte aligned.
+// ----------------------------------------------------------------------------
+template <int C> __device__ __forceinline__ int xt_off(int c, int t, int ld)
+{
+    constexpr int NB = C / 8;
+    return c * ld + ((((t >> 3) ^ (c >> 3)) & (NB - 1)) << 3) + (t & 7);
+}
+
+// Token tile held in registers between the global load and the transposing LDS write.
+// The tile is C tokens x NCOLS columns; thread (tid) owns row pairs and 8-column groups.
+template <typename T, int C, int NCOLS, int NT> struct TokTile {
+    static constexpr int NVEC = (C / 2) * (NCOLS / 8);          // (row pair, column group) items
+    static constexpr int PER = (NVEC + NT - 1) / NT;
+    Raw8<T> a[PER], b[PER];
+    // src: row 0 of the tile, column 0 of the slice; rows >= len read as zero; columns >= ncols skipped
+    __device__ __forceinline__ void load(const T *src, size_t gld, int len, int ncols, int tid)
+    {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int idx = tid + NT * u;
+            const int rp = idx / (NCOLS / 8), cg = idx - rp * (NCOLS / 8);
+            const bool ok = idx < NVEC && cg * 8 < ncols;
+            if (ok && 2 * rp < len) a[u].load(src + (size_t)(2 * rp) * gld + cg * 8); else a[u].zero();
+            if (ok && 2 * rp + 1 < len) b[u].load(src + (size_t)(2 * rp + 1) * gld + cg * 8); else b[u].zero();
+        }
+    }
+    __device__ __forceinline__ void store_transposed(T *XT, int ld, int ncols, int tid) const
+    {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int idx = tid + NT * u;
+            const int rp = idx / (NCOLS / 8), cg = idx - rp * (NCOLS / 8);
+            if (idx < NVEC && cg * 8 < ncols) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    T *dst = XT + xt_off<C>(cg * 8 + e, 2 * rp, ld);
+                    dst[0] = a[u].get(e);
+                    dst[1] = b[u].get(e);
+                }
+            }
+        }
+    }
+};
 
 // Reduce over the 16 lanes that share l/16 (the 16 columns of one D-tile row).
 __device__ __forceinline__ float row16_max(float x)

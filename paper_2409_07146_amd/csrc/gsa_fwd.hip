@@ -3,16 +3,18 @@
 //
 // Both slot memories decay with the same gate and are written with the same
 // intensity, so they are carried as ONE memory S = [Kt | Vt] of shape
-// [m x (d_k+d_v)]:
+// [m x (d_k+d_v)].  Kernels of one forward call:
 //
 //   gate_kernel +     (gsa_scan.hip) one workgroup per (sequence, head, column slice of S)
 //   scan_kernel       walks the chunks in order, keeps its slice of S in matrix-core
 //                     accumulators and writes the memory at the START of every chunk to the
 //                     workspace (the only sequential part; column slices are independent).
-//   out_fwd_kernel    one workgroup per (chunk, head): pass-1 scores z (inter-chunk term
-//                     from the stored memory + gated intra-chunk term), softmax over the
-//                     slots in registers, pass-2 output o.  z and p never round-trip HBM
-//                     except for the z the backward needs.
+//   chunk_fwd_kernel  one workgroup per (chunk, head): pass-1 scores z (inter-chunk term from
+//                     the stored memory + gated intra-chunk term), softmax over the slots in
+//                     registers, and the two small matrices of pass 2: p*exp(G) [C x m] and
+//                     the pair weights A2 [C x C].  z and p never round-trip HBM except for
+//                     the z the backward needs.
+//   apply_kernel      (gsa_apply.hip) o = (p e^G) Vt_start + A2 V, the wide contraction.
 //
 // Gate handling inside a chunk: rows are grouped in blocks of 16 tokens.  For row block I
 // the reference is the cumulative log gate just before the block, Gref_I.  exp(G_t - G_r)
@@ -74,85 +76,60 @@ hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------------
-// Chunk-parallel output kernel.
+// Chunk kernel of the forward: scores, softmax, pass-2 weights.
 // ---------------------------------------------------------------------------------------
-template <typename T, int M> struct OutLds {
+template <typename T, int M> struct ChunkFwdLds {
     static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
-    static constexpr int KM = (M < 32) ? 32 : M;                // slots padded to the contraction depth
-    static constexpr int KS = (sizeof(T) == 2) ? 64 : 32;       // d_k slice streamed per step
-    static constexpr int NS = 64;                               // d_v slice per output step
+    static constexpr int KM = (M < 32) ? 32 : M;   // slots padded to the contraction depth
     static constexpr int ldg = M + 4;
-    static constexpr int lda = C + PAD;        // As, VT
-    static constexpr int ldp = KM + PAD;       // Ps, SvT
-    static constexpr int ldq = KS + PAD;       // Qs, Ks, Sts
-    static constexpr int ldo = NS + PAD;       // Os
+    static constexpr int lda = C + PAD;            // As
+    static constexpr int ldp = KM + PAD;           // Ps
     static constexpr size_t oG = 0;
     static constexpr size_t oS = oG + sizeof(float) * C * ldg;
     static constexpr size_t oA = oS + sizeof(float) * C * ldg;
-    static constexpr size_t oP = oA + sizeof(T) * C * lda;
-    static constexpr size_t oU = oP + sizeof(T) * C * ldp;
-    // gate_prep's scratch (dead before the first staging write)
-    static constexpr size_t oTot = oU;
-    // phase 1 view of the union
-    static constexpr size_t oQ = oU;
-    static constexpr size_t oK = oQ + sizeof(T) * C * ldq;
-    static constexpr size_t oSt = oK + sizeof(T) * C * ldq;
-    static constexpr size_t end1 = oSt + sizeof(T) * M * ldq;
-    // phase 2 view (only when a block takes the unfactored path): fp32 softmax weights
-    static constexpr size_t oPf = oU;
-    static constexpr size_t end2 = oPf + sizeof(float) * C * ldg;
-    // phase 4 view of the union
-    static constexpr size_t oSvT = oU;
-    static constexpr size_t oVT = oSvT + sizeof(T) * NS * ldp;
-    static constexpr size_t oO = oVT + sizeof(T) * NS * lda;
-    static constexpr size_t end4 = oO + sizeof(T) * C * ldo;
-    static constexpr size_t e12 = end1 > end2 ? end1 : end2;
-    static constexpr size_t bytes = e12 > end4 ? e12 : end4;
+    static constexpr size_t oTot = oA;             // gate_prep's scratch, dead before As is written
+    static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
+                                                                                  : sizeof(float) * Geo<T>::NT;
+    static constexpr size_t oP = oA + szA;
+    static constexpr size_t bytes = oP + sizeof(T) * C * ldp;
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
-                                                             const T *__restrict__ q, const T *__restrict__ k,
-                                                             const T *__restrict__ v, const float *__restrict__ g,
-                                                             const T *__restrict__ S, T *__restrict__ o,
-                                                             float *__restrict__ z_saved)
+__global__ __launch_bounds__(Geo<T>::NT) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
+                                                               const T *__restrict__ q, const T *__restrict__ k,
+                                                               const float *__restrict__ g,
+                                                               const T *__restrict__ S, StateLayout lay,
+                                                               float *__restrict__ z_saved, T *__restrict__ tA,
+                                                               T *__restrict__ tP)
 {
-    using L = OutLds<T, M>;
-    constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
-    constexpr int MI = M / 16, CI = C / 16;
-    constexpr int NIo = L::NS / (16 * NW);     // output column atoms per wave
+    using L = ChunkFwdLds<T, M>;
+    constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
+    constexpr int MI = M / 16, CI = C / 16, KM = L::KM;
     extern __shared__ __align__(16) unsigned char smem[];
     float *Gs = reinterpret_cast<float *>(smem + L::oG);
     float *Ss = reinterpret_cast<float *>(smem + L::oS);
     float *tot = reinterpret_cast<float *>(smem + L::oTot);
     T *As = reinterpret_cast<T *>(smem + L::oA);      // [C][lda]  A = QK^T masked, later A2
-    T *Ps = reinterpret_cast<T *>(smem + L::oP);      // [C][ldp]  gated softmax weights
-    T *Qs = reinterpret_cast<T *>(smem + L::oQ);
-    T *Ks = reinterpret_cast<T *>(smem + L::oK);
-    T *Sts = reinterpret_cast<T *>(smem + L::oSt);
-    float *Pf = reinterpret_cast<float *>(smem + L::oPf);
-    T *SvT = reinterpret_cast<T *>(smem + L::oSvT);
-    T *VT = reinterpret_cast<T *>(smem + L::oVT);
-    T *Os = reinterpret_cast<T *>(smem + L::oO);
+    T *Ps = reinterpret_cast<T *>(smem + L::oP);      // [C][ldp]  softmax weights in their gated forms
 
     ChunkInfo ci;
     if (!chunk_lookup(cm, blockIdx.x, ci)) return;
     const int h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4;
-    const int D = d_k + d_v;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const T *Sc = S + (((size_t)blockIdx.x * H + h) * M) * D;       // memory at chunk start [M][D]
-    const int rowb = 16 * w;                                        // this wave's row block
+    const size_t ch = (size_t)blockIdx.x * H + h;
+    const T *Kn = S + ch * lay.stride + lay.oKn;      // key memory at chunk start [M][d_k]
+    const int rowb = 16 * w;                          // this wave's row block
 
     gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
 
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
     float p[MI][4];
     bool unsafe;
-    gated_scores<T, M, C, L::KS>(p, unsafe, Gs, Ss, L::ldg, As, L::lda, Qs, Ks, Sts, L::ldq, q + tokh * d_k,
-                                 k + tokh * d_k, (size_t)H * d_k, d_k, Sc, (size_t)D, ci.len, tid);
+    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, As, L::lda, q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k,
+                          d_k, Kn, (size_t)d_k, ci.len, tid);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
@@ -177,7 +154,25 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
         for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(p[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
-    // ---- pass 2 weights: P-bar = p * exp(G - Gref) as the operand of the pair-weight contraction
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p[ni][j] *= rsum[j];
+    if (M < KM) {   // zero the padded slot columns once
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Ps[(rowb + g4 + j) * L::ldp + M + r] = from_f32<T>(0.f);
+    }
+    // ---- pass-2 pair weights A2[t][r] = sum_i p_t[i] s_r[i] exp(G_t[i] - G_r[i]), r <= t
+    f32x4 exact = {0.f, 0.f, 0.f, 0.f};
+    if (__syncthreads_or(unsafe)) {   // rare: some row block needs its diagonal unfactored
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Ps[(rowb + g4 + j) * L::ldp + ni * 16 + r] = from_f32<T>(p[ni][j]);
+        __syncthreads();
+        if (unsafe) exact = pair_weights_exact<M, T>(Ps, L::ldp, Gs, Ss, L::ldg, lane, rowb);
+        __syncthreads();
+    }
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) {
         const int i = ni * 16 + r;
@@ -185,29 +180,21 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
-            p[ni][j] *= rsum[j];
             Ps[t * L::ldp + i] = from_f32<T>(p[ni][j] * __expf(Gs[t * L::ldg + i] - gref));
-            if (unsafe) Pf[t * L::ldg + i] = p[ni][j];
         }
-    }
-    if (M < L::KM) {   // zero the padded slot columns
-#pragma unroll
-        for (int j = 0; j < 4; ++j) Ps[(rowb + g4 + j) * L::ldp + M + r] = from_f32<T>(0.f);
     }
     __syncthreads();
     {
-        // A2[t][r] = sum_i p_t[i] s_r[i] exp(G_t[i] - G_r[i]) for r <= t; overwrites this block's rows of As
         f32x4 acc2[CI];
-        pair_weights<T, M, C, L::KM>(acc2, Ps, L::ldp, Gs, Ss, L::ldg, unsafe, lane, w);
+        pair_weights<T, M, C, KM>(acc2, Ps, L::ldp, Gs, Ss, L::ldg, unsafe, lane, w);
         if (unsafe) {
-            const f32x4 ex = pair_weights_exact<M>(Pf, L::ldg, Gs, Ss, L::ldg, lane, rowb);
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni)
-                if (ni == w) acc2[ni] = ex;
+                if (ni == w) acc2[ni] = exact;
         }
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) {
-            if (ni > w) continue;
+            if (ni > w) continue;   // those columns already hold zeros from the masked A
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int t = rowb + g4 + j, rr = ni * 16 + r;
@@ -215,7 +202,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
             }
         }
     }
-    // inter-chunk pass-2 weights p * exp(G)
+    // inter-chunk pass-2 weights p * exp(G) (this wave's rows of Ps were read by this wave only)
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) {
         const int i = ni * 16 + r;
@@ -226,34 +213,21 @@ __global__ __launch_bounds__(Geo<T>::NT) void out_fwd_kernel(ChunkMap cm, int H,
         }
     }
     __syncthreads();
-
-    // ---- o = [p exp(G) | A2] [Vt ; V], streamed over d_v (Eq. (gla-chunk) with the gate on the slot/key side)
-    for (int cs = 0; cs < d_v; cs += L::NS) {
-        const int ncols = min(L::NS, d_v - cs);
-        stage_cols<T, T>(SvT, L::ldp, Sc + d_k + cs, (size_t)D, M, ncols, M, tid, NT);
-        if (M < L::KM) {
-            for (int idx = tid; idx < ncols * (L::KM - M); idx += NT)
-                SvT[(idx / (L::KM - M)) * L::ldp + M + idx % (L::KM - M)] = from_f32<T>(0.f);
+    // ---- hand the two small matrices to the apply kernel
+    {
+        T *dA = tA + ch * C * C, *dP = tP + ch * C * KM;
+        for (int idx = tid; idx < C * C / 8; idx += NT) {
+            const int t = idx / (C / 8), c8 = (idx - t * (C / 8)) * 8;
+            Raw8<T> x;
+            x.load(As + t * L::lda + c8);
+            x.store(dA + t * C + c8);
         }
-        stage_cols<T, T>(VT, L::lda, v + tokh * d_v + cs, (size_t)H * d_v, C, ncols, ci.len, tid, NT);
-        __syncthreads();
-        const int wcol = 16 * NIo * w;
-        if (wcol < ncols) {
-            f32x4 acc[CI][NIo];
-            zero_acc(acc);
-            gemm_nt<T, CI, NIo>(acc, Ps, L::ldp, SvT + wcol * L::ldp, L::ldp, L::KM, lane);
-            gemm_nt<T, CI, NIo>(acc, As, L::lda, VT + wcol * L::lda, L::lda, C, lane);
-#pragma unroll
-            for (int mi = 0; mi < CI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NIo; ++ni)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+        for (int idx = tid; idx < C * KM / 8; idx += NT) {
+            const int t = idx / (KM / 8), c8 = (idx - t * (KM / 8)) * 8;
+            Raw8<T> x;
+            x.load(Ps + t * L::ldp + c8);
+            x.store(dP + t * KM + c8);
         }
-        __syncthreads();
-        store_tile<T>(o + tokh * d_v + cs, (size_t)H * d_v, Os, L::ldo, C, ncols, ci.len, tid, NT);
-        __syncthreads();
     }
 }
 
@@ -267,16 +241,22 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
 {
     const ChunkMap cm = make_chunk_map(pl, w);
     GSA_HIP_TRY(launch_gates(pl, w, g, st));
-    const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false};
-    GSA_HIP_TRY(launch_scan(pl, w, io, st));
-    auto kern = out_fwd_kernel<T, M>;
-    const size_t lds = OutLds<T, M>::bytes;
-    GSA_HIP_TRY(allow_lds(kern, lds));
-    dim3 grid(pl.chunk_slots, pl.H);
-    KernelTimer kt(kSlotOutFwd, st);
-    hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, (const T *)q,
-                       (const T *)k, (const T *)v, g, (const T *)w.S, (T *)o, z_saved);
-    return hipGetLastError();
+    {
+        const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false, pl.layS_fwd, pl.laySF};
+        GSA_HIP_TRY(launch_scan(pl, w, io, st));
+    }
+    {
+        auto kern = chunk_fwd_kernel<T, M>;
+        const size_t lds = ChunkFwdLds<T, M>::bytes;
+        GSA_HIP_TRY(allow_lds(kern, lds));
+        dim3 grid(pl.chunk_slots, pl.H);
+        KernelTimer kt(kSlotChunkFwd, st);
+        hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.scale, (const T *)q,
+                           (const T *)k, g, (const T *)w.S, pl.layS_fwd, z_saved, (T *)w.tA, (T *)w.tP);
+        GSA_HIP_TRY(hipGetLastError());
+    }
+    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.layS_fwd.oVt, pl.layS_fwd.stride, o, pl.d_v, 1.f, 1.f};
+    return launch_apply(pl, w, &io, 1, kSlotApplyFwd, st);
 }
 
 template <typename T>

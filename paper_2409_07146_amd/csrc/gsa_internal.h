@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "gsa_layout.h"
+
 namespace gsa {
 
 // Everything a launcher needs to know about one problem, resolved on the host.
@@ -16,27 +18,36 @@ struct Plan {
     int32_t chunk;              // tokens per chunk for this dtype
     int32_t chunk_slots;        // upper bound on chunks (exact in batch form)
     // workspace offsets in bytes (256-byte aligned); 0-sized parts share an offset
-    size_t off_table, off_seqtab, off_Wf, off_dec, off_S, off_SF, off_Wr, off_E, off_dz, off_dgf, total_fwd,
-        total_bwd;
+    size_t off_table, off_seqtab, off_Wf, off_dec, off_S, off_tA, off_tP, total_fwd;
+    size_t off_SF, off_Wr, off_E, off_dz, off_dgf, off_tB, off_tBT, off_tA2T, off_tAvT, off_tSbe, total_bwd;
+    // layouts of the memory snapshots (elements); see gsa_layout.h
+    StateLayout layS_fwd, layS_bwd, layE, laySF;
 };
 
 // Workspace views handed to the launchers.
 struct Work {
     int32_t *table;   // [4*chunk_slots] packed form only
     int32_t *seqtab;  // [4*n_seqs]     packed form only
-    void *Wf;         // [chunk_slots][H][m][C]    forward scan weights s*exp(G_C-G)          (I/O dtype)
-    float *dec;       // [chunk_slots][H][m]       chunk decay exp(G_C)
-    void *S;          // [chunk_slots][H][m][d_k+d_v] memories at the start of each chunk     (I/O dtype)
-    void *SF;         // [n_seqs][H][m][d_k+d_v]   memories after the last token (backward)   (I/O dtype)
-    void *Wr;         // [chunk_slots][H][2][m][C] reverse scan weights                       (I/O dtype)
-    void *E;          // same shape as S: gradient of the memories at the end of each chunk   (I/O dtype)
-    float *dz;        // [tokens][H][m]
-    float *dgf;       // [tokens][H][m]
+    // per (chunk, head) records, element type = I/O dtype unless noted; KM = max(m, 32)
+    void *Wf;         // [m][C]      forward scan weights s*exp(G_C-G)
+    float *dec;       // [m]         chunk decay exp(G_C)                                  (fp32)
+    void *S;          // memory at the start of the chunk, blocks per Plan::layS_fwd / layS_bwd
+    void *tA;         // [C][C]      forward: pair weights A2;  backward: Bm
+    void *tP;         // [C][KM]     forward: p*exp(G);         backward: dz*exp(G)
+    void *SF;         // per (sequence, head): memory after the last token (Plan::laySF)
+    void *Wr;         // [2][m][C]   reverse scan weights
+    void *E;          // gradient of the memory at the end of the chunk (Plan::layE)
+    void *tBT;        // [C][C]      Bm^T
+    void *tA2T;       // [C][C]      A2^T
+    void *tAvT;       // [C][C]      (dO_t . v_r)^T, causally masked
+    void *tSbe;       // [C][KM]     s*exp(G_C-G)
+    float *dz;        // [tokens][H][m]                                                     (fp32)
+    float *dgf;       // [tokens][H][m]   z*dz + p*dp                                       (fp32)
 };
 
 // Kernel slots of the optional per-kernel event timing (gsa_profile_*).
-enum KernelSlot { kSlotPrepare = 0, kSlotGates, kSlotScanFwd, kSlotOutFwd, kSlotBwdDz, kSlotScanBwd, kSlotBwdMain,
-                  kSlotDecode, kNumKernelSlots };
+enum KernelSlot { kSlotPrepare = 0, kSlotGates, kSlotScanFwd, kSlotChunkFwd, kSlotApplyFwd, kSlotChunkDz, kSlotScanBwd,
+                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kNumKernelSlots };
 
 // Brackets one kernel launch with events on its stream when timing is enabled; otherwise a no-op.
 class KernelTimer {
@@ -66,8 +77,22 @@ struct ScanIo {
     float *outK, *outV;
     void *outJ;
     bool reverse;
+    StateLayout lay;    // layout of the per-chunk snapshots
+    StateLayout layJ;   // layout of outJ
 };
 hipError_t launch_scan(const Plan &pl, const Work &w, const ScanIo &io, hipStream_t st);
+
+// The wide contractions out = s_tok * A_tok X + s_slot * A_slot St for up to three outputs in one
+// launch (see gsa_apply.hip).  xslot_rec + xslot_off points at a transposed memory block [d][m] of
+// the first (chunk, head) record; records are xslot_stride elements apart.
+struct ApplyIo {
+    const void *A_tok, *A_slot, *xtok, *xslot_rec;
+    long long xslot_off, xslot_stride;
+    void *out;
+    int d;
+    float s_tok, s_slot;
+};
+hipError_t launch_apply(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st);
 
 hipError_t launch_fwd(const Plan &pl, const Work &w, const void *q, const void *k, const void *v, const float *g,
                       const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,

@@ -20,8 +20,9 @@ struct Slot {
     double ms = 0.0;
     int64_t launches = 0;
 };
-Slot g_slots[kNumKernelSlots] = {{"prepare_kernel"}, {"gate_kernel"}, {"scan_fwd_kernel"}, {"out_fwd_kernel"}, {"bwd_dz_kernel"},
-                                 {"scan_bwd_kernel"}, {"bwd_main_kernel"}, {"decode_kernel"}};
+Slot g_slots[kNumKernelSlots] = {{"prepare_kernel"}, {"gate_kernel"},      {"scan_fwd_kernel"}, {"chunk_fwd_kernel"},
+                                 {"apply_fwd_kernel"}, {"chunk_dz_kernel"}, {"scan_bwd_kernel"}, {"chunk_intra_kernel"},
+                                 {"apply_bwd_kernel"}, {"decode_kernel"}};
 
 hipEvent_t take_event(Slot &s)
 {

@@ -56,9 +56,11 @@ template <typename T> struct ScanArgs {
     const float *dec;      // [chunk][H][M]
     const T *xk, *xv;      // token tensors feeding the key / value columns
     const float *initK, *initV;   // [n_seqs][H][M][d] or NULL
-    T *snap;               // [chunk][H][M][D]
+    T *snap;               // per (chunk, head) record laid out by `lay`
+    StateLayout lay;
     float *outK, *outV;    // [n_seqs][H][M][d] or NULL: acc after the last chunk
-    T *outJ;               // [n_seqs][H][M][D] or NULL: the same, joint layout, element type T
+    T *outJ;               // per (sequence, head) record laid out by `layJ`, or NULL: the same, element type T
+    StateLayout layJ;
 };
 
 template <typename T, int M, int NS> struct ScanLds {
@@ -66,10 +68,12 @@ template <typename T, int M, int NS> struct ScanLds {
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int ldw = C + PAD;      // We [M][ldw], XT [NS][ldw]
     static constexpr int lds = NS + PAD;     // snapshot tile [M][lds]
+    static constexpr int ldt = M + PAD;      // transposed snapshot tile [NS][ldt]
     static constexpr size_t oW = 0;
     static constexpr size_t oX = oW + sizeof(T) * M * ldw;
     static constexpr size_t oSn = oX + sizeof(T) * NS * ldw;
-    static constexpr size_t bytes = oSn + sizeof(T) * M * lds;
+    static constexpr size_t oSt = oSn + sizeof(T) * M * lds;
+    static constexpr size_t bytes = oSt + sizeof(T) * NS * ldt;
 };
 
 template <typename T, int M, int NS, bool REVERSE>
@@ -85,6 +89,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
     T *We = reinterpret_cast<T *>(smem + L::oW);
     T *XT = reinterpret_cast<T *>(smem + L::oX);
     T *Sn = reinterpret_cast<T *>(smem + L::oSn);
+    T *St = reinterpret_cast<T *>(smem + L::oSt);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4;
@@ -145,24 +150,44 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
 #pragma unroll
             for (int j = 0; j < 4; ++j) decr[mi][j] = a.dec[ch * M + mi * 16 + g4 + j];
     };
-    auto snapshot_to_lds = [&]() {
+    // accumulator -> LDS in the layouts the record asks for (natural [m][cols], transposed [cols][m])
+    auto snapshot_to_lds = [&](const StateLayout &lay) {
+        const bool nat = (isK ? lay.oKn : lay.oVn) >= 0, tr = (isK ? lay.oKt : lay.oVt) >= 0;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+                for (int j = 0; j < 4; ++j) {
+                    const T x = from_f32<T>(acc[mi][ni][j]);
+                    if (nat) Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = x;
+                    if (tr) St[(wcol + ni * 16 + r) * L::ldt + mi * 16 + g4 + j] = x;
+                }
     };
-    auto snapshot_to_global = [&](T *dst) {   // dst: [M][D] rows, this slice starts at column col0
+    auto snapshot_to_global = [&](T *rec, const StateLayout &lay) {   // rec: start of the (chunk, head) record
+        const long long oN = isK ? lay.oKn : lay.oVn, oT = isK ? lay.oKt : lay.oVt;
+        if (oN >= 0) {
 #pragma unroll
-        for (int u = 0; u < SV; ++u) {
-            const int idx = tid + NT * u;
-            if (idx < SVEC) {
-                const int i = idx / (NS / 8), cg = idx - i * (NS / 8);
-                Raw8<T> x;
-                x.load(Sn + i * L::lds + cg * 8);
-                x.store(dst + (size_t)i * D + col0 + cg * 8);
+            for (int u = 0; u < SV; ++u) {
+                const int idx = tid + NT * u;
+                if (idx < SVEC) {
+                    const int i = idx / (NS / 8), cg = idx - i * (NS / 8);
+                    Raw8<T> x;
+                    x.load(Sn + i * L::lds + cg * 8);
+                    x.store(rec + oN + (size_t)i * dsrc + c0 + cg * 8);
+                }
+            }
+        }
+        if (oT >= 0) {
+#pragma unroll
+            for (int u = 0; u < SV; ++u) {
+                const int idx = tid + NT * u;
+                if (idx < SVEC) {
+                    const int c = idx / (M / 8), ig = idx - c * (M / 8);
+                    Raw8<T> x;
+                    x.load(St + c * L::ldt + ig * 8);
+                    x.store(rec + oT + (size_t)(c0 + c) * M + ig * 8);
+                }
             }
         }
     };
@@ -188,7 +213,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
                 for (int e = 0; e < 8; ++e) XT[(cg * 8 + e) * L::ldw + row] = xreg[u].get(e);
             }
         }
-        snapshot_to_lds();
+        snapshot_to_lds(a.lay);
         float dcur[MI][4];
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
@@ -196,7 +221,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
             for (int j = 0; j < 4; ++j) dcur[mi][j] = decr[mi][j];
         __syncthreads();
         if (it + 1 < nch) fetch(REVERSE ? n - 1 : n + 1);
-        snapshot_to_global(a.snap + (((size_t)(chunk0 + n) * H + h) * M) * D);
+        snapshot_to_global(a.snap + ((size_t)(chunk0 + n) * H + h) * a.lay.stride, a.lay);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -220,9 +245,9 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
                 }
     }
     if (a.outJ) {
-        snapshot_to_lds();
+        snapshot_to_lds(a.layJ);
         __syncthreads();
-        snapshot_to_global(a.outJ + (((size_t)s * H + h) * M) * D);
+        snapshot_to_global(a.outJ + ((size_t)s * H + h) * a.layJ.stride, a.layJ);
     }
 }
 
@@ -277,9 +302,11 @@ static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io
     a.initK = io.initK;
     a.initV = io.initV;
     a.snap = static_cast<T *>(io.reverse ? w.E : w.S);
+    a.lay = io.lay;
     a.outK = io.outK;
     a.outV = io.outV;
     a.outJ = static_cast<T *>(io.outJ);
+    a.layJ = io.layJ;
     // 128-column slices when both widths allow it and the grid still covers the chip
     const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
                       ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
