@@ -86,7 +86,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_dz_kernel(ChunkMap cm, int H
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
-            zv[ni][j] = (t < ci.len) ? z[(tokh + (size_t)t * H) * M + ni * 16 + r] : 0.f;
+            zv[ni][j] = z[(tokh + (size_t)min(t, ci.len - 1) * H) * M + ni * 16 + r];   // clamped, never stored past len
             rmax[j] = fmaxf(rmax[j], zv[ni][j]);
         }
 #pragma unroll
@@ -245,39 +245,70 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, in
     float cpart[NCP];
 #pragma unroll
     for (int u = 0; u < NCP; ++u) cpart[u] = 0.f;
-    const bool la = rowb + r < ci.len;
     {
-        const T *qa = a.q + (tokh + (size_t)(rowb + r) * H) * d_k + g8;
-        const T *ka = a.k + (tokh + (size_t)(rowb + r) * H) * d_k + g8;
-#pragma unroll 2
-        for (int k0 = 0; k0 < d_k; k0 += 32) {
-            const typename Atom<T>::Frag aQ = gfrag<T>(qa + k0, la);
-            const typename Atom<T>::Frag aK = gfrag<T>(ka + k0, la);
+        // Double-buffered: the fragments of the next 32 columns are in flight while these multiply.
+        // Token rows past the end of a ragged chunk are read as copies of its last row (finite; they
+        // only feed rows that are never stored or that meet zero weights).
+        typedef typename Atom<T>::Frag Frag;
+        const size_t rown = (size_t)min(rowb + r, ci.len - 1) * H;
+        size_t rowy[CI];
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni)
-                if (ni <= w)
-                    Atom<T>::mma(accA[ni], aQ,
-                                 gfrag<T>(a.k + (tokh + (size_t)(ni * 16 + r) * H) * d_k + k0 + g8, ni * 16 + r < ci.len));
+        for (int ni = 0; ni < CI; ++ni) rowy[ni] = (size_t)min(ni * 16 + r, ci.len - 1) * H;
+        struct Set { Frag x, y, by[CI], be[MI], bs[NCP]; };
+        auto multiply = [&](const Set &f, bool with_A) {
+            if (with_A) {
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) {
-                const size_t off = (size_t)(ni * 16 + r) * d_k + k0 + g8;
-                const typename Atom<T>::Frag bE = Atom<T>::load(EK + off);
-                Atom<T>::mma(accX[ni], aK, bE);
-                if (ni % NW == w) cpart[ni / NW] += frag_dot<T>(bE, Atom<T>::load(SendK + off));
+                for (int ni = 0; ni < CI; ++ni) Atom<T>::mma(accA[ni], f.x, f.by[ni]);
+            }
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(accX[ni], f.y, f.be[ni]);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni)
+                if (ni % NW == w) cpart[ni / NW] += frag_dot<T>(f.be[ni], f.bs[ni / NW]);
+        };
+        // key half: A = Q K^T, X += K E_k^T, carry += <E_k, S_end,k>
+        {
+            const T *qa = a.q + (tokh + rown) * d_k + g8, *ka = a.k + (tokh + rown) * d_k + g8;
+            auto fetch = [&](int k0, Set &f) {
+                f.x = Atom<T>::load(qa + k0);
+                f.y = Atom<T>::load(ka + k0);
+#pragma unroll
+                for (int ni = 0; ni < CI; ++ni) f.by[ni] = Atom<T>::load(a.k + (tokh + rowy[ni]) * d_k + k0 + g8);
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) {
+                    const size_t off = (size_t)(ni * 16 + r) * d_k + k0 + g8;
+                    f.be[ni] = Atom<T>::load(EK + off);
+                    if (ni % NW == w) f.bs[ni / NW] = Atom<T>::load(SendK + off);
+                }
+            };
+            Set f0, f1;
+            fetch(0, f0);
+            for (int k0 = 0; k0 < d_k; k0 += 64) {
+                fetch(k0 + 32, f1);
+                multiply(f0, true);
+                if (k0 + 64 < d_k) fetch(k0 + 64, f0);
+                multiply(f1, true);
             }
         }
-    }
-    {
-        const T *va = a.v + (tokh + (size_t)(rowb + r) * H) * d_v + g8;
-#pragma unroll 2
-        for (int k0 = 0; k0 < d_v; k0 += 32) {
-            const typename Atom<T>::Frag aV = gfrag<T>(va + k0, la);
+        // value half: X += V E_v^T, carry += <E_v, S_end,v>
+        {
+            const T *va = a.v + (tokh + rown) * d_v + g8;
+            auto fetch = [&](int k0, Set &f) {
+                f.y = Atom<T>::load(va + k0);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) {
-                const size_t off = (size_t)(ni * 16 + r) * d_v + k0 + g8;
-                const typename Atom<T>::Frag bE = Atom<T>::load(EV + off);
-                Atom<T>::mma(accX[ni], aV, bE);
-                if (ni % NW == w) cpart[ni / NW] += frag_dot<T>(bE, Atom<T>::load(SendV + off));
+                for (int ni = 0; ni < MI; ++ni) {
+                    const size_t off = (size_t)(ni * 16 + r) * d_v + k0 + g8;
+                    f.be[ni] = Atom<T>::load(EV + off);
+                    if (ni % NW == w) f.bs[ni / NW] = Atom<T>::load(SendV + off);
+                }
+            };
+            Set f0, f1;
+            fetch(0, f0);
+            for (int k0 = 0; k0 < d_v; k0 += 64) {
+                fetch(k0 + 32, f1);
+                multiply(f0, false);
+                if (k0 + 64 < d_v) fetch(k0 + 64, f0);
+                multiply(f1, false);
             }
         }
     }
@@ -367,7 +398,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, in
                     ds += sum;
                 }
                 const float sv = Ss[rr * L::ldg + i];
-                const float f = (rr < ci.len) ? a.dgf[(tokh + (size_t)rr * H) * M + i] : 0.f;
+                const float fl = a.dgf[(tokh + (size_t)min(rr, ci.len - 1) * H) * M + i];
+                const float f = (rr < ci.len) ? fl : 0.f;
                 dGam[ni][j] = f - sv * ds;
                 ads[ni][j] = (1.f - sv) * ds;
             }

@@ -65,18 +65,36 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) accZ[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
     {
-        const T *xa = X + (size_t)(rowb + r) * ldx + g8;
-        const bool la = rowb + r < len;
-#pragma unroll 2
-        for (int k0 = 0; k0 < d; k0 += 32) {
-            const typename Atom<T>::Frag a = gfrag<T>(xa + k0, la);
+        // Rows past the end of a ragged chunk are read as copies of its last row: they stay finite
+        // and only ever produce rows of the result that are not stored or that meet zero weights.
+        const T *xa = X + (size_t)min(rowb + r, len - 1) * ldx + g8;
+        const T *yb[CI], *sb[MI];
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni)
-                if (ni <= w)
-                    Atom<T>::mma(accA[ni], a, gfrag<T>(Y + (size_t)(ni * 16 + r) * ldx + k0 + g8, ni * 16 + r < len));
+        for (int ni = 0; ni < CI; ++ni) yb[ni] = Y + (size_t)min(ni * 16 + r, len - 1) * ldx + g8;
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni)
-                Atom<T>::mma(accZ[ni], a, Atom<T>::load(St + (size_t)(ni * 16 + r) * ldst + k0 + g8));
+        for (int ni = 0; ni < MI; ++ni) sb[ni] = St + (size_t)(ni * 16 + r) * ldst + g8;
+        typedef typename Atom<T>::Frag Frag;
+        Frag a0, a1, y0[CI], y1[CI], s0[MI], s1[MI];
+        auto fetch = [&](int k0, Frag &fa, Frag (&fy)[CI], Frag (&fs)[MI]) {
+            fa = Atom<T>::load(xa + k0);
+#pragma unroll
+            for (int ni = 0; ni < CI; ++ni) fy[ni] = Atom<T>::load(yb[ni] + k0);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(sb[ni] + k0);
+        };
+        auto multiply = [&](const Frag &fa, const Frag (&fy)[CI], const Frag (&fs)[MI]) {
+#pragma unroll
+            for (int ni = 0; ni < CI; ++ni) Atom<T>::mma(accA[ni], fa, fy[ni]);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(accZ[ni], fa, fs[ni]);
+        };
+        // two register sets: the loads of the next 32 columns are in flight while these multiply
+        fetch(0, a0, y0, s0);
+        for (int k0 = 0; k0 < d; k0 += 64) {   // d is a multiple of 64
+            fetch(k0 + 32, a1, y1, s1);
+            multiply(a0, y0, s0);
+            if (k0 + 64 < d) fetch(k0 + 64, a0, y0, s0);
+            multiply(a1, y1, s1);
         }
     }
     // causally masked X Y^T, as an operand
@@ -217,9 +235,10 @@ __device__ __forceinline__ void softmax_rows(float *Pf, float *Df, int ld, const
     const int t = tid >> 2, sub = tid & 3;
     float zv[Q];
     float mx = -INFINITY;
+    const size_t row = (size_t)min(t, len - 1) * gld;   // clamped: the load is unconditional
 #pragma unroll
     for (int u = 0; u < Q; ++u) {
-        zv[u] = (t < len) ? z[(size_t)t * gld + sub + 4 * u] : 0.f;
+        zv[u] = z[row + sub + 4 * u];
         mx = fmaxf(mx, zv[u]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
@@ -233,8 +252,11 @@ __device__ __forceinline__ void softmax_rows(float *Pf, float *Df, int ld, const
 #pragma unroll
     for (int u = 0; u < Q; ++u) Pf[t * ld + sub + 4 * u] = zv[u] * inv;
     if (Df) {
+        float dv[Q];
 #pragma unroll
-        for (int u = 0; u < Q; ++u) Df[t * ld + sub + 4 * u] = (t < len) ? dz[(size_t)t * gld + sub + 4 * u] : 0.f;
+        for (int u = 0; u < Q; ++u) dv[u] = dz[row + sub + 4 * u];
+#pragma unroll
+        for (int u = 0; u < Q; ++u) Df[t * ld + sub + 4 * u] = (t < len) ? dv[u] : 0.f;
     }
 }
 

@@ -152,6 +152,12 @@ template <> struct Raw8<bf16_t> {
         for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.f;
     }
     __device__ __forceinline__ bf16_t get(int e) const { return v[e]; }
+    __device__ __forceinline__ void keep(bool live) {   // zero unless live, by register select
+        bf16x8 z;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = (bf16_t)0.f;
+        v = live ? v : z;
+    }
 };
 template <> struct Raw8<float> {
     f32x4 lo, hi;
@@ -165,6 +171,11 @@ template <> struct Raw8<float> {
     }
     __device__ __forceinline__ void zero() { lo = f32x4{0.f, 0.f, 0.f, 0.f}; hi = lo; }
     __device__ __forceinline__ float get(int e) const { return e < 4 ? lo[e] : hi[e - 4]; }
+    __device__ __forceinline__ void keep(bool live) {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        lo = live ? lo : z;
+        hi = live ? hi : z;
+    }
 };
 
 // dst[r][c] = src[r][c]   (dst row stride ld)
@@ -270,15 +281,20 @@ __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *
     constexpr int TP = C / P;            // tokens per partition
     static_assert(NT % M == 0 && C % P == 0, "gate_prep partitioning");
     const int i = tid % M, part = tid / M;
+    float gv[TP];
+#pragma unroll
+    for (int tt = 0; tt < TP; ++tt) {   // all loads first, rows clamped into the chunk
+        const int t = part * TP + tt;
+        gv[tt] = g[(size_t)min(t, len - 1) * gld + i];
+    }
     float run = 0.f;
-#pragma unroll 4
+#pragma unroll
     for (int tt = 0; tt < TP; ++tt) {
         const int t = part * TP + tt;
-        float gv = 0.f;
-        if (t < len) gv = fmaxf(g[(size_t)t * gld + i], kGateFloor);
-        run += gv;
+        const float x = (t < len) ? fmaxf(gv[tt], kGateFloor) : 0.f;
+        run += x;
         Gs[t * ldg + i] = run;
-        Ss[t * ldg + i] = (t < len) ? -expm1f(gv) : 0.f;
+        Ss[t * ldg + i] = (t < len) ? -expm1f(x) : 0.f;
     }
     tot[part * M + i] = run;
     __syncthreads();
@@ -291,12 +307,18 @@ __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *
     __syncthreads();
 }
 
-// Fragment straight from global memory: 8 consecutive elements of one row; zero if !live.
+// Fragment straight from global memory: 8 consecutive elements of one row.  Loads in this
+// library are never placed under a data-dependent branch (the compiler would have to wait for
+// each one before leaving the branch, which serialises them): callers clamp the row index into
+// the valid range so the load is always legal, and rows past the end are zeroed by a register
+// select here -- or left as finite duplicates of the last row where they only ever meet zero
+// weights.
 template <typename T>
 __device__ __forceinline__ typename Atom<T>::Frag gfrag(const T *p, bool live)
 {
-    if (live) return Atom<T>::load(p);
-    return Atom<T>::zero();
+    const typename Atom<T>::Frag f = Atom<T>::load(p);
+    const typename Atom<T>::Frag z = Atom<T>::zero();
+    return live ? f : z;
 }
 
 // ----------------------------------------------------------------------------
@@ -322,11 +344,18 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
     {
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
-            const int idx = tid + NT * u;
-            const int rp = idx / (NCOLS / 8), cg = idx - rp * (NCOLS / 8);
-            const bool ok = idx < NVEC && cg * 8 < ncols;
-            if (ok && 2 * rp < len) a[u].load(src + (size_t)(2 * rp) * gld + cg * 8); else a[u].zero();
-            if (ok && 2 * rp + 1 < len) b[u].load(src + (size_t)(2 * rp + 1) * gld + cg * 8); else b[u].zero();
+            int idx = tid + NT * u;
+            const bool in = idx < NVEC;
+            idx = in ? idx : 0;
+            const int rp = idx / (NCOLS / 8);
+            int cg = idx - rp * (NCOLS / 8);
+            const bool ok = in && cg * 8 < ncols;
+            cg = ok ? cg : 0;
+            const int r0 = min(2 * rp, len - 1), r1 = min(2 * rp + 1, len - 1);
+            a[u].load(src + (size_t)r0 * gld + cg * 8);
+            b[u].load(src + (size_t)r1 * gld + cg * 8);
+            a[u].keep(ok && 2 * rp < len);
+            b[u].keep(ok && 2 * rp + 1 < len);
         }
     }
     __device__ __forceinline__ void store_transposed(T *XT, int ld, int ncols, int tid) const

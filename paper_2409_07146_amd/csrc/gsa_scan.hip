@@ -134,16 +134,17 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
 #pragma unroll
         for (int u = 0; u < WV; ++u) {
             const int idx = tid + NT * u;
-            if (idx < WVEC) wreg[u].load(Wg + (size_t)idx * 8);
+            wreg[u].load(Wg + (size_t)(idx < WVEC ? idx : 0) * 8);
         }
         const int len = min(C, ntok - n * C);
         const T *Xg = src + ((size_t)(tok0 + n * C) * H + h) * dsrc + c0;
 #pragma unroll
         for (int u = 0; u < XV; ++u) {
             const int idx = tid + NT * u;
-            const int row = idx / (NS / 8), cg = idx - row * (NS / 8);
-            if (idx < XVEC && row < len) xreg[u].load(Xg + (size_t)row * H * dsrc + cg * 8);
-            else xreg[u].zero();
+            const int vi = idx < XVEC ? idx : 0;
+            const int row = vi / (NS / 8), cg = vi - row * (NS / 8);
+            xreg[u].load(Xg + (size_t)min(row, len - 1) * H * dsrc + cg * 8);   // unconditional, row clamped
+            xreg[u].keep(idx < XVEC && row < len);
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
