@@ -367,6 +367,7 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             if (idx < NVEC && cg * 8 < ncols) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
+                    // two 2-byte stores: measured faster here than one packed 4-byte store
                     T *dst = XT + xt_off<C>(cg * 8 + e, 2 * rp, ld);
                     dst[0] = a[u].get(e);
                     dst[1] = b[u].get(e);

@@ -83,8 +83,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
     using L = ScanLds<T, M, NS>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
     constexpr int MI = M / 16, NI = NS / (16 * NW);
-    constexpr int WVEC = M * C / 8, XVEC = C * NS / 8, SVEC = M * NS / 8;
-    constexpr int WV = (WVEC + NT - 1) / NT, XV = (XVEC + NT - 1) / NT, SV = (SVEC + NT - 1) / NT;
+    constexpr int WVEC = M * C / 8, SVEC = M * NS / 8;
+    constexpr int WV = (WVEC + NT - 1) / NT, SV = (SVEC + NT - 1) / NT;
     extern __shared__ __align__(16) unsigned char smem[];
     T *We = reinterpret_cast<T *>(smem + L::oW);
     T *XT = reinterpret_cast<T *>(smem + L::oX);
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
     T *St = reinterpret_cast<T *>(smem + L::oSt);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 15, g4 = (lane >> 4) * 4;
+    const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const int D = d_k + d_v;
     const int nsl = D / NS;
     // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs; give each
@@ -126,7 +126,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
                 }
     }
 
-    Raw8<T> wreg[WV], xreg[XV];
+    Raw8<T> wreg[WV];
+    TokTile<T, C, NS, NT> xt;   // token tile of the next chunk, transposed (and swizzled) when it enters LDS
     float decr[MI][4];
     auto fetch = [&](int n) {
         const size_t ch = (size_t)(chunk0 + n) * H + h;
@@ -138,14 +139,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
         }
         const int len = min(C, ntok - n * C);
         const T *Xg = src + ((size_t)(tok0 + n * C) * H + h) * dsrc + c0;
-#pragma unroll
-        for (int u = 0; u < XV; ++u) {
-            const int idx = tid + NT * u;
-            const int vi = idx < XVEC ? idx : 0;
-            const int row = vi / (NS / 8), cg = vi - row * (NS / 8);
-            xreg[u].load(Xg + (size_t)min(row, len - 1) * H * dsrc + cg * 8);   // unconditional, row clamped
-            xreg[u].keep(idx < XVEC && row < len);
-        }
+        xt.load(Xg, (size_t)H * dsrc, len, NS, tid);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -205,15 +199,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
                 wreg[u].store(We + i * L::ldw + tg * 8);
             }
         }
-#pragma unroll
-        for (int u = 0; u < XV; ++u) {
-            const int idx = tid + NT * u;
-            if (idx < XVEC) {
-                const int row = idx / (NS / 8), cg = idx - row * (NS / 8);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) XT[(cg * 8 + e) * L::ldw + row] = xreg[u].get(e);
-            }
-        }
+        xt.store_transposed(XT, L::ldw, NS, tid);
         snapshot_to_lds(a.lay);
         float dcur[MI][4];
 #pragma unroll
@@ -229,7 +215,18 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dcur[mi][j];
-        gemm_nt<T, MI, NI>(acc, We, L::ldw, XT + wcol * L::ldw, L::ldw, C, lane);
+#pragma unroll
+        for (int k0 = 0; k0 < C; k0 += 32) {
+            typename Atom<T>::Frag af[MI], bf[NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) af[mi] = Atom<T>::load(We + (mi * 16 + r) * L::ldw + k0 + g8);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) bf[ni] = Atom<T>::load(XT + xt_off<C>(wcol + ni * 16 + r, k0 + g8, L::ldw));
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bf[ni]);
+        }
         __syncthreads();
     }
     // accumulator after the last chunk
@@ -308,9 +305,10 @@ static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io
     a.outV = io.outV;
     a.outJ = static_cast<T *>(io.outJ);
     a.layJ = io.layJ;
-    // 128-column slices when both widths allow it and the grid still covers the chip
+    // 64-column slices put two or more workgroups on a CU so their dependent chains overlap; the wider
+    // slice (fewer re-reads of the gate weights) only pays once the grid is far larger than the chip
     const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
-                      ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 256);
+                      ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 1024);
     if (io.reverse) {
         if (wide) return run_scan<T, M, 128, true>(pl, cm, a, st);
         return run_scan<T, M, 64, true>(pl, cm, a, st);
