@@ -24,6 +24,13 @@ template <> __device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t *p) {
 
 // M: slots.  NV: float4 column groups per lane per row = ceil(max(d_k,d_v) / 256).
 // EARLY_V: issue the value-memory loads before the key-memory arithmetic.
+//
+// Each wave owns M/16 slots (rows of both memories).  It updates its key rows, gets their
+// scores by wave reductions, and folds its value rows into a partial output with a softmax
+// that is local to the wave (its own maximum and sum); the 16 partial outputs are merged at the
+// end with the usual rescaling.  So there is a single barrier, at the end, and no wave waits for
+// another before its stores are issued.  No load sits under a data-dependent branch: column
+// indices past the width are clamped and the lanes masked by register selects.
 template <typename T, int M, int NV, bool EARLY_V>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(int d_k, int d_v, float scale,
                                                              const T *__restrict__ q, const T *__restrict__ k,
@@ -31,9 +38,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(int d_k, int d_v, f
                                                              float *__restrict__ Kst, float *__restrict__ Vst,
                                                              T *__restrict__ o)
 {
-    constexpr int R = (M + kDecWaves - 1) / kDecWaves;  // rows (slots) per wave
+    static_assert(M % kDecWaves == 0, "slots must split evenly over the waves");
+    constexpr int R = M / kDecWaves;  // rows (slots) per wave
     extern __shared__ float smem[];
-    float *zs = smem;                 // [M] scores
+    float *ms = smem;                 // [kDecWaves][2] wave maximum and sum
     float *part = smem + 128;         // [kDecWaves][d_v] partial outputs
 
     const int bh = blockIdx.x;
@@ -43,128 +51,116 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(int d_k, int d_v, f
     const T *qb = q + (size_t)bh * d_k, *kb = k + (size_t)bh * d_k, *vb = v + (size_t)bh * d_v;
     const float *gb = g + (size_t)bh * M;
 
-    f32x4 Kr[R][NV], Vr[R][NV];
-    // ---- issue the memory loads
-#pragma unroll
-    for (int rr = 0; rr < R; ++rr) {
-        const int row = wave * R + rr;
-#pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int col = 4 * (lane + 64 * j);
-            Kr[rr][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (row < M && col < d_k) Kr[rr][j] = *reinterpret_cast<const f32x4 *>(Kb + (size_t)row * d_k + col);
-        }
-    }
-    if (EARLY_V) {
-#pragma unroll
-        for (int rr = 0; rr < R; ++rr) {
-            const int row = wave * R + rr;
-#pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                const int col = 4 * (lane + 64 * j);
-                Vr[rr][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (row < M && col < d_v) Vr[rr][j] = *reinterpret_cast<const f32x4 *>(Vb + (size_t)row * d_v + col);
-            }
-        }
-    }
-    f32x4 qv[NV], kv[NV], vv[NV];
+    int colk[NV], colv[NV];
+    bool okk[NV], okv[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int col = 4 * (lane + 64 * j);
-        qv[j] = kv[j] = vv[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (col < d_k) { qv[j] = load4<T>(qb + col); kv[j] = load4<T>(kb + col); }
-        if (col < d_v) vv[j] = load4<T>(vb + col);
+        okk[j] = col < d_k;
+        okv[j] = col < d_v;
+        colk[j] = okk[j] ? col : d_k - 4;
+        colv[j] = okv[j] ? col : d_v - 4;
+    }
+    f32x4 Kr[R][NV], Vr[R][NV];
+    // ---- issue the memory loads
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            Kr[rr][j] = *reinterpret_cast<const f32x4 *>(Kb + (size_t)(wave * R + rr) * d_k + colk[j]);
+    if (EARLY_V) {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+            for (int j = 0; j < NV; ++j)
+                Vr[rr][j] = *reinterpret_cast<const f32x4 *>(Vb + (size_t)(wave * R + rr) * d_v + colv[j]);
+    }
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    f32x4 qv[NV], kv[NV], vv[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        qv[j] = load4<T>(qb + colk[j]);
+        kv[j] = load4<T>(kb + colk[j]);
+        vv[j] = load4<T>(vb + colv[j]);
+        qv[j] = okk[j] ? qv[j] : zero4;   // masked lanes contribute nothing to the row dots
     }
     float a[R], s[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        const int row = wave * R + rr;
-        const float gv = (row < M) ? fmaxf(gb[row], kGateFloor) : 0.f;
+        const float gv = fmaxf(gb[wave * R + rr], kGateFloor);
         a[rr] = __expf(gv);
         s[rr] = -expm1f(gv);
     }
     // ---- key memories: update, write back, slot scores
+    float z[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         const int row = wave * R + rr;
         float dot = 0.f;
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
-            const int col = 4 * (lane + 64 * j);
             f32x4 x = Kr[rr][j];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 x[e] = a[rr] * x[e] + s[rr] * kv[j][e];
                 dot += x[e] * qv[j][e];
             }
-            if (row < M && col < d_k) *reinterpret_cast<f32x4 *>(Kb + (size_t)row * d_k + col) = x;
+            if (okk[j]) *reinterpret_cast<f32x4 *>(Kb + (size_t)row * d_k + colk[j]) = x;
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
-        if (lane == 0 && row < M) zs[row] = scale * dot;
+        z[rr] = scale * dot;
     }
     if (!EARLY_V) {
 #pragma unroll
-        for (int rr = 0; rr < R; ++rr) {
-            const int row = wave * R + rr;
+        for (int rr = 0; rr < R; ++rr)
 #pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                const int col = 4 * (lane + 64 * j);
-                Vr[rr][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (row < M && col < d_v) Vr[rr][j] = *reinterpret_cast<const f32x4 *>(Vb + (size_t)row * d_v + col);
-            }
-        }
+            for (int j = 0; j < NV; ++j)
+                Vr[rr][j] = *reinterpret_cast<const f32x4 *>(Vb + (size_t)(wave * R + rr) * d_v + colv[j]);
     }
-    // ---- value memories: update and write back (independent of the scores)
+    // ---- wave-local softmax weights
+    float mw = z[0];
+#pragma unroll
+    for (int rr = 1; rr < R; ++rr) mw = fmaxf(mw, z[rr]);
+    float sw = 0.f, e[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) { e[rr] = __expf(z[rr] - mw); sw += e[rr]; }
+    // ---- value memories: update, write back, partial output
+    f32x4 acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = zero4;
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         const int row = wave * R + rr;
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
-            const int col = 4 * (lane + 64 * j);
+            f32x4 x = Vr[rr][j];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) Vr[rr][j][e] = a[rr] * Vr[rr][j][e] + s[rr] * vv[j][e];
-            if (row < M && col < d_v) *reinterpret_cast<f32x4 *>(Vb + (size_t)row * d_v + col) = Vr[rr][j];
+            for (int c = 0; c < 4; ++c) {
+                x[c] = a[rr] * x[c] + s[rr] * vv[j][c];
+                acc[j][c] += e[rr] * x[c];
+            }
+            if (okv[j]) *reinterpret_cast<f32x4 *>(Vb + (size_t)row * d_v + colv[j]) = x;
         }
     }
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+        if (okv[j]) *reinterpret_cast<f32x4 *>(part + (size_t)wave * d_v + colv[j]) = acc[j];
+    if (lane == 0) { ms[2 * wave] = mw; ms[2 * wave + 1] = sw; }
     __syncthreads();
-    // ---- softmax over the slots (every wave computes it; M <= 128)
-    float z0 = (lane < M) ? zs[lane] : -INFINITY;
-    float z1 = (lane + 64 < M) ? zs[lane + 64] : -INFINITY;
-    float mx = fmaxf(z0, z1);
+    // ---- merge the 16 wave-local softmaxes
+    float mx = ms[0];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    float e0 = (lane < M) ? __expf(z0 - mx) : 0.f;
-    float e1 = (lane + 64 < M) ? __expf(z1 - mx) : 0.f;
-    float den = e0 + e1;
+    for (int w = 1; w < kDecWaves; ++w) mx = fmaxf(mx, ms[2 * w]);
+    float fw[kDecWaves], den = 0.f;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off, 64);
+    for (int w = 0; w < kDecWaves; ++w) { fw[w] = __expf(ms[2 * w] - mx); den += fw[w] * ms[2 * w + 1]; }
     const float inv = 1.f / den;
-    // ---- output: slot-weighted sum of the updated value memories
-    f32x4 acc[NV];
-#pragma unroll
-    for (int j = 0; j < NV; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int rr = 0; rr < R; ++rr) {
-        const int row = wave * R + rr;
-        const float pe = (row < 64) ? __shfl(e0, row & 63, 64) : __shfl(e1, row & 63, 64);
-        const float p = (row < M) ? pe * inv : 0.f;
-#pragma unroll
-        for (int j = 0; j < NV; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[j][e] += p * Vr[rr][j][e];
-    }
-#pragma unroll
-    for (int j = 0; j < NV; ++j) {
-        const int col = 4 * (lane + 64 * j);
-        if (col < d_v) *reinterpret_cast<f32x4 *>(part + (size_t)wave * d_v + col) = acc[j];
-    }
-    __syncthreads();
     for (int c = tid; c < d_v; c += kDecThreads) {
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) sum += part[(size_t)w * d_v + c];
-        o[(size_t)bh * d_v + c] = from_f32<T>(sum);
+        for (int w = 0; w < kDecWaves; ++w) sum += fw[w] * part[(size_t)w * d_v + c];
+        o[(size_t)bh * d_v + c] = from_f32<T>(sum * inv);
     }
 }
 
@@ -173,7 +169,7 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
                                    const void *v, const float *g, float *K, float *V, void *o, hipStream_t st)
 {
     const size_t lds = (128 + (size_t)kDecWaves * d_v) * sizeof(float);
-    constexpr bool early = (NV * ((M + kDecWaves - 1) / kDecWaves) <= 8);
+    constexpr bool early = (NV * (M / kDecWaves) <= 8);
     auto kern = decode_kernel<T, M, NV, early>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
