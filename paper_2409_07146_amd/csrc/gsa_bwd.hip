@@ -19,7 +19,8 @@
 // The last line replaces the sequence-long reversed cumulative sum of Algorithm 1 by a
 // chunk-local one: the sum of dGam over all later chunks equals the row-wise inner product
 // of the chunk-end memory with its gradient, which both scans already hold.  That keeps
-// rounding errors from accumulating along the sequence.
+// rounding errors from accumulating along the sequence (measured: summing the chunk totals
+// instead costs about a third more error on dg with bf16 memories).
 //
 // Kernels of one backward call: gate + forward scan (gsa_scan.hip; recompute the chunk-start
 // memories, since nothing but z was saved by the forward), chunk_dz (chunk-parallel: dp, dz,
@@ -43,7 +44,8 @@ template <typename T, int M> struct DzLds {
     static constexpr size_t oTot = oA;   // gate_prep's scratch, dead before As is written
     static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                   : sizeof(float) * Geo<T>::NT;
-    static constexpr size_t bytes = oA + szA;
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // aliases As
+    static constexpr size_t bytes = oA + (szA > szRed ? szA : szRed);
 };
 
 template <typename T, int M>
@@ -76,8 +78,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_dz_kernel(ChunkMap cm, int H
     gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
     float dp[MI][4];
     bool unsafe;
-    gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, As, L::lda, dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v,
-                          d_v, Vn, (size_t)d_v, ci.len, tid);
+    gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, As, L::lda, reinterpret_cast<f32x4 *>(smem + L::oA),
+                          dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn, (size_t)d_v, ci.len, tid);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -177,8 +179,9 @@ template <typename T, int M> struct IntraLds {
     static constexpr size_t oTot = oAT;   // gate_prep's and the suffix sum's scratch (ATs is dead by then)
     static constexpr size_t szAT = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                    : sizeof(float) * Geo<T>::NT;
-    static constexpr size_t oCarry = oAT + szAT;
-    static constexpr size_t bytes = oCarry + sizeof(float) * 128;
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // aliases Pf, Df, ATs
+    static constexpr size_t oCarry = (oAT + szAT > oPf + szRed) ? oAT + szAT : oPf + szRed;
+    static constexpr size_t bytes = oCarry + sizeof(float) * (C / 16) * M;   // per-wave partial carries
 };
 
 template <typename T> struct IntraArgs {
@@ -192,26 +195,26 @@ template <typename T> struct IntraArgs {
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
+__global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
                                                                  IntraArgs<T> a)
 {
     using L = IntraLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT, NW = Geo<T>::NW;
     constexpr int MI = M / 16, CI = C / 16, KM = L::KM;
-    constexpr int NCP = (MI + NW - 1) / NW;   // slot blocks whose carry this wave accumulates
+    constexpr int NB = CI + MI;
     extern __shared__ __align__(16) unsigned char smem[];
     float *Gs = reinterpret_cast<float *>(smem + L::oG);
     float *Ss = reinterpret_cast<float *>(smem + L::oS);
     float *Pf = reinterpret_cast<float *>(smem + L::oPf);    // p, later exp(g)*ds
     float *Df = reinterpret_cast<float *>(smem + L::oDf);    // dz, later dGam
     float *tot = reinterpret_cast<float *>(smem + L::oTot);
-    float *carry = reinterpret_cast<float *>(smem + L::oCarry);
+    float *carry = reinterpret_cast<float *>(smem + L::oCarry);   // [NW][M]
     T *ATs = reinterpret_cast<T *>(smem + L::oAT);           // [r][t] (q_t . k_r) for t >= r; later Bm [t][r]
 
     ChunkInfo ci;
     if (!chunk_lookup(cm, blockIdx.x, ci)) return;
     const int h = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const size_t ch = (size_t)blockIdx.x * H + h;
@@ -233,93 +236,89 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, in
     const int rowb = 16 * w;
 
     gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, a.g + tokh * M, (size_t)H * M, ci.len, tid);
-    softmax_rows<M, C>(Pf, Df, L::ldg, a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
-
     // ---- phase 1: contractions over the head dimension, operands straight from global memory
     //   A[t][r] = q_t . k_r (r <= t),  X[r][i] = <E[i], [k_r | v_r]>,  carry[i] = <E[i], S_end[i]>
+    // Split over the waves in steps of 32 columns (see gated_scores): every wave covers all row
+    // blocks over its share of the columns, the partial sums meet in LDS.
     f32x4 accA[CI], accX[MI];
-#pragma unroll
-    for (int ni = 0; ni < CI; ++ni) accA[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ni = 0; ni < MI; ++ni) accX[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float cpart[NCP];
-#pragma unroll
-    for (int u = 0; u < NCP; ++u) cpart[u] = 0.f;
     {
-        // Double-buffered: the fragments of the next 32 columns are in flight while these multiply.
+        typedef typename Atom<T>::Frag Frag;
+        f32x4 acc[NW][NB];   // [row block][k blocks (causal) | slot blocks]
+#pragma unroll
+        for (int rb = 0; rb < NW; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float cpart[MI];     // this lane's share of the carry of slot 16*ni + lane%16
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) cpart[ni] = 0.f;
         // Token rows past the end of a ragged chunk are read as copies of its last row (finite; they
         // only feed rows that are never stored or that meet zero weights).
-        typedef typename Atom<T>::Frag Frag;
-        const size_t rown = (size_t)min(rowb + r, ci.len - 1) * H;
-        size_t rowy[CI];
+        uint32_t tk[CI], tv[CI], ek[MI], ev[MI];
 #pragma unroll
-        for (int ni = 0; ni < CI; ++ni) rowy[ni] = (size_t)min(ni * 16 + r, ci.len - 1) * H;
-        struct Set { Frag x, y, by[CI], be[MI], bs[NCP]; };
-        auto multiply = [&](const Set &f, bool with_A) {
-            if (with_A) {
-#pragma unroll
-                for (int ni = 0; ni < CI; ++ni) Atom<T>::mma(accA[ni], f.x, f.by[ni]);
-            }
-#pragma unroll
-            for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(accX[ni], f.y, f.be[ni]);
-#pragma unroll
-            for (int ni = 0; ni < MI; ++ni)
-                if (ni % NW == w) cpart[ni / NW] += frag_dot<T>(f.be[ni], f.bs[ni / NW]);
-        };
-        // key half: A = Q K^T, X += K E_k^T, carry += <E_k, S_end,k>
-        {
-            const T *qa = a.q + (tokh + rown) * d_k + g8, *ka = a.k + (tokh + rown) * d_k + g8;
-            auto fetch = [&](int k0, Set &f) {
-                f.x = Atom<T>::load(qa + k0);
-                f.y = Atom<T>::load(ka + k0);
-#pragma unroll
-                for (int ni = 0; ni < CI; ++ni) f.by[ni] = Atom<T>::load(a.k + (tokh + rowy[ni]) * d_k + k0 + g8);
-#pragma unroll
-                for (int ni = 0; ni < MI; ++ni) {
-                    const size_t off = (size_t)(ni * 16 + r) * d_k + k0 + g8;
-                    f.be[ni] = Atom<T>::load(EK + off);
-                    if (ni % NW == w) f.bs[ni / NW] = Atom<T>::load(SendK + off);
-                }
-            };
-            Set f0, f1;
-            fetch(0, f0);
-            for (int k0 = 0; k0 < d_k; k0 += 64) {
-                fetch(k0 + 32, f1);
-                multiply(f0, true);
-                if (k0 + 64 < d_k) fetch(k0 + 64, f0);
-                multiply(f1, true);
-            }
+        for (int ni = 0; ni < CI; ++ni) {
+            const uint32_t row = (uint32_t)min(ni * 16 + r, ci.len - 1) * (uint32_t)H;
+            tk[ni] = row * (uint32_t)d_k + g8;
+            tv[ni] = row * (uint32_t)d_v + g8;
         }
-        // value half: X += V E_v^T, carry += <E_v, S_end,v>
-        {
-            const T *va = a.v + (tokh + rown) * d_v + g8;
-            auto fetch = [&](int k0, Set &f) {
-                f.y = Atom<T>::load(va + k0);
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) {
-                    const size_t off = (size_t)(ni * 16 + r) * d_v + k0 + g8;
-                    f.be[ni] = Atom<T>::load(EV + off);
-                    if (ni % NW == w) f.bs[ni / NW] = Atom<T>::load(SendV + off);
-                }
-            };
-            Set f0, f1;
-            fetch(0, f0);
-            for (int k0 = 0; k0 < d_v; k0 += 64) {
-                fetch(k0 + 32, f1);
-                multiply(f0, false);
-                if (k0 + 64 < d_v) fetch(k0 + 64, f0);
-                multiply(f1, false);
-            }
+        for (int ni = 0; ni < MI; ++ni) {
+            ek[ni] = (uint32_t)(ni * 16 + r) * (uint32_t)d_k + g8;
+            ev[ni] = (uint32_t)(ni * 16 + r) * (uint32_t)d_v + g8;
         }
-    }
+        const T *qb = a.q + tokh * d_k, *kb = a.k + tokh * d_k, *vb = a.v + tokh * d_v;
+        // key half: A = Q K^T, X += K E_k^T
+        for (int k0 = 32 * w; k0 < d_k; k0 += 32 * NW) {
+            Frag fq[CI], fk[CI], fe[MI], fs[MI];
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni) {
-        if (ni % NW != w) continue;
-        float x = cpart[ni / NW];
-        x += __shfl_xor(x, 16, 64);
-        x += __shfl_xor(x, 32, 64);
-        if (lane < 16) carry[ni * 16 + lane] = x;
+            for (int ni = 0; ni < CI; ++ni) fq[ni] = Atom<T>::load(qb + tk[ni] + k0);
+#pragma unroll
+            for (int ni = 0; ni < CI; ++ni) fk[ni] = Atom<T>::load(kb + tk[ni] + k0);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EK + ek[ni] + k0);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendK + ek[ni] + k0);
+#pragma unroll
+            for (int rb = 0; rb < NW; ++rb) {
+#pragma unroll
+                for (int cb = 0; cb <= rb; ++cb) Atom<T>::mma(acc[rb][cb], fq[rb], fk[cb]);
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fk[rb], fe[ni]);
+            }
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[ni], fs[ni]);
+        }
+        // value half: X += V E_v^T
+        for (int k0 = 32 * w; k0 < d_v; k0 += 32 * NW) {
+            Frag fv[CI], fe[MI], fs[MI];
+#pragma unroll
+            for (int ni = 0; ni < CI; ++ni) fv[ni] = Atom<T>::load(vb + tv[ni] + k0);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EV + ev[ni] + k0);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendV + ev[ni] + k0);
+#pragma unroll
+            for (int rb = 0; rb < NW; ++rb)
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fv[rb], fe[ni]);
+#pragma unroll
+            for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[ni], fs[ni]);
+        }
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) {
+            float x = cpart[ni];
+            x += __shfl_xor(x, 16, 64);
+            x += __shfl_xor(x, 32, 64);
+            if (lane < 16) carry[w * M + ni * 16 + lane] = x;   // read after the barriers of the reduction
+        }
+        f32x4 own[NB];
+        reduce_row_blocks<NW, NB, CI>(own, acc, reinterpret_cast<f32x4 *>(smem + L::oPf), lane, w);
+#pragma unroll
+        for (int ni = 0; ni < CI; ++ni) accA[ni] = own[ni];
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) accX[ni] = own[CI + ni];
     }
+    // p and dz tiles (they overwrite the reduction buffer, which every wave has left by now)
+    softmax_rows<M, C>(Pf, Df, L::ldg, a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
     // ---- phase 2a: transposed masked A into LDS; the slot-side operand tiles of the apply kernel
 #pragma unroll
     for (int ni = 0; ni < CI; ++ni)
@@ -356,25 +355,31 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, in
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) accW[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
         const int tstart = unsafe ? rowb + 16 : rowb;
+        float gend[MI];
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) gend[ni] = Gs[(rowb + 15) * L::ldg + ni * 16 + r];
+        // LDS reads are unconditional (every token of the tile exists); masking is a register select
         for (int k0 = (tstart & ~31); k0 < C; k0 += 32) {
             const typename Atom<T>::Frag aA = Atom<T>::load(ATs + (rowb + r) * L::lda + k0 + g8);
             const typename Atom<T>::Frag aAv = Atom<T>::load(AvT + (rowb + r) * C + k0 + g8);
 #pragma unroll
             for (int ni = 0; ni < MI; ++ni) {
                 const int i = ni * 16 + r;
-                const float gend = Gs[(rowb + 15) * L::ldg + i];
-                typename Atom<T>::Frag bdz, bp;
+                float gv[8], dv[8], pv[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int t = k0 + g8 + e;
-                    float x = 0.f, y = 0.f;
-                    if (t >= tstart) {
-                        const float f = __expf(fminf(Gs[t * L::ldg + i] - gend, kExpClamp));
-                        x = scale * Df[t * L::ldg + i] * f;
-                        y = Pf[t * L::ldg + i] * f;
-                    }
-                    bdz[e] = from_f32<T>(x);
-                    bp[e] = from_f32<T>(y);
+                    gv[e] = Gs[t * L::ldg + i];
+                    dv[e] = Df[t * L::ldg + i];
+                    pv[e] = Pf[t * L::ldg + i];
+                }
+                typename Atom<T>::Frag bdz, bp;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool on = k0 + g8 + e >= tstart;
+                    const float f = __expf(fminf(gv[e] - gend[ni], kExpClamp));
+                    bdz[e] = from_f32<T>(on ? scale * dv[e] * f : 0.f);
+                    bp[e] = from_f32<T>(on ? pv[e] * f : 0.f);
                 }
                 Atom<T>::mma(accW[ni], aA, bdz);
                 Atom<T>::mma(accW[ni], aAv, bp);
@@ -411,38 +416,26 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, in
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) { accB[ni] = f32x4{0.f, 0.f, 0.f, 0.f}; acc2[ni] = f32x4{0.f, 0.f, 0.f, 0.f}; }
         for (int k0 = 0; k0 < KM; k0 += 32) {
+            const SlotSpan<M, KM> sp(k0 + g8);
+            float gref[8];
+            gate_ref8(gref, Gs, L::ldg, rowb, sp.i0);
             typename Atom<T>::Frag adz, ap;
             {
-                const int t = rowb + r;
+                float gv[8], dv[8], pv[8];
+                lds_row8(gv, Gs + (rowb + r) * L::ldg + sp.i0);
+                lds_row8(dv, Df + (rowb + r) * L::ldg + sp.i0);
+                lds_row8(pv, Pf + (rowb + r) * L::ldg + sp.i0);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const int i = k0 + g8 + e;
-                    float x = 0.f, y = 0.f;
-                    if (i < M) {
-                        const float gref = rowb ? Gs[(rowb - 1) * L::ldg + i] : 0.f;
-                        const float f = __expf(Gs[t * L::ldg + i] - gref);
-                        x = Df[t * L::ldg + i] * f;
-                        y = Pf[t * L::ldg + i] * f;
-                    }
-                    adz[e] = from_f32<T>(x);
-                    ap[e] = from_f32<T>(y);
+                    const float f = __expf(gv[e] - gref[e]);
+                    adz[e] = from_f32<T>(sp.live ? dv[e] * f : 0.f);
+                    ap[e] = from_f32<T>(sp.live ? pv[e] * f : 0.f);
                 }
             }
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni) {
-                if (ni > w || (unsafe && ni == w)) continue;
-                const int rr = ni * 16 + r;
-                typename Atom<T>::Frag b;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int i = k0 + g8 + e;
-                    float val = 0.f;
-                    if (i < M) {
-                        const float gref = rowb ? Gs[(rowb - 1) * L::ldg + i] : 0.f;
-                        val = Ss[rr * L::ldg + i] * __expf(fminf(gref - Gs[rr * L::ldg + i], kExpClamp));
-                    }
-                    b[e] = from_f32<T>(val);
-                }
+                if (ni > w || (unsafe && ni == w)) continue;   // wave-uniform
+                const typename Atom<T>::Frag b = write_frag<T>(Gs, Ss, L::ldg, ni * 16 + r, sp.i0, sp.live, gref);
                 Atom<T>::mma(accB[ni], adz, b);
                 Atom<T>::mma(acc2[ni], ap, b);
             }
@@ -505,7 +498,9 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_intra_kernel(ChunkMap cm, in
         }
         tot[part * M + i] = run;
         __syncthreads();
-        float off = carry[i];
+        float off = 0.f;
+#pragma unroll
+        for (int u = 0; u < NW; ++u) off += carry[u * M + i];
         for (int pp = part + 1; pp < P; ++pp) off += tot[pp * M + i];
         for (int tt = 0; tt < TP; ++tt) {
             const int t = part * TP + tt;

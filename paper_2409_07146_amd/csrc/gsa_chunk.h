@@ -36,6 +36,43 @@ __device__ __forceinline__ bool block_unsafe(const float *Gs, int ldg, int rowb,
     return wave_max(drop) > kExpClamp;
 }
 
+// Split-contraction bookkeeping.  The chunk kernels contract over the head dimension with
+// every wave taking a slice of that dimension for ALL row blocks of the chunk (so each
+// operand byte is loaded by exactly one wave, in whole 128-byte lines), and then sum the
+// per-wave partial accumulators so that wave w ends up with the totals of row block w.
+// acc[rb][cb] are D fragments; the first CAUSAL column blocks are only needed for cb <= rb.
+// Red: LDS, NW*NB*64 f32x4 (fragments are exchanged lane for lane, so any wave's layout
+// is every wave's layout).  w must be wave-uniform.  Contains barriers: all threads of the
+// workgroup must call it.
+template <int NW, int NB, int CAUSAL>
+__device__ __forceinline__ void reduce_row_blocks(f32x4 (&own)[NB], const f32x4 (&acc)[NW][NB], f32x4 *Red, int lane,
+                                                  int w)
+{
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) own[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // One round per row block: every wave posts its partial of that block, the block's owner adds
+    // them in wave order.  (Register arrays are indexed by constants only; the wave index enters
+    // through LDS addresses.)
+#pragma unroll
+    for (int rb = 0; rb < NW; ++rb) {
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb)
+            if (!(cb < CAUSAL && cb > rb)) Red[(w * NB + cb) * kWave + lane] = acc[rb][cb];
+        __syncthreads();
+        if (w == rb) {
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb) {
+                if (cb < CAUSAL && cb > rb) continue;
+                f32x4 x = Red[cb * kWave + lane];
+#pragma unroll
+                for (int u = 1; u < NW; ++u) x += Red[(u * NB + cb) * kWave + lane];
+                own[cb] = x;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // For this wave's row block (rows t = rowb .. rowb+15), in D layout (lane holds slot
 // i = 16*ni + lane%16, rows t = rowb + 4*(lane/16) + j):
 //
@@ -45,57 +82,60 @@ __device__ __forceinline__ bool block_unsafe(const float *Gs, int ldg, int rowb,
 // slot side (pass 1 of Eq. (gsa-2pass) with X=q, Y=k, St=Kt; its mirror in the backward
 // with X=dO, Y=v, St=Vt).  X, Y: [len][d] rows in global memory (row stride ldx elements);
 // St: [M][d] rows of T (stride ldst).  The contraction over d reads its operand fragments
-// straight from global memory (each lane 16 bytes of one row; no LDS, no barriers), so the
-// loads of many k-steps and of several resident workgroups are in flight together.
+// straight from global memory (each lane 16 bytes of one row; no staging).  It is split over
+// the waves in steps of 32 columns, wave w taking steps w, w+NW, ...: neighbouring waves ask
+// for the two halves of a 128-byte line at about the same time, so each line crosses the
+// memory system once.  The partial sums meet through Red (see reduce_row_blocks; Red may
+// alias As).  d must be a multiple of 32.
 // LDS: Gs, Ss filled by gate_prep; As [C][lda] is left holding the causally masked X Y^T
 // rounded to T.  All threads of the workgroup must call it.
 template <typename T, int M, int C>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, const float *Gs, const float *Ss,
-                                             int ldg, T *As, int lda, const T *X, const T *Y, size_t ldx, int d,
-                                             const T *St, size_t ldst, int len, int tid)
+                                             int ldg, T *As, int lda, f32x4 *Red, const T *X, const T *Y, size_t ldx,
+                                             int d, const T *St, size_t ldst, int len, int tid)
 {
-    constexpr int MI = M / 16, CI = C / 16;
-    const int lane = tid & 63, w = tid >> 6;
+    constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
+    const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const int rowb = 16 * w;
 
     f32x4 accA[CI], accZ[MI];
-#pragma unroll
-    for (int ni = 0; ni < CI; ++ni) accA[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ni = 0; ni < MI; ++ni) accZ[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
     {
+        f32x4 acc[NW][NB];   // [row block][Y blocks | St blocks]
+#pragma unroll
+        for (int rb = 0; rb < NW; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
         // Rows past the end of a ragged chunk are read as copies of its last row: they stay finite
         // and only ever produce rows of the result that are not stored or that meet zero weights.
-        const T *xa = X + (size_t)min(rowb + r, len - 1) * ldx + g8;
-        const T *yb[CI], *sb[MI];
+        uint32_t xo[CI], so[MI];
 #pragma unroll
-        for (int ni = 0; ni < CI; ++ni) yb[ni] = Y + (size_t)min(ni * 16 + r, len - 1) * ldx + g8;
+        for (int ni = 0; ni < CI; ++ni) xo[ni] = (uint32_t)min(ni * 16 + r, len - 1) * (uint32_t)ldx + g8;
 #pragma unroll
-        for (int ni = 0; ni < MI; ++ni) sb[ni] = St + (size_t)(ni * 16 + r) * ldst + g8;
+        for (int ni = 0; ni < MI; ++ni) so[ni] = (uint32_t)(ni * 16 + r) * (uint32_t)ldst + g8;
         typedef typename Atom<T>::Frag Frag;
-        Frag a0, a1, y0[CI], y1[CI], s0[MI], s1[MI];
-        auto fetch = [&](int k0, Frag &fa, Frag (&fy)[CI], Frag (&fs)[MI]) {
-            fa = Atom<T>::load(xa + k0);
+        for (int k0 = 32 * w; k0 < d; k0 += 32 * NW) {
+            Frag fx[CI], fy[CI], fs[MI];
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) fy[ni] = Atom<T>::load(yb[ni] + k0);
+            for (int ni = 0; ni < CI; ++ni) fx[ni] = Atom<T>::load(X + xo[ni] + k0);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(sb[ni] + k0);
-        };
-        auto multiply = [&](const Frag &fa, const Frag (&fy)[CI], const Frag (&fs)[MI]) {
+            for (int ni = 0; ni < CI; ++ni) fy[ni] = Atom<T>::load(Y + xo[ni] + k0);
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) Atom<T>::mma(accA[ni], fa, fy[ni]);
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(St + so[ni] + k0);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(accZ[ni], fa, fs[ni]);
-        };
-        // two register sets: the loads of the next 32 columns are in flight while these multiply
-        fetch(0, a0, y0, s0);
-        for (int k0 = 0; k0 < d; k0 += 64) {   // d is a multiple of 64
-            fetch(k0 + 32, a1, y1, s1);
-            multiply(a0, y0, s0);
-            if (k0 + 64 < d) fetch(k0 + 64, a0, y0, s0);
-            multiply(a1, y1, s1);
+            for (int rb = 0; rb < NW; ++rb) {
+#pragma unroll
+                for (int cb = 0; cb <= rb; ++cb) Atom<T>::mma(acc[rb][cb], fx[rb], fy[cb]);
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fx[rb], fs[ni]);
+            }
         }
+        f32x4 own[NB];
+        reduce_row_blocks<NW, NB, CI>(own, acc, Red, lane, w);
+#pragma unroll
+        for (int ni = 0; ni < CI; ++ni) accA[ni] = own[ni];
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) accZ[ni] = own[CI + ni];
     }
     // causally masked X Y^T, as an operand
 #pragma unroll
@@ -111,19 +151,28 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
     f32x4 accI[MI];
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) accI[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float gref[MI];
+#pragma unroll
+    for (int ni = 0; ni < MI; ++ni) gref[ni] = rowb ? Gs[(rowb - 1) * ldg + ni * 16 + r] : 0.f;
+    // Every LDS read below is unconditional (tokens up to k0+31 < C exist in the tiles; the clamp keeps
+    // the unused ones finite) and masking is a register select: a read under a per-lane branch would
+    // wait out the full LDS latency element by element.
     for (int k0 = 0; k0 < kend; k0 += 32) {
         const typename Atom<T>::Frag a = Atom<T>::load(As + (rowb + r) * lda + k0 + g8);
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) {
             const int i = ni * 16 + r;
-            const float gref = rowb ? Gs[(rowb - 1) * ldg + i] : 0.f;
+            float sv[8], gv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                sv[e] = Ss[(k0 + g8 + e) * ldg + i];
+                gv[e] = Gs[(k0 + g8 + e) * ldg + i];
+            }
             typename Atom<T>::Frag b;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int kk = k0 + g8 + e;
-                float val = 0.f;
-                if (kk < kend) val = Ss[kk * ldg + i] * __expf(fminf(gref - Gs[kk * ldg + i], kExpClamp));
-                b[e] = from_f32<T>(val);
+                const float val = sv[e] * __expf(fminf(gref[ni] - gv[e], kExpClamp));
+                b[e] = from_f32<T>((k0 + g8 + e < kend) ? val : 0.f);
             }
             Atom<T>::mma(accI[ni], a, b);
         }
@@ -131,12 +180,11 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) {
         const int i = ni * 16 + r;
-        const float gref = rowb ? Gs[(rowb - 1) * ldg + i] : 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
             const float G = Gs[t * ldg + i];
-            float val = __expf(G) * accZ[ni][j] + __expf(G - gref) * accI[ni][j];
+            float val = __expf(G) * accZ[ni][j] + __expf(G - gref[ni]) * accI[ni][j];
             if (unsafe) {
                 float sum = 0.f;
                 for (int rr = rowb; rr <= t; ++rr)
@@ -146,6 +194,49 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
             out[ni][j] = val;
         }
     }
+}
+
+// Eight consecutive floats of an LDS row (16-byte aligned).
+__device__ __forceinline__ void lds_row8(float (&x)[8], const float *p)
+{
+    const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
+    const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[e] = lo[e]; x[4 + e] = hi[e]; }
+}
+
+// The eight slots i0 .. i0+7 a lane contributes to a contraction over the (padded) slot axis,
+// and whether they exist: with M < KM the padding lanes re-read the last eight real slots and
+// are masked, so that no LDS read sits under a per-lane branch.
+template <int M, int KM> struct SlotSpan {
+    int i0;
+    bool live;
+    __device__ __forceinline__ SlotSpan(int k) : i0((M < KM) ? min(k, M - 8) : k), live((M >= KM) || (k < M)) {}
+};
+
+// Gate reference of row block rowb (cumulative log gate just before it) for slots i0 .. i0+7.
+__device__ __forceinline__ void gate_ref8(float (&gref)[8], const float *Gs, int ldg, int rowb, int i0)
+{
+    lds_row8(gref, Gs + (rowb ? rowb - 1 : 0) * ldg + i0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) gref[e] = rowb ? gref[e] : 0.f;
+}
+
+// B fragment  b[e] = s_rr[i0+e] * exp(gref[e] - G_rr[i0+e])  (clamped; zero where !live).
+template <typename T>
+__device__ __forceinline__ typename Atom<T>::Frag write_frag(const float *Gs, const float *Ss, int ldg, int rr, int i0,
+                                                             bool live, const float (&gref)[8])
+{
+    float sv[8], gv[8];
+    lds_row8(sv, Ss + rr * ldg + i0);
+    lds_row8(gv, Gs + rr * ldg + i0);
+    typename Atom<T>::Frag b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = sv[e] * __expf(fminf(gref[e] - gv[e], kExpClamp));
+        b[e] = from_f32<T>(live ? x : 0.f);
+    }
+    return b;
 }
 
 // Row block w of the pair-weight matrix, for column blocks ni <= w:
@@ -165,21 +256,13 @@ __device__ __forceinline__ void pair_weights(f32x4 (&acc)[C / 16], const T *Wa, 
     for (int ni = 0; ni < CI; ++ni) acc[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int k0 = 0; k0 < KM; k0 += 32) {
         const typename Atom<T>::Frag a = Atom<T>::load(Wa + (rowb + r) * ldp + k0 + g8);
+        const SlotSpan<M, KM> sp(k0 + g8);
+        float gref[8];
+        gate_ref8(gref, Gs, ldg, rowb, sp.i0);
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) {
-            if (ni > w || (unsafe && ni == w)) continue;
-            const int rr = ni * 16 + r;
-            typename Atom<T>::Frag b;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = k0 + g8 + e;
-                float val = 0.f;
-                if (i < M) {
-                    const float gref = rowb ? Gs[(rowb - 1) * ldg + i] : 0.f;
-                    val = Ss[rr * ldg + i] * __expf(fminf(gref - Gs[rr * ldg + i], kExpClamp));
-                }
-                b[e] = from_f32<T>(val);
-            }
+            if (ni > w || (unsafe && ni == w)) continue;   // wave-uniform
+            const typename Atom<T>::Frag b = write_frag<T>(Gs, Ss, ldg, ni * 16 + r, sp.i0, sp.live, gref);
             Atom<T>::mma(acc[ni], a, b);
         }
     }

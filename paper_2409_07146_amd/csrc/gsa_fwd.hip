@@ -92,7 +92,8 @@ template <typename T, int M> struct ChunkFwdLds {
     static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                   : sizeof(float) * Geo<T>::NT;
     static constexpr size_t oP = oA + szA;
-    static constexpr size_t bytes = oP + sizeof(T) * C * ldp;
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // aliases As, Ps
+    static constexpr size_t bytes = (oP + sizeof(T) * C * ldp > oA + szRed) ? oP + sizeof(T) * C * ldp : oA + szRed;
 };
 
 template <typename T, int M>
@@ -128,8 +129,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_fwd_kernel(ChunkMap cm, int 
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
     float p[MI][4];
     bool unsafe;
-    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, As, L::lda, q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k,
-                          d_k, Kn, (size_t)d_k, ci.len, tid);
+    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, As, L::lda, reinterpret_cast<f32x4 *>(smem + L::oA),
+                          q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn, (size_t)d_k, ci.len, tid);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
