@@ -1,6 +1,6 @@
 // The wide contractions of Gated Slot Attention: every output of width d_k or d_v is
 //
-//     out[C x cols] = s_tok * A_tok[C x C] X[C x cols]  +  s_slot * A_slot[C x m] St[m x cols]
+//     out[C x cols] = A_tok[C x C] X[C x cols]  +  A_slot[C x m] St[m x cols]
 //
 // per (chunk, head): the intra-chunk term contracts a small token-by-token matrix with a token
 // tensor of the chunk, the inter-chunk term contracts a small token-by-slot matrix with a slot
@@ -9,8 +9,8 @@
 // is where the bytes move:
 //
 //     forward  o  = A2   V  + (p e^G)      Vt_start
-//     backward dq = Bm   K  + (dz e^G)     Kt_start      (both scaled)
-//              dk = Bm^T Q  + (s e^{G_C-G}) E_k           (first term scaled)
+//     backward dq = Bm   K  + (dz e^G)     Kt_start      (Bm and dz carry the softmax scale)
+//              dk = Bm^T Q  + (s e^{G_C-G}) E_k
 //              dv = A2^T dO + (s e^{G_C-G}) E_v
 //
 // One workgroup per (column slice, chunk, head, output).  LDS holds only the transposed token
@@ -32,7 +32,6 @@ template <typename T> struct ApplyOne {
     long long xs_stride;  // elements per (chunk, head) record
     T *out;               // [tokens][H][d]
     int d;
-    float s_tok, s_slot;
 };
 template <typename T> struct ApplyArgs { ApplyOne<T> one[3]; };
 
@@ -40,9 +39,12 @@ template <typename T, int M> struct ApplyLds {
     static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int NS = (sizeof(T) == 2) ? 128 : 64;
-    static constexpr int lda = C + PAD, ldo = NS + PAD;
+    static constexpr int KM = (M < 32) ? 32 : M;
+    static constexpr int lda = C + PAD, ldo = NS + PAD, lds = KM + PAD;
     static constexpr size_t szX = sizeof(T) * NS * lda, szO = sizeof(T) * C * ldo;
-    static constexpr size_t bytes = szX > szO ? szX : szO;
+    static constexpr size_t oAt = szX > szO ? szX : szO;          // A_tok  [C][lda]
+    static constexpr size_t oAs = oAt + sizeof(T) * C * lda;      // A_slot [C][lds]
+    static constexpr size_t bytes = oAs + sizeof(T) * C * lds;
 };
 
 template <typename T, int M>
@@ -72,45 +74,68 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
 
     TokTile<T, C, L::NS, NT> tt;
     tt.load(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);
-
-    // inter-chunk term first: its operands come straight from global memory
-    f32x4 acc2[CI][NIo];
-    zero_acc(acc2);
-    if (active) {
-        const T *As = a.A_slot + ch * C * KM;
+    // the two small matrices go through LDS: every wave needs all of both
+    T *Ats = reinterpret_cast<T *>(smem + L::oAt), *Ass = reinterpret_cast<T *>(smem + L::oAs);
+    {
+        const T *At = a.A_tok + ch * C * C, *As = a.A_slot + ch * C * KM;
+        constexpr int VT = C * C / 8, VS = C * KM / 8;
+        Raw8<T> xt[(VT + NT - 1) / NT], xs[(VS + NT - 1) / NT];
+#pragma unroll
+        for (int u = 0; u < (VT + NT - 1) / NT; ++u) xt[u].load(At + (size_t)min(tid + u * NT, VT - 1) * 8);
+#pragma unroll
+        for (int u = 0; u < (VS + NT - 1) / NT; ++u) xs[u].load(As + (size_t)min(tid + u * NT, VS - 1) * 8);
+#pragma unroll
+        for (int u = 0; u < (VT + NT - 1) / NT; ++u) {
+            const int idx = tid + u * NT, t = idx / (C / 8), c8 = (idx - t * (C / 8)) * 8;
+            if (idx < VT) xt[u].store(Ats + t * L::lda + c8);
+        }
+#pragma unroll
+        for (int u = 0; u < (VS + NT - 1) / NT; ++u) {
+            const int idx = tid + u * NT, t = idx / (KM / 8), c8 = (idx - t * (KM / 8)) * 8;
+            if (idx < VS) xs[u].store(Ass + t * L::lds + c8);
+        }
+    }
+    // slot-memory fragments straight from global memory (each wave has its own columns)
+    typename Atom<T>::Frag bs[KM / 32][NIo];
+    {
         const T *Bs = a.xslotT + ch * a.xs_stride + (size_t)cs * M;
 #pragma unroll
-        for (int k0 = 0; k0 < KM; k0 += 32) {
-            typename Atom<T>::Frag af[CI], bf[NIo];
+        for (int ks = 0; ks < KM / 32; ++ks)
 #pragma unroll
-            for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(As + (mi * 16 + r) * KM + k0 + g8);
-#pragma unroll
-            for (int ni = 0; ni < NIo; ++ni)
-                bf[ni] = gfrag<T>(Bs + (size_t)(wcol + ni * 16 + r) * M + k0 + g8, k0 + g8 < M);
-#pragma unroll
-            for (int mi = 0; mi < CI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc2[mi][ni], af[mi], bf[ni]);
-        }
+            for (int ni = 0; ni < NIo; ++ni) {
+                // clamped to the slice and to the real slots: the load is unconditional and stays inside the block
+                const int c = min(wcol + ni * 16 + r, ncols - 1);
+                const SlotSpan<M, KM> sp(ks * 32 + g8);
+                bs[ks][ni] = gfrag<T>(Bs + (size_t)c * M + sp.i0, sp.live);
+            }
     }
     tt.store_transposed(XT, L::lda, ncols, tid);
     __syncthreads();
-    f32x4 acc1[CI][NIo];
-    zero_acc(acc1);
+    f32x4 acc[CI][NIo];
+    zero_acc(acc);
     if (active) {
-        const T *At = a.A_tok + ch * C * C;
+#pragma unroll
+        for (int ks = 0; ks < KM / 32; ++ks) {
+            typename Atom<T>::Frag af[CI];
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(Ass + (mi * 16 + r) * L::lds + ks * 32 + g8);
+#pragma unroll
+            for (int mi = 0; mi < CI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bs[ks][ni]);
+        }
 #pragma unroll
         for (int k0 = 0; k0 < C; k0 += 32) {
             typename Atom<T>::Frag af[CI], bf[NIo];
 #pragma unroll
-            for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(At + (mi * 16 + r) * C + k0 + g8);
+            for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(Ats + (mi * 16 + r) * L::lda + k0 + g8);
 #pragma unroll
             for (int ni = 0; ni < NIo; ++ni)
                 bf[ni] = Atom<T>::load(XT + xt_off<C>(wcol + ni * 16 + r, k0 + g8, L::lda));
 #pragma unroll
             for (int mi = 0; mi < CI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc1[mi][ni], af[mi], bf[ni]);
+                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bf[ni]);
         }
     }
     __syncthreads();   // the token tile is dead: its space becomes the output tile
@@ -121,8 +146,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
             for (int ni = 0; ni < NIo; ++ni)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] =
-                        from_f32<T>(a.s_tok * acc1[mi][ni][j] + a.s_slot * acc2[mi][ni][j]);
+                    Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
     }
     __syncthreads();
     store_tile<T>(a.out + tokh * a.d + cs, (size_t)H * a.d, Os, L::ldo, C, ncols, ci.len, tid, NT);
@@ -144,8 +168,6 @@ static hipError_t launch_apply_tm(const Plan &pl, const Work &w, const ApplyIo *
         o.xs_stride = s.xslot_stride;
         o.out = static_cast<T *>(s.out);
         o.d = s.d;
-        o.s_tok = s.s_tok;
-        o.s_slot = s.s_slot;
         if (i < n && s.d > dmax) dmax = s.d;
     }
     constexpr int NS = ApplyLds<T, M>::NS;

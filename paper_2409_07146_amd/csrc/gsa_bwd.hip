@@ -10,7 +10,7 @@
 //             chunks only; carried backwards by  E' = Diag(exp G_C) E + (w * exp G)^T x
 //             with (w, x) = (scale*dz, q) on the key columns and (p, dO) on the value columns
 //   Bm[t,r] = sum_i dz_t[i] s_r[i] exp(G_t[i]-G_r[i]),  A2[t,r] likewise with p_t   (r <= t)
-//   dq = scale * ((dz*exp G) Kt_start + Bm K)
+//   dq = scale * ((dz*exp G) Kt_start + Bm K)        (the scale is folded into the small matrices)
 //   dk = scale * Bm^T Q + (s*exp(G_C-G)) E_k          dv = A2^T dO + (s*exp(G_C-G)) E_v
 //   ds_r[i] = exp(G_C-G_r)[i] <E[i], [k_r|v_r]> + sum_{t>=r} exp(G_t-G_r)[i] (scale dz_t[i] <q_t,k_r> + p_t[i] <dO_t,v_r>)
 //   dGam_t = z_t dz_t + p_t dp_t - s_t ds_t          (gradient w.r.t. the cumulative log gate)
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm,
                 x[e] = y[e] = 0.f;
                 if (i < M) {
                     const float G = Gs[t * L::ldg + i];
-                    x[e] = Df[t * L::ldg + i] * __expf(G);
+                    x[e] = scale * Df[t * L::ldg + i] * __expf(G);
                     y[e] = Ss[t * L::ldg + i] * __expf(Gs[(C - 1) * L::ldg + i] - G);
                 }
             }
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm,
             for (int j = 0; j < 4; ++j) {
                 const int t = rowb + g4 + j;
                 const bool keep = (ni <= w) && (rr <= t);
-                bv[j] = keep ? accB[ni][j] : 0.f;
+                bv[j] = keep ? scale * accB[ni][j] : 0.f;
                 av[j] = keep ? acc2[ni][j] : 0.f;
                 ATs[t * L::lda + rr] = from_f32<T>(bv[j]);     // Bm in natural orientation, staged for a row-wise copy
             }
@@ -560,9 +560,9 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     }
     // 5. dq, dk, dv
     const ApplyIo io[3] = {
-        {w.tA, w.tP, k, w.S, pl.layS_bwd.oKt, pl.layS_bwd.stride, dq, pl.d_k, pl.scale, pl.scale},
-        {w.tBT, w.tSbe, q, w.E, pl.layE.oKt, pl.layE.stride, dk, pl.d_k, pl.scale, 1.f},
-        {w.tA2T, w.tSbe, dO, w.E, pl.layE.oVt, pl.layE.stride, dv, pl.d_v, 1.f, 1.f},
+        {w.tA, w.tP, k, w.S, pl.layS_bwd.oKt, pl.layS_bwd.stride, dq, pl.d_k},
+        {w.tBT, w.tSbe, q, w.E, pl.layE.oKt, pl.layE.stride, dk, pl.d_k},
+        {w.tA2T, w.tSbe, dO, w.E, pl.layE.oVt, pl.layE.stride, dv, pl.d_v},
     };
     return launch_apply(pl, w, io, 3, kSlotApplyBwd, st);
 }

@@ -256,7 +256,7 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
                            (const T *)k, g, (const T *)w.S, pl.layS_fwd, z_saved, (T *)w.tA, (T *)w.tP);
         GSA_HIP_TRY(hipGetLastError());
     }
-    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.layS_fwd.oVt, pl.layS_fwd.stride, o, pl.d_v, 1.f, 1.f};
+    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.layS_fwd.oVt, pl.layS_fwd.stride, o, pl.d_v};
     return launch_apply(pl, w, &io, 1, kSlotApplyFwd, st);
 }
 

@@ -32,12 +32,12 @@ struct Work {
     void *Wf;         // [m][C]      forward scan weights s*exp(G_C-G)
     float *dec;       // [m]         chunk decay exp(G_C)                                  (fp32)
     void *S;          // memory at the start of the chunk, blocks per Plan::layS_fwd / layS_bwd
-    void *tA;         // [C][C]      forward: pair weights A2;  backward: Bm
-    void *tP;         // [C][KM]     forward: p*exp(G);         backward: dz*exp(G)
+    void *tA;         // [C][C]      forward: pair weights A2;  backward: scale*Bm
+    void *tP;         // [C][KM]     forward: p*exp(G);         backward: scale*dz*exp(G)
     void *SF;         // per (sequence, head): memory after the last token (Plan::laySF)
     void *Wr;         // [2][m][C]   reverse scan weights
     void *E;          // gradient of the memory at the end of the chunk (Plan::layE)
-    void *tBT;        // [C][C]      Bm^T
+    void *tBT;        // [C][C]      scale*Bm^T
     void *tA2T;       // [C][C]      A2^T
     void *tAvT;       // [C][C]      (dO_t . v_r)^T, causally masked
     void *tSbe;       // [C][KM]     s*exp(G_C-G)
@@ -82,7 +82,7 @@ struct ScanIo {
 };
 hipError_t launch_scan(const Plan &pl, const Work &w, const ScanIo &io, hipStream_t st);
 
-// The wide contractions out = s_tok * A_tok X + s_slot * A_slot St for up to three outputs in one
+// The wide contractions out = A_tok X + A_slot St for up to three outputs in one
 // launch (see gsa_apply.hip).  xslot_rec + xslot_off points at a transposed memory block [d][m] of
 // the first (chunk, head) record; records are xslot_stride elements apart.
 struct ApplyIo {
@@ -90,7 +90,6 @@ struct ApplyIo {
     long long xslot_off, xslot_stride;
     void *out;
     int d;
-    float s_tok, s_slot;
 };
 hipError_t launch_apply(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st);
 
