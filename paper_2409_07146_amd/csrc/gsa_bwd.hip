@@ -154,18 +154,6 @@ template <typename T> __device__ __forceinline__ float frag_dot(const typename A
     return d;
 }
 
-// four consecutive elements of one row, from fp32
-__device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d)
-{
-    bf16x4 x;
-    x[0] = (bf16_t)a; x[1] = (bf16_t)b; x[2] = (bf16_t)c; x[3] = (bf16_t)d;
-    *reinterpret_cast<bf16x4 *>(p) = x;
-}
-__device__ __forceinline__ void store4(float *p, float a, float b, float c, float d)
-{
-    *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
-}
-
 template <typename T, int M> struct IntraLds {
     static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;

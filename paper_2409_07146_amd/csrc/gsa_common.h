@@ -178,6 +178,18 @@ template <> struct Raw8<float> {
     }
 };
 
+// four consecutive elements of one row, from fp32
+__device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d)
+{
+    bf16x4 x;
+    x[0] = (bf16_t)a; x[1] = (bf16_t)b; x[2] = (bf16_t)c; x[3] = (bf16_t)d;
+    *reinterpret_cast<bf16x4 *>(p) = x;
+}
+__device__ __forceinline__ void store4(float *p, float a, float b, float c, float d)
+{
+    *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
+}
+
 // dst[r][c] = src[r][c]   (dst row stride ld)
 template <typename T, typename Tin>
 __device__ __forceinline__ void stage_rows(T *dst, int ld, const Tin *src, size_t gld, int rows, int cols,

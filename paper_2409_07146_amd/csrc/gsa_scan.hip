@@ -77,7 +77,7 @@ template <typename T, int M, int NS> struct ScanLds {
 };
 
 template <typename T, int M, int NS, bool REVERSE>
-__global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, int d_k, int d_v, int n_seqs,
+__global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H, int d_k, int d_v, int n_seqs,
                                                           ScanArgs<T> a)
 {
     using L = ScanLds<T, M, NS>;
@@ -126,95 +126,104 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
                 }
     }
 
-    Raw8<T> wreg[WV];
-    TokTile<T, C, NS, NT> xt;   // token tile of the next chunk, transposed (and swizzled) when it enters LDS
-    float decr[MI][4];
-    auto fetch = [&](int n) {
+    // Operands of one chunk, staged in registers: the loads of the next two chunks are in flight
+    // while the current one multiplies (one chunk ahead does not cover the memory latency of a
+    // loaded chip, and the chain over the chunks is the only sequential part of the method).
+    struct Stage {
+        Raw8<T> wreg[WV];
+        TokTile<T, C, NS, NT> xt;   // transposed (and swizzled) when it enters LDS
+        f32x4 dec[MI];
+    };
+    auto fetch = [&](Stage &st, int n) {
         const size_t ch = (size_t)(chunk0 + n) * H + h;
         const T *Wg = a.W + ch * a.w_parts * M * C + wpart;
 #pragma unroll
         for (int u = 0; u < WV; ++u) {
             const int idx = tid + NT * u;
-            wreg[u].load(Wg + (size_t)(idx < WVEC ? idx : 0) * 8);
+            st.wreg[u].load(Wg + (size_t)(idx < WVEC ? idx : 0) * 8);
         }
         const int len = min(C, ntok - n * C);
         const T *Xg = src + ((size_t)(tok0 + n * C) * H + h) * dsrc + c0;
-        xt.load(Xg, (size_t)H * dsrc, len, NS, tid);
+        st.xt.load(Xg, (size_t)H * dsrc, len, NS, tid);
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) decr[mi][j] = a.dec[ch * M + mi * 16 + g4 + j];
+        for (int mi = 0; mi < MI; ++mi) st.dec[mi] = *reinterpret_cast<const f32x4 *>(a.dec + ch * M + mi * 16 + g4);
     };
     // accumulator -> LDS in the layouts the record asks for (natural [m][cols], transposed [cols][m])
     auto snapshot_to_lds = [&](const StateLayout &lay) {
         const bool nat = (isK ? lay.oKn : lay.oVn) >= 0, tr = (isK ? lay.oKt : lay.oVt) >= 0;
+        if (tr) {   // a lane holds four consecutive slots of one column: one 4-element store each
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
+                    store4(St + (wcol + ni * 16 + r) * L::ldt + mi * 16 + g4, acc[mi][ni][0], acc[mi][ni][1],
+                           acc[mi][ni][2], acc[mi][ni][3]);
+        }
+        if (nat) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const T x = from_f32<T>(acc[mi][ni][j]);
-                    if (nat) Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = x;
-                    if (tr) St[(wcol + ni * 16 + r) * L::ldt + mi * 16 + g4 + j] = x;
-                }
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+        }
     };
     auto snapshot_to_global = [&](T *rec, const StateLayout &lay) {   // rec: start of the (chunk, head) record
+        // LDS reads first (clamped, unconditional), then the stores: no read sits under a branch
         const long long oN = isK ? lay.oKn : lay.oVn, oT = isK ? lay.oKt : lay.oVt;
         if (oN >= 0) {
+            Raw8<T> x[SV];
 #pragma unroll
             for (int u = 0; u < SV; ++u) {
-                const int idx = tid + NT * u;
-                if (idx < SVEC) {
-                    const int i = idx / (NS / 8), cg = idx - i * (NS / 8);
-                    Raw8<T> x;
-                    x.load(Sn + i * L::lds + cg * 8);
-                    x.store(rec + oN + (size_t)i * dsrc + c0 + cg * 8);
-                }
+                const int idx = min(tid + NT * u, SVEC - 1), i = idx / (NS / 8), cg = idx - i * (NS / 8);
+                x[u].load(Sn + i * L::lds + cg * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < SV; ++u) {
+                const int idx = tid + NT * u, i = idx / (NS / 8), cg = idx - i * (NS / 8);
+                if (SVEC % NT == 0 || idx < SVEC) x[u].store(rec + oN + (size_t)i * dsrc + c0 + cg * 8);
             }
         }
         if (oT >= 0) {
+            Raw8<T> x[SV];
 #pragma unroll
             for (int u = 0; u < SV; ++u) {
-                const int idx = tid + NT * u;
-                if (idx < SVEC) {
-                    const int c = idx / (M / 8), ig = idx - c * (M / 8);
-                    Raw8<T> x;
-                    x.load(St + c * L::ldt + ig * 8);
-                    x.store(rec + oT + (size_t)(c0 + c) * M + ig * 8);
-                }
+                const int idx = min(tid + NT * u, SVEC - 1), c = idx / (M / 8), ig = idx - c * (M / 8);
+                x[u].load(St + c * L::ldt + ig * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < SV; ++u) {
+                const int idx = tid + NT * u, c = idx / (M / 8), ig = idx - c * (M / 8);
+                if (SVEC % NT == 0 || idx < SVEC) x[u].store(rec + oT + (size_t)(c0 + c) * M + ig * 8);
             }
         }
     };
 
-    if (nch > 0) fetch(REVERSE ? nch - 1 : 0);
-    for (int it = 0; it < nch; ++it) {
+    // One chunk: staged registers -> LDS (W as is, X transposed), accumulator snapshot -> LDS and on to
+    // global memory, refill the stage with the chunk two steps on, then S <- Diag(dec) S + W X.
+    auto step = [&](Stage &st, int it) {
         const int n = REVERSE ? nch - 1 - it : it;
-        // staged registers -> LDS (W as is, X transposed), accumulator snapshot -> LDS
 #pragma unroll
         for (int u = 0; u < WV; ++u) {
             const int idx = tid + NT * u;
             if (idx < WVEC) {
                 const int i = idx / (C / 8), tg = idx - i * (C / 8);
-                wreg[u].store(We + i * L::ldw + tg * 8);
+                st.wreg[u].store(We + i * L::ldw + tg * 8);
             }
         }
-        xt.store_transposed(XT, L::ldw, NS, tid);
+        st.xt.store_transposed(XT, L::ldw, NS, tid);
         snapshot_to_lds(a.lay);
-        float dcur[MI][4];
+        f32x4 dcur[MI];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) dcur[mi][j] = decr[mi][j];
+        for (int mi = 0; mi < MI; ++mi) dcur[mi] = st.dec[mi];
         __syncthreads();
-        if (it + 1 < nch) fetch(REVERSE ? n - 1 : n + 1);
+        if (it + 2 < nch) fetch(st, REVERSE ? n - 2 : n + 2);
         snapshot_to_global(a.snap + ((size_t)(chunk0 + n) * H + h) * a.lay.stride, a.lay);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) acc[mi][ni][j] *= dcur[mi][j];
+            for (int ni = 0; ni < NI; ++ni) acc[mi][ni] *= dcur[mi];
 #pragma unroll
         for (int k0 = 0; k0 < C; k0 += 32) {
             typename Atom<T>::Frag af[MI], bf[NI];
@@ -228,6 +237,13 @@ __global__ __launch_bounds__(Geo<T>::NT) void scan_kernel(ChunkMap cm, int H, in
                 for (int ni = 0; ni < NI; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bf[ni]);
         }
         __syncthreads();
+    };
+    Stage sa, sb;
+    if (nch > 0) fetch(sa, REVERSE ? nch - 1 : 0);
+    if (nch > 1) fetch(sb, REVERSE ? nch - 2 : 1);
+    for (int it = 0; it < nch; it += 2) {
+        step(sa, it);
+        if (it + 1 < nch) step(sb, it + 1);
     }
     // accumulator after the last chunk
     float *ST = isK ? a.outK : a.outV;
@@ -305,15 +321,8 @@ static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io
     a.outV = io.outV;
     a.outJ = static_cast<T *>(io.outJ);
     a.layJ = io.layJ;
-    // 64-column slices put two or more workgroups on a CU so their dependent chains overlap; the wider
-    // slice (fewer re-reads of the gate weights) only pays once the grid is far larger than the chip
-    const bool wide = (pl.d_k % 128 == 0) && (pl.d_v % 128 == 0) &&
-                      ((int64_t)pl.n_seqs * pl.H * ((pl.d_k + pl.d_v) / 128) >= 1024);
-    if (io.reverse) {
-        if (wide) return run_scan<T, M, 128, true>(pl, cm, a, st);
-        return run_scan<T, M, 64, true>(pl, cm, a, st);
-    }
-    if (wide) return run_scan<T, M, 128, false>(pl, cm, a, st);
+    // 64-column slices: several workgroups per CU, so that their dependent chains overlap
+    if (io.reverse) return run_scan<T, M, 64, true>(pl, cm, a, st);
     return run_scan<T, M, 64, false>(pl, cm, a, st);
 }
 
