@@ -88,8 +88,20 @@ def main():
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
+    # yardstick: a plain device copy of 256 MiB (512 MiB of traffic) through the library's probe kernel
     prof = gsa.gsa_profile_read()
+    cp_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    cp_dst = torch.empty_like(cp_src)
+    for _ in range(3):
+        gsa.gsa_profile_copy(cp_dst, cp_src)      # first touches of the destination
+    torch.cuda.synchronize()
+    gsa.gsa_profile_reset()
+    for _ in range(10):
+        gsa.gsa_profile_copy(cp_dst, cp_src)
+    torch.cuda.synchronize()
+    prof["copy_probe_kernel"] = gsa.gsa_profile_read()["copy_probe_kernel"]
     gsa.gsa_profile_enable(False)
+    del cp_src, cp_dst
     kern_ms = {n: ms / max(cnt, 1) for n, (ms, cnt) in prof.items() if cnt}
     esz = 2 if cfg.dtype == "bf16" else 4
     fwd_b, bwd_b = per_token_bytes(cfg, esz)
@@ -110,8 +122,17 @@ def main():
     achieved = alg_bytes[dom] / (kern_ms[dom] * 1e-3) / 1e9
     ffl, bfl, aff, abf = per_token_head_flops(cfg)
     exec_flops = (ffl + bfl) * tokens * cfg.H
+    # HBM traffic per launch of that kernel, from hardware counters collected in separate profiler
+    # runs of this same command (stored next to their summaries); None when no such record exists
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % cfg.name)
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            rec = json.load(f).get("kernels", {}).get(dom)
+        if rec:
+            traffic = int(rec["fetch_bytes"] + rec["write_bytes"])
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_ms": round(kern_ms[dom], 4),
                 "algorithmic_bytes_per_launch": alg_bytes[dom]}
 
@@ -169,6 +190,8 @@ def main():
                  "frac_hbm_peak": round((fwd_b + bwd_b) * tokens / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                  "kernel_ms": {n: round(ms, 4) for n, ms in kern_ms.items()}},
         "decode": dec,
+        "copy_probe": {"bytes_moved": 2 * (256 << 20), "us": round(kern_ms["copy_probe_kernel"] * 1e3, 2),
+                       "GB_per_s": round(2 * (256 << 20) / (kern_ms["copy_probe_kernel"] * 1e-3) / 1e9, 1)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

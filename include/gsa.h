@@ -141,6 +141,15 @@ gsa_status gsa_profile_enable(int on);
 gsa_status gsa_profile_reset(void);
 gsa_status gsa_profile_read(int32_t index, const char **name, double *ms, int64_t *launches);
 
+/*
+ * Bandwidth probe: copies `bytes` (a multiple of 16) from device memory `src` to device
+ * memory `dst` (both 16-byte aligned, not overlapping) with one plain kernel
+ * ("copy_probe_kernel") on `stream`.  It reads and writes exactly `bytes` each, which makes
+ * it the yardstick for hardware memory counters and for the copy rate this chip sustains.
+ * Timed in slot "copy_probe_kernel" while profiling is enabled.
+ */
+gsa_status gsa_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

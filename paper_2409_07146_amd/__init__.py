@@ -3,5 +3,5 @@
 The package is a thin binding over the C-ABI library `libgsa.so` built from `csrc/`.
 """
 from .api import (GsaError, alloc_workspace, gsa_bwd, gsa_decode_step, gsa_fwd,  # noqa: F401
-                  gsa_profile_enable, gsa_profile_read, gsa_profile_reset, gsa_workspace_bytes,
+                  gsa_profile_copy, gsa_profile_enable, gsa_profile_read, gsa_profile_reset, gsa_workspace_bytes,
                   make_problem)

@@ -7,7 +7,7 @@ LIB_PATH = os.path.join(_HERE, "libgsa.so")
 
 # every symbol include/gsa.h declares
 EXPORTS = ("gsa_status_string", "gsa_abi_version", "gsa_workspace_bytes", "gsa_fwd", "gsa_bwd",
-           "gsa_decode_step", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read")
+           "gsa_decode_step", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read", "gsa_profile_copy")
 
 
 class GsaProblem(ctypes.Structure):
@@ -50,5 +50,7 @@ def load():
     lib.gsa_profile_read.restype = ctypes.c_int
     lib.gsa_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_int64)]
+    lib.gsa_profile_copy.restype = ctypes.c_int
+    lib.gsa_profile_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib

@@ -155,6 +155,18 @@ def gsa_profile_reset() -> None:
     _lib.load().gsa_profile_reset()
 
 
+def gsa_profile_copy(dst, src) -> None:
+    """Plain device copy src -> dst with the library's probe kernel (same byte count read and written)."""
+    if dst.device != src.device or not dst.is_cuda or not dst.is_contiguous() or not src.is_contiguous():
+        raise ValueError("dst and src must be contiguous tensors on the same GPU")
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src must hold the same number of bytes")
+    rc = _lib.load().gsa_profile_copy(_ptr(dst), _ptr(src), nbytes, _stream(src))
+    if rc != 0:
+        raise GsaError(rc, "gsa_profile_copy")
+
+
 def gsa_profile_read():
     """Returns {kernel name: (milliseconds, launches)} accumulated since the last reset."""
     lib = _lib.load()

@@ -47,7 +47,7 @@ struct Work {
 
 // Kernel slots of the optional per-kernel event timing (gsa_profile_*).
 enum KernelSlot { kSlotPrepare = 0, kSlotGates, kSlotScanFwd, kSlotChunkFwd, kSlotApplyFwd, kSlotChunkDz, kSlotScanBwd,
-                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kNumKernelSlots };
+                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kSlotCopyProbe, kNumKernelSlots };
 
 // Brackets one kernel launch with events on its stream when timing is enabled; otherwise a no-op.
 class KernelTimer {

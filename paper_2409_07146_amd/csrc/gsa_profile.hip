@@ -2,6 +2,7 @@
 // roofline measurements).  Disabled by default: then a KernelTimer costs one relaxed load.
 #include "../../include/gsa.h"
 #include "gsa_internal.h"
+#include "gsa_common.h"
 
 #include <atomic>
 #include <mutex>
@@ -22,7 +23,7 @@ struct Slot {
 };
 Slot g_slots[kNumKernelSlots] = {{"prepare_kernel"}, {"gate_kernel"},      {"scan_fwd_kernel"}, {"chunk_fwd_kernel"},
                                  {"apply_fwd_kernel"}, {"chunk_dz_kernel"}, {"scan_bwd_kernel"}, {"chunk_intra_kernel"},
-                                 {"apply_bwd_kernel"}, {"decode_kernel"}};
+                                 {"apply_bwd_kernel"}, {"decode_kernel"}, {"copy_probe_kernel"}};
 
 hipEvent_t take_event(Slot &s)
 {
@@ -72,9 +73,34 @@ KernelTimer::~KernelTimer()
     s.pending.emplace_back(static_cast<hipEvent_t>(start_), e);
 }
 
+// 16 bytes per thread and iteration, consecutive threads on consecutive addresses.
+__global__ __launch_bounds__(256) void copy_probe_kernel(f32x4 *__restrict__ dst, const f32x4 *__restrict__ src,
+                                                         size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
 }  // namespace gsa
 
 extern "C" {
+
+gsa_status gsa_profile_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src) return GSA_ERR_NULL;
+    if (bytes % 16 || (reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16) return GSA_ERR_SHAPE;
+    if (bytes == 0) return GSA_OK;
+    const size_t n = bytes / 16;
+    const size_t want = (n + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 256 * 32 ? want : 256 * 32);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        gsa::KernelTimer kt(gsa::kSlotCopyProbe, st);
+        hipLaunchKernelGGL(gsa::copy_probe_kernel, dim3(blocks), dim3(256), 0, st, static_cast<gsa::f32x4 *>(dst),
+                           static_cast<const gsa::f32x4 *>(src), n);
+    }
+    return hipGetLastError() == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
 
 gsa_status gsa_profile_enable(int on)
 {
