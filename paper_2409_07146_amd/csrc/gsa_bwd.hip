@@ -44,12 +44,12 @@ template <typename T, int M> struct DzLds {
     static constexpr size_t oTot = oA;   // gate_prep's scratch, dead before As is written
     static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                   : sizeof(float) * Geo<T>::NT;
-    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // aliases As
-    static constexpr size_t bytes = oA + (szA > szRed ? szA : szRed);
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
+    static constexpr size_t bytes = (oA + szA > szRed) ? oA + szA : szRed;
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
+__global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
                                                               const T *__restrict__ v, const T *__restrict__ dO,
                                                               const float *__restrict__ g, const float *__restrict__ z,
                                                               const T *__restrict__ S, StateLayout lay,
@@ -66,20 +66,21 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_dz_kernel(ChunkMap cm, int H
     T *As = reinterpret_cast<T *>(smem + L::oA);
 
     ChunkInfo ci;
-    if (!chunk_lookup(cm, blockIdx.x, ci)) return;
-    const int h = blockIdx.y;
+    int cid, h;
+    chunk_order(cm, H, true, cid, h);   // the forward scan has just written the last chunks
+    if (!chunk_lookup(cm, cid, ci)) return;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const size_t ch = (size_t)blockIdx.x * H + h;
+    const size_t ch = (size_t)cid * H + h;
     const T *Vn = S + ch * lay.stride + lay.oVn;      // value memory at chunk start [M][d_v]
     const int rowb = 16 * w;
 
-    gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
     float dp[MI][4];
     bool unsafe;
-    gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, As, L::lda, reinterpret_cast<f32x4 *>(smem + L::oA),
-                          dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn, (size_t)d_v, ci.len, tid);
+    gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
+                          reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn,
+                          (size_t)d_v, ci.len, tid);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -200,12 +201,13 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm,
     T *ATs = reinterpret_cast<T *>(smem + L::oAT);           // [r][t] (q_t . k_r) for t >= r; later Bm [t][r]
 
     ChunkInfo ci;
-    if (!chunk_lookup(cm, blockIdx.x, ci)) return;
-    const int h = blockIdx.y;
+    int cid, h;
+    chunk_order(cm, H, false, cid, h);   // the reverse scan has just written the first chunks
+    if (!chunk_lookup(cm, cid, ci)) return;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const size_t ch = (size_t)blockIdx.x * H + h;
+    const size_t ch = (size_t)cid * H + h;
     const T *EK = a.E + ch * a.layE.stride + a.layE.oKn;     // memory gradient at chunk end, natural
     const T *EV = a.E + ch * a.layE.stride + a.layE.oVn;
     int chunk0, nch, stok0, sntok;

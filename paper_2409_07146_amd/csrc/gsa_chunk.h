@@ -87,12 +87,16 @@ __device__ __forceinline__ void reduce_row_blocks(f32x4 (&own)[NB], const f32x4 
 // for the two halves of a 128-byte line at about the same time, so each line crosses the
 // memory system once.  The partial sums meet through Red (see reduce_row_blocks; Red may
 // alias As).  d must be a multiple of 32.
-// LDS: Gs, Ss filled by gate_prep; As [C][lda] is left holding the causally masked X Y^T
-// rounded to T.  All threads of the workgroup must call it.
+// The gate tiles Gs, Ss are produced in here as well (from g: [len][M] fp32, row stride gld;
+// `tot`: scratch of NT floats): the gate loads are issued after the contraction and land during
+// the reduction, and the tiles are written once the reduction buffer is dead, so Red may alias
+// Gs and Ss too.  As [C][lda] is left holding the causally masked X Y^T rounded to T.
+// All threads of the workgroup must call it.
 template <typename T, int M, int C>
-__device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, const float *Gs, const float *Ss,
-                                             int ldg, T *As, int lda, f32x4 *Red, const T *X, const T *Y, size_t ldx,
-                                             int d, const T *St, size_t ldst, int len, int tid)
+__device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
+                                             float *tot, const float *g, size_t gld, T *As, int lda, f32x4 *Red,
+                                             const T *X, const T *Y, size_t ldx, int d, const T *St, size_t ldst,
+                                             int len, int tid)
 {
     constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -130,12 +134,15 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
                 for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fx[rb], fs[ni]);
             }
         }
+        GatePrep<M, Geo<T>::NT, C> gp;
+        gp.load(g, gld, len, tid);
         f32x4 own[NB];
         reduce_row_blocks<NW, NB, CI>(own, acc, Red, lane, w);
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) accA[ni] = own[ni];
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) accZ[ni] = own[CI + ni];
+        gp.finish(Gs, Ss, ldg, tot, len, tid);
     }
     // causally masked X Y^T, as an operand
 #pragma unroll

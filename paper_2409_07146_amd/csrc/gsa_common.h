@@ -261,6 +261,27 @@ __device__ __forceinline__ bool chunk_lookup(const ChunkMap &cm, int c, ChunkInf
     return true;
 }
 
+// Which (chunk, head) a workgroup of a chunk-parallel kernel takes, for a grid of
+// (n_chunk_slots, H) workgroups dispatched x-fastest.  Workgroups are handed out so that all
+// sequences and heads advance through their chunks together, newest_first = from the last chunk
+// of every sequence backwards: a kernel that follows a scan then starts on the snapshots the scan
+// wrote last, which are the ones still sitting in the memory-side cache.
+__device__ __forceinline__ void chunk_order(const ChunkMap &cm, int H, bool newest_first, int &chunk, int &head)
+{
+    const int b = blockIdx.y * gridDim.x + blockIdx.x;
+    if (cm.table) {
+        const int c = b / H;
+        head = b - c * H;
+        chunk = newest_first ? cm.n_chunk_slots - 1 - c : c;
+        return;
+    }
+    const int n = cm.chunks_per_seq, per = (cm.n_chunk_slots / n) * H;   // per: (sequence, head) pairs
+    const int rank = b / per, rem = b - rank * per;
+    const int seq = rem / H;
+    head = rem - seq * H;
+    chunk = seq * n + (newest_first ? n - 1 - rank : rank);
+}
+
 // First chunk id, number of chunks and first token of sequence s.
 __device__ __forceinline__ void seq_lookup(const ChunkMap &cm, int s, int &chunk0, int &nchunks, int &tok0, int &ntok)
 {
@@ -285,38 +306,51 @@ __device__ __forceinline__ void seq_lookup(const ChunkMap &cm, int s, int &chunk
 // Rows t >= len are padded with g = 0.  Needs blockDim.x = NT threads, NT % M == 0,
 // C % (NT/M) == 0, and `tot` scratch of NT floats.  Ends with a __syncthreads().
 // ----------------------------------------------------------------------------
+template <int M, int NT, int C> struct GatePrep {
+    static constexpr int P = NT / M;     // token partitions
+    static constexpr int TP = C / P;     // tokens per partition
+    static_assert(NT % M == 0 && C % P == 0, "gate_prep partitioning");
+    float gv[TP];
+    // Issues the loads (rows clamped into the chunk).  May be called well before finish() so that
+    // other work hides the latency.
+    __device__ __forceinline__ void load(const float *g, size_t gld, int len, int tid)
+    {
+        const int i = tid % M, part = tid / M;
+#pragma unroll
+        for (int tt = 0; tt < TP; ++tt) gv[tt] = g[(size_t)min(part * TP + tt, len - 1) * gld + i];
+    }
+    // Fills Gs, Ss.  Contains barriers (all threads must call it) and ends with one.
+    __device__ __forceinline__ void finish(float *Gs, float *Ss, int ldg, float *tot, int len, int tid) const
+    {
+        const int i = tid % M, part = tid / M;
+        float run = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < TP; ++tt) {
+            const int t = part * TP + tt;
+            const float x = (t < len) ? fmaxf(gv[tt], kGateFloor) : 0.f;
+            run += x;
+            Gs[t * ldg + i] = run;
+            Ss[t * ldg + i] = (t < len) ? -expm1f(x) : 0.f;
+        }
+        tot[part * M + i] = run;
+        __syncthreads();
+        float off = 0.f;
+        for (int pp = 0; pp < part; ++pp) off += tot[pp * M + i];
+        if (part > 0) {
+#pragma unroll 4
+            for (int tt = 0; tt < TP; ++tt) Gs[(part * TP + tt) * ldg + i] += off;
+        }
+        __syncthreads();
+    }
+};
+
 template <int M, int NT, int C>
 __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *tot, const float *g, size_t gld,
                                           int len, int tid)
 {
-    constexpr int P = NT / M;            // token partitions
-    constexpr int TP = C / P;            // tokens per partition
-    static_assert(NT % M == 0 && C % P == 0, "gate_prep partitioning");
-    const int i = tid % M, part = tid / M;
-    float gv[TP];
-#pragma unroll
-    for (int tt = 0; tt < TP; ++tt) {   // all loads first, rows clamped into the chunk
-        const int t = part * TP + tt;
-        gv[tt] = g[(size_t)min(t, len - 1) * gld + i];
-    }
-    float run = 0.f;
-#pragma unroll
-    for (int tt = 0; tt < TP; ++tt) {
-        const int t = part * TP + tt;
-        const float x = (t < len) ? fmaxf(gv[tt], kGateFloor) : 0.f;
-        run += x;
-        Gs[t * ldg + i] = run;
-        Ss[t * ldg + i] = (t < len) ? -expm1f(x) : 0.f;
-    }
-    tot[part * M + i] = run;
-    __syncthreads();
-    float off = 0.f;
-    for (int pp = 0; pp < part; ++pp) off += tot[pp * M + i];
-    if (part > 0) {
-#pragma unroll 4
-        for (int tt = 0; tt < TP; ++tt) Gs[(part * TP + tt) * ldg + i] += off;
-    }
-    __syncthreads();
+    GatePrep<M, NT, C> gp;
+    gp.load(g, gld, len, tid);
+    gp.finish(Gs, Ss, ldg, tot, len, tid);
 }
 
 // Fragment straight from global memory: 8 consecutive elements of one row.  Loads in this

@@ -92,12 +92,12 @@ template <typename T, int M> struct ChunkFwdLds {
     static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                   : sizeof(float) * Geo<T>::NT;
     static constexpr size_t oP = oA + szA;
-    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // aliases As, Ps
-    static constexpr size_t bytes = (oP + sizeof(T) * C * ldp > oA + szRed) ? oP + sizeof(T) * C * ldp : oA + szRed;
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
+    static constexpr size_t bytes = (oP + sizeof(T) * C * ldp > szRed) ? oP + sizeof(T) * C * ldp : szRed;
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
+__global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const float *__restrict__ g,
                                                                const T *__restrict__ S, StateLayout lay,
@@ -115,22 +115,22 @@ __global__ __launch_bounds__(Geo<T>::NT) void chunk_fwd_kernel(ChunkMap cm, int 
     T *Ps = reinterpret_cast<T *>(smem + L::oP);      // [C][ldp]  softmax weights in their gated forms
 
     ChunkInfo ci;
-    if (!chunk_lookup(cm, blockIdx.x, ci)) return;
-    const int h = blockIdx.y;
+    int cid, h;
+    chunk_order(cm, H, true, cid, h);   // the forward scan has just written the last chunks
+    if (!chunk_lookup(cm, cid, ci)) return;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const size_t tokh = (size_t)ci.tok0 * H + h;
-    const size_t ch = (size_t)blockIdx.x * H + h;
+    const size_t ch = (size_t)cid * H + h;
     const T *Kn = S + ch * lay.stride + lay.oKn;      // key memory at chunk start [M][d_k]
     const int rowb = 16 * w;                          // this wave's row block
-
-    gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, ci.len, tid);
 
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
     float p[MI][4];
     bool unsafe;
-    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, As, L::lda, reinterpret_cast<f32x4 *>(smem + L::oA),
-                          q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn, (size_t)d_k, ci.len, tid);
+    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
+                          reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn,
+                          (size_t)d_k, ci.len, tid);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void gate_kernel(ChunkMap cm, int H, co
                                                           T *__restrict__ Wf, float *__restrict__ dec)
 {
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
-    constexpr int ldg = M + 4;
+    constexpr int ldg = M + 1;   // odd row stride: the column reads below spread over all banks
     __shared__ float Gs[C * ldg];
     __shared__ float Ss[C * ldg];
     __shared__ float tot[NT];
@@ -40,9 +40,13 @@ __global__ __launch_bounds__(Geo<T>::NT) void gate_kernel(ChunkMap cm, int H, co
     const size_t ch = (size_t)blockIdx.x * H + h;
     gate_prep<M, NT, C>(Gs, Ss, ldg, tot, g + ((size_t)ci.tok0 * H + h) * M, (size_t)H * M, ci.len, tid);
     T *W = Wf + ch * M * C;
-    for (int idx = tid; idx < M * C; idx += NT) {
-        const int i = idx / C, t = idx - i * C;
-        W[idx] = from_f32<T>(Ss[t * ldg + i] * __expf(Gs[(C - 1) * ldg + i] - Gs[t * ldg + i]));
+    for (int idx = tid; idx < M * C / 8; idx += NT) {   // eight consecutive tokens of one slot per thread
+        const int i = idx / (C / 8), t8 = (idx - i * (C / 8)) * 8;
+        const float gc = Gs[(C - 1) * ldg + i];
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = Ss[(t8 + e) * ldg + i] * __expf(gc - Gs[(t8 + e) * ldg + i]);
+        store8<T>(W + i * C + t8, x);
     }
     if (tid < M) dec[ch * M + tid] = __expf(Gs[(C - 1) * ldg + tid]);
 }
