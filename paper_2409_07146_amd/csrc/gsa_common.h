@@ -385,7 +385,11 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
     static constexpr int NVEC = (C / 2) * (NCOLS / 8);          // (row pair, column group) items
     static constexpr int PER = (NVEC + NT - 1) / NT;
     Raw8<T> a[PER], b[PER];
-    // src: row 0 of the tile, column 0 of the slice; rows >= len read as zero; columns >= ncols skipped
+    bool la[PER], lb[PER];   // whether the row really exists (else it is written as zeros)
+    // src: row 0 of the tile, column 0 of the slice; rows >= len read as zero; columns >= ncols skipped.
+    // Only issues the loads: the masking of missing rows is left to store_transposed, so that nothing
+    // here waits for the data (a select right after the load would stall the wave for the full memory
+    // latency before it could issue anything else).
     __device__ __forceinline__ void load(const T *src, size_t gld, int len, int ncols, int tid)
     {
 #pragma unroll
@@ -400,8 +404,8 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             const int r0 = min(2 * rp, len - 1), r1 = min(2 * rp + 1, len - 1);
             a[u].load(src + (size_t)r0 * gld + cg * 8);
             b[u].load(src + (size_t)r1 * gld + cg * 8);
-            a[u].keep(ok && 2 * rp < len);
-            b[u].keep(ok && 2 * rp + 1 < len);
+            la[u] = ok && 2 * rp < len;
+            lb[u] = ok && 2 * rp + 1 < len;
         }
     }
     __device__ __forceinline__ void store_transposed(T *XT, int ld, int ncols, int tid) const
@@ -411,12 +415,15 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             const int idx = tid + NT * u;
             const int rp = idx / (NCOLS / 8), cg = idx - rp * (NCOLS / 8);
             if (idx < NVEC && cg * 8 < ncols) {
+                Raw8<T> x = a[u], y = b[u];
+                x.keep(la[u]);
+                y.keep(lb[u]);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     // two 2-byte stores: measured faster here than one packed 4-byte store
                     T *dst = XT + xt_off<C>(cg * 8 + e, 2 * rp, ld);
-                    dst[0] = a[u].get(e);
-                    dst[1] = b[u].get(e);
+                    dst[0] = x.get(e);
+                    dst[1] = y.get(e);
                 }
             }
         }

@@ -128,6 +128,10 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
                     const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
                     acc[mi][ni][j] = S0 ? S0[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
                 }
+        // Let these loads land before the loop's prefetches are issued: otherwise the first use of the
+        // accumulator inside the loop has to wait for "everything older", which the compiler can only
+        // express as "everything", and that would drain the prefetches in every iteration.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
     }
 
     // Operands of one chunk, staged in registers: the loads of the next two chunks are in flight
@@ -245,10 +249,12 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
     Stage sa, sb;
     if (nch > 0) fetch(sa, REVERSE ? nch - 1 : 0);
     if (nch > 1) fetch(sb, REVERSE ? nch - 2 : 1);
-    for (int it = 0; it < nch; it += 2) {
+    int it = 0;
+    for (; it + 1 < nch; it += 2) {   // two steps per trip: each stage keeps its own registers
         step(sa, it);
-        if (it + 1 < nch) step(sb, it + 1);
+        step(sb, it + 1);
     }
+    if (it < nch) step(sa, it);
     // accumulator after the last chunk
     float *ST = isK ? a.outK : a.outV;
     if (ST) {
