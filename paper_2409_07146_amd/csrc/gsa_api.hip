@@ -44,12 +44,9 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     const size_t esz = p->dtype == GSA_BF16 ? 2 : 4;
     const size_t M = p->m, dk = p->d_k, dv = p->d_v, D = dk + dv, C = pl->chunk, KM = M < 32 ? 32 : M;
     const size_t ch = (size_t)slots * p->H;                 // (chunk, head) records
-    // memory snapshots: forward keeps Kt natural and Vt transposed; the backward's recomputation
-    // keeps both natural plus Kt transposed; the memory gradient is kept in all four forms
-    pl->layS_fwd = {(long long)(M * D), 0, -1, -1, (long long)(M * dk)};
-    pl->layS_bwd = {(long long)(M * (D + dk)), 0, (long long)(M * dk), (long long)(M * D), -1};
-    pl->layE = {(long long)(2 * M * D), 0, (long long)(M * dk), (long long)(M * D), (long long)(M * D + M * dk)};
-    pl->laySF = {(long long)(M * D), 0, (long long)(M * dk), -1, -1};
+    // memory snapshots: every record is [Kt | Vt] in natural orientation, [m][d_k] then [m][d_v]
+    // (the apply kernel transposes the slices it needs on their way into LDS)
+    pl->lay = {(long long)(M * D), 0, (long long)(M * dk)};
     const size_t tokm = (size_t)tokens * p->H * M * sizeof(float);
     size_t off = 0;
     pl->off_table = off;  off += align_up(p->cu_seqlens ? (size_t)slots * 4 * sizeof(int32_t) : 0);
@@ -60,10 +57,10 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     pl->off_tP = off;     off += align_up(ch * C * KM * esz);
     pl->off_S = off;
     pl->total_fwd = off + align_up(ch * M * D * esz);
-    off += align_up(ch * M * (D + dk) * esz);
+    off += align_up(ch * M * D * esz);
     pl->off_SF = off;     off += align_up((size_t)pl->n_seqs * p->H * M * D * esz);
     pl->off_Wr = off;     off += align_up(ch * 2 * M * C * esz);
-    pl->off_E = off;      off += align_up(ch * 2 * M * D * esz);
+    pl->off_E = off;      off += align_up(ch * M * D * esz);
     pl->off_tBT = off;    off += align_up(ch * C * C * esz);
     pl->off_tA2T = off;   off += align_up(ch * C * C * esz);
     pl->off_tAvT = off;   off += align_up(ch * C * C * esz);

@@ -13,12 +13,13 @@
 //              dk = Bm^T Q  + (s e^{G_C-G}) E_k
 //              dv = A2^T dO + (s e^{G_C-G}) E_v
 //
-// One workgroup per (column slice, chunk, head, output).  LDS holds only the transposed token
-// tile (contraction over tokens needs token-fastest operands; the tile is written with an XOR
-// swizzle so the transposing stores spread over all banks) and is reused for the output tile.
-// The small matrices and the slot memories (stored transposed by the scans) are read as
-// fragments straight from global memory.  ~18 KB of LDS per workgroup, so many workgroups
-// are resident per CU and their loads overlap.
+// One workgroup per (column slice, chunk, head, output).  Both wide operands arrive with the
+// column index fastest (token rows; rows of the slot memory as the scans store it) while the
+// matrix cores want the contraction index fastest, so each is loaded with whole-row 16-byte
+// loads and transposed on its way into LDS (XOR-swizzled so the transposing stores spread over
+// all banks).  One LDS tile serves the slot operand, then the token operand, then the output
+// tile; the two small matrices are staged once per workgroup.  ~37 KB of LDS per workgroup, so
+// several workgroups are resident per CU and their loads overlap.
 #include "gsa_chunk.h"
 #include "gsa_launch.h"
 
@@ -28,7 +29,7 @@ template <typename T> struct ApplyOne {
     const T *A_tok;       // [chunk][H][C][C]
     const T *A_slot;      // [chunk][H][C][KM]
     const T *xtok;        // [tokens][H][d]
-    const T *xslotT;      // record base + block offset: [d][M] per (chunk, head)
+    const T *xslot;       // record base + block offset: [M][d] per (chunk, head)
     long long xs_stride;  // elements per (chunk, head) record
     T *out;               // [tokens][H][d]
     int d;
@@ -40,8 +41,8 @@ template <typename T, int M> struct ApplyLds {
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int NS = (sizeof(T) == 2) ? 128 : 64;
     static constexpr int KM = (M < 32) ? 32 : M;
-    static constexpr int lda = C + PAD, ldo = NS + PAD, lds = KM + PAD;
-    static constexpr size_t szX = sizeof(T) * NS * lda, szO = sizeof(T) * C * ldo;
+    static constexpr int lda = C + PAD, ldo = NS + PAD, lds = KM + PAD, ldm = M + PAD;
+    static constexpr size_t szX = sizeof(T) * NS * (lda > ldm ? lda : ldm), szO = sizeof(T) * C * ldo;
     static constexpr size_t oAt = szX > szO ? szX : szO;          // A_tok  [C][lda]
     static constexpr size_t oAs = oAt + sizeof(T) * C * lda;      // A_slot [C][lds]
     static constexpr size_t bytes = oAs + sizeof(T) * C * lds;
@@ -95,35 +96,36 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
             if (idx < VS) xs[u].store(Ass + t * L::lds + c8);
         }
     }
-    // slot-memory fragments straight from global memory (each wave has its own columns)
-    typename Atom<T>::Frag bs[KM / 32][NIo];
-    {
-        const T *Bs = a.xslotT + ch * a.xs_stride + (size_t)cs * M;
-#pragma unroll
-        for (int ks = 0; ks < KM / 32; ++ks)
-#pragma unroll
-            for (int ni = 0; ni < NIo; ++ni) {
-                // clamped to the slice and to the real slots: the load is unconditional and stays inside the block
-                const int c = min(wcol + ni * 16 + r, ncols - 1);
-                const SlotSpan<M, KM> sp(ks * 32 + g8);
-                bs[ks][ni] = gfrag<T>(Bs + (size_t)c * M + sp.i0, sp.live);
-            }
-    }
-    tt.store_transposed(XT, L::lda, ncols, tid);
+    // the slot memory's column slice, rows = slots
+    TokTile<T, M, L::NS, NT> ts;
+    ts.load(a.xslot + ch * a.xs_stride + cs, (size_t)a.d, M, ncols, tid);
+    ts.store_transposed(XT, L::ldm, ncols, tid);
     __syncthreads();
     f32x4 acc[CI][NIo];
     zero_acc(acc);
     if (active) {
 #pragma unroll
         for (int ks = 0; ks < KM / 32; ++ks) {
-            typename Atom<T>::Frag af[CI];
+            typename Atom<T>::Frag af[CI], bf[NIo];
 #pragma unroll
             for (int mi = 0; mi < CI; ++mi) af[mi] = Atom<T>::load(Ass + (mi * 16 + r) * L::lds + ks * 32 + g8);
+            const SlotSpan<M, KM> sp(ks * 32 + g8);   // padded slots re-read real ones and are zeroed
+#pragma unroll
+            for (int ni = 0; ni < NIo; ++ni) {
+                const typename Atom<T>::Frag f = Atom<T>::load(XT + xt_off<M>(wcol + ni * 16 + r, sp.i0, L::ldm));
+                const typename Atom<T>::Frag z = Atom<T>::zero();
+                bf[ni] = sp.live ? f : z;
+            }
 #pragma unroll
             for (int mi = 0; mi < CI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bs[ks][ni]);
+                for (int ni = 0; ni < NIo; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bf[ni]);
         }
+    }
+    __syncthreads();   // the slot tile is dead: the token tile takes its place
+    tt.store_transposed(XT, L::lda, ncols, tid);
+    __syncthreads();
+    if (active) {
 #pragma unroll
         for (int k0 = 0; k0 < C; k0 += 32) {
             typename Atom<T>::Frag af[CI], bf[NIo];
@@ -164,7 +166,7 @@ static hipError_t launch_apply_tm(const Plan &pl, const Work &w, const ApplyIo *
         o.A_tok = static_cast<const T *>(s.A_tok);
         o.A_slot = static_cast<const T *>(s.A_slot);
         o.xtok = static_cast<const T *>(s.xtok);
-        o.xslotT = static_cast<const T *>(s.xslot_rec) + s.xslot_off;
+        o.xslot = static_cast<const T *>(s.xslot_rec) + s.xslot_off;
         o.xs_stride = s.xslot_stride;
         o.out = static_cast<T *>(s.out);
         o.d = s.d;

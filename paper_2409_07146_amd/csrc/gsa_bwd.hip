@@ -73,7 +73,7 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_dz_kernel(ChunkMap cm, in
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const size_t ch = (size_t)cid * H + h;
-    const T *Vn = S + ch * lay.stride + lay.oVn;      // value memory at chunk start [M][d_v]
+    const T *Vn = S + ch * lay.stride + lay.oV;      // value memory at chunk start [M][d_v]
     const int rowb = 16 * w;
 
     float dp[MI][4];
@@ -177,7 +177,7 @@ template <typename T> struct IntraArgs {
     const T *q, *k, *v;
     const float *g, *z, *dz, *dgf;
     const T *S, *SF, *E;
-    StateLayout layS, laySF, layE;
+    StateLayout lay;
     const T *tAvT;
     float *dg;
     T *tB, *tBT, *tA2T, *tDZe, *tSbe;
@@ -208,19 +208,19 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm,
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const size_t ch = (size_t)cid * H + h;
-    const T *EK = a.E + ch * a.layE.stride + a.layE.oKn;     // memory gradient at chunk end, natural
-    const T *EV = a.E + ch * a.layE.stride + a.layE.oVn;
+    const T *EK = a.E + ch * a.lay.stride + a.lay.oK;        // memory gradient at chunk end
+    const T *EV = a.E + ch * a.lay.stride + a.lay.oV;
     int chunk0, nch, stok0, sntok;
     seq_lookup(cm, ci.seq, chunk0, nch, stok0, sntok);
     const T *SendK, *SendV;                                  // memory at chunk end, natural
     if (ci.idx + 1 < nch) {
-        const T *rec = a.S + (ch + H) * a.layS.stride;       // = start of the next chunk
-        SendK = rec + a.layS.oKn;
-        SendV = rec + a.layS.oVn;
+        const T *rec = a.S + (ch + H) * a.lay.stride;        // = start of the next chunk
+        SendK = rec + a.lay.oK;
+        SendV = rec + a.lay.oV;
     } else {
-        const T *rec = a.SF + ((size_t)ci.seq * H + h) * a.laySF.stride;
-        SendK = rec + a.laySF.oKn;
-        SendV = rec + a.laySF.oVn;
+        const T *rec = a.SF + ((size_t)ci.seq * H + h) * a.lay.stride;
+        SendK = rec + a.lay.oK;
+        SendV = rec + a.lay.oV;
     }
     const T *AvT = a.tAvT + ch * C * C;
     const int rowb = 16 * w;
@@ -512,7 +512,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     // 1. recompute the chunk-start memories (and the memories after the last token)
     GSA_HIP_TRY(launch_gates(pl, w, g, st));
     {
-        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false, pl.layS_bwd, pl.laySF};
+        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     dim3 grid(pl.chunk_slots, pl.H);
@@ -523,12 +523,12 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         GSA_HIP_TRY(allow_lds(kern, lds));
         KernelTimer kt(kSlotChunkDz, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_v, pl.scale, (const T *)v,
-                           (const T *)dO, g, z, (const T *)w.S, pl.layS_bwd, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT);
+                           (const T *)dO, g, z, (const T *)w.S, pl.lay, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT);
         GSA_HIP_TRY(hipGetLastError());
     }
     // 3. reverse scan of the memory gradient
     {
-        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true, pl.layE, pl.laySF};
+        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     // 4. everything chunk-local except the wide contractions
@@ -540,7 +540,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         a.q = (const T *)q; a.k = (const T *)k; a.v = (const T *)v;
         a.g = g; a.z = z; a.dz = w.dz; a.dgf = w.dgf;
         a.S = (const T *)w.S; a.SF = (const T *)w.SF; a.E = (const T *)w.E;
-        a.layS = pl.layS_bwd; a.laySF = pl.laySF; a.layE = pl.layE;
+        a.lay = pl.lay;
         a.tAvT = (const T *)w.tAvT;
         a.dg = dg;
         a.tB = (T *)w.tA; a.tBT = (T *)w.tBT; a.tA2T = (T *)w.tA2T; a.tDZe = (T *)w.tP; a.tSbe = (T *)w.tSbe;
@@ -550,9 +550,9 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     }
     // 5. dq, dk, dv
     const ApplyIo io[3] = {
-        {w.tA, w.tP, k, w.S, pl.layS_bwd.oKt, pl.layS_bwd.stride, dq, pl.d_k},
-        {w.tBT, w.tSbe, q, w.E, pl.layE.oKt, pl.layE.stride, dk, pl.d_k},
-        {w.tA2T, w.tSbe, dO, w.E, pl.layE.oVt, pl.layE.stride, dv, pl.d_v},
+        {w.tA, w.tP, k, w.S, pl.lay.oK, pl.lay.stride, dq, pl.d_k},
+        {w.tBT, w.tSbe, q, w.E, pl.lay.oK, pl.lay.stride, dk, pl.d_k},
+        {w.tA2T, w.tSbe, dO, w.E, pl.lay.oV, pl.lay.stride, dv, pl.d_v},
     };
     return launch_apply(pl, w, io, 3, kSlotApplyBwd, st);
 }

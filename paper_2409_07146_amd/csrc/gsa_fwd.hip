@@ -122,7 +122,7 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_fwd_kernel(ChunkMap cm, i
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const size_t ch = (size_t)cid * H + h;
-    const T *Kn = S + ch * lay.stride + lay.oKn;      // key memory at chunk start [M][d_k]
+    const T *Kn = S + ch * lay.stride + lay.oK;      // key memory at chunk start [M][d_k]
     const int rowb = 16 * w;                          // this wave's row block
 
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
@@ -243,7 +243,7 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
     const ChunkMap cm = make_chunk_map(pl, w);
     GSA_HIP_TRY(launch_gates(pl, w, g, st));
     {
-        const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false, pl.layS_fwd, pl.laySF};
+        const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     {
@@ -253,10 +253,10 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
         dim3 grid(pl.chunk_slots, pl.H);
         KernelTimer kt(kSlotChunkFwd, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.scale, (const T *)q,
-                           (const T *)k, g, (const T *)w.S, pl.layS_fwd, z_saved, (T *)w.tA, (T *)w.tP);
+                           (const T *)k, g, (const T *)w.S, pl.lay, z_saved, (T *)w.tA, (T *)w.tP);
         GSA_HIP_TRY(hipGetLastError());
     }
-    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.layS_fwd.oVt, pl.layS_fwd.stride, o, pl.d_v};
+    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v};
     return launch_apply(pl, w, &io, 1, kSlotApplyFwd, st);
 }
 

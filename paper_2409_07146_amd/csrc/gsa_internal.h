@@ -20,8 +20,8 @@ struct Plan {
     // workspace offsets in bytes (256-byte aligned); 0-sized parts share an offset
     size_t off_table, off_seqtab, off_Wf, off_dec, off_S, off_tA, off_tP, total_fwd;
     size_t off_SF, off_Wr, off_E, off_dz, off_dgf, off_tB, off_tBT, off_tA2T, off_tAvT, off_tSbe, total_bwd;
-    // layouts of the memory snapshots (elements); see gsa_layout.h
-    StateLayout layS_fwd, layS_bwd, layE, laySF;
+    // layout of every memory snapshot record (elements); see gsa_layout.h
+    StateLayout lay;
 };
 
 // Workspace views handed to the launchers.
@@ -31,12 +31,12 @@ struct Work {
     // per (chunk, head) records, element type = I/O dtype unless noted; KM = max(m, 32)
     void *Wf;         // [m][C]      forward scan weights s*exp(G_C-G)
     float *dec;       // [m]         chunk decay exp(G_C)                                  (fp32)
-    void *S;          // memory at the start of the chunk, blocks per Plan::layS_fwd / layS_bwd
+    void *S;          // memory at the start of the chunk (Plan::lay)
     void *tA;         // [C][C]      forward: pair weights A2;  backward: scale*Bm
     void *tP;         // [C][KM]     forward: p*exp(G);         backward: scale*dz*exp(G)
-    void *SF;         // per (sequence, head): memory after the last token (Plan::laySF)
+    void *SF;         // per (sequence, head): memory after the last token (Plan::lay)
     void *Wr;         // [2][m][C]   reverse scan weights
-    void *E;          // gradient of the memory at the end of the chunk (Plan::layE)
+    void *E;          // gradient of the memory at the end of the chunk (Plan::lay)
     void *tBT;        // [C][C]      scale*Bm^T
     void *tA2T;       // [C][C]      A2^T
     void *tAvT;       // [C][C]      (dO_t . v_r)^T, causally masked
@@ -77,14 +77,12 @@ struct ScanIo {
     float *outK, *outV;
     void *outJ;
     bool reverse;
-    StateLayout lay;    // layout of the per-chunk snapshots
-    StateLayout layJ;   // layout of outJ
 };
 hipError_t launch_scan(const Plan &pl, const Work &w, const ScanIo &io, hipStream_t st);
 
 // The wide contractions out = A_tok X + A_slot St for up to three outputs in one
-// launch (see gsa_apply.hip).  xslot_rec + xslot_off points at a transposed memory block [d][m] of
-// the first (chunk, head) record; records are xslot_stride elements apart.
+// launch (see gsa_apply.hip).  xslot_rec + xslot_off points at a memory block [m][d] of the first
+// (chunk, head) record; records are xslot_stride elements apart.
 struct ApplyIo {
     const void *A_tok, *A_slot, *xtok, *xslot_rec;
     long long xslot_off, xslot_stride;

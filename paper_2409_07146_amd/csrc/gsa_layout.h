@@ -3,14 +3,14 @@
 
 namespace gsa {
 
-// Where the pieces of a per-chunk memory snapshot live.  A snapshot of the joint memory
-// [Kt | Vt] is stored as up to four blocks per (chunk, head): the key and value parts in
-// natural layout ([m][d], what a contraction over d reads) and/or transposed ([d][m], what
-// a contraction over the slots reads).  Offsets are in elements from the start of the
-// (chunk, head) record; -1 = block not stored.
+// A snapshot of the joint memory [Kt | Vt] (or of its gradient) is one record per (chunk, head)
+// or per (sequence, head): the key part [m][d_k] followed by the value part [m][d_v], rows =
+// slots, head dimension fastest.  That is the orientation a contraction over the head dimension
+// reads directly; the apply kernel, which contracts over the slots, transposes the column slice
+// it needs on its way into LDS.  Offsets are in elements from the start of the record.
 struct StateLayout {
-    long long stride;            // elements per (chunk, head)
-    long long oKn, oVn, oKt, oVt;
+    long long stride;   // elements per record
+    long long oK, oV;   // key part, value part
 };
 
 

@@ -60,11 +60,10 @@ template <typename T> struct ScanArgs {
     const float *dec;      // [chunk][H][M]
     const T *xk, *xv;      // token tensors feeding the key / value columns
     const float *initK, *initV;   // [n_seqs][H][M][d] or NULL
-    T *snap;               // per (chunk, head) record laid out by `lay`
-    StateLayout lay;
+    T *snap;               // one record per (chunk, head)
+    StateLayout lay;       // layout of every record
     float *outK, *outV;    // [n_seqs][H][M][d] or NULL: acc after the last chunk
-    T *outJ;               // per (sequence, head) record laid out by `layJ`, or NULL: the same, element type T
-    StateLayout layJ;
+    T *outJ;               // one record per (sequence, head), or NULL: the same, element type T
 };
 
 template <typename T, int M, int NS> struct ScanLds {
@@ -72,12 +71,10 @@ template <typename T, int M, int NS> struct ScanLds {
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int ldw = C + PAD;      // We [M][ldw], XT [NS][ldw]
     static constexpr int lds = NS + PAD;     // snapshot tile [M][lds]
-    static constexpr int ldt = M + PAD;      // transposed snapshot tile [NS][ldt]
     static constexpr size_t oW = 0;
     static constexpr size_t oX = oW + sizeof(T) * M * ldw;
     static constexpr size_t oSn = oX + sizeof(T) * NS * ldw;
-    static constexpr size_t oSt = oSn + sizeof(T) * M * lds;
-    static constexpr size_t bytes = oSt + sizeof(T) * NS * ldt;
+    static constexpr size_t bytes = oSn + sizeof(T) * M * lds;
 };
 
 template <typename T, int M, int NS, bool REVERSE>
@@ -93,7 +90,6 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
     T *We = reinterpret_cast<T *>(smem + L::oW);
     T *XT = reinterpret_cast<T *>(smem + L::oX);
     T *Sn = reinterpret_cast<T *>(smem + L::oSn);
-    T *St = reinterpret_cast<T *>(smem + L::oSt);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
@@ -156,55 +152,29 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) st.dec[mi] = *reinterpret_cast<const f32x4 *>(a.dec + ch * M + mi * 16 + g4);
     };
-    // accumulator -> LDS in the layouts the record asks for (natural [m][cols], transposed [cols][m])
-    auto snapshot_to_lds = [&](const StateLayout &lay) {
-        const bool nat = (isK ? lay.oKn : lay.oVn) >= 0, tr = (isK ? lay.oKt : lay.oVt) >= 0;
-        if (tr) {   // a lane holds four consecutive slots of one column: one 4-element store each
+    // accumulator -> LDS tile [m][cols] -> whole rows of the record's key or value part
+    auto snapshot_to_lds = [&]() {
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    store4(St + (wcol + ni * 16 + r) * L::ldt + mi * 16 + g4, acc[mi][ni][0], acc[mi][ni][1],
-                           acc[mi][ni][2], acc[mi][ni][3]);
-        }
-        if (nat) {
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
-        }
+                for (int j = 0; j < 4; ++j)
+                    Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
     };
-    auto snapshot_to_global = [&](T *rec, const StateLayout &lay) {   // rec: start of the (chunk, head) record
+    auto snapshot_to_global = [&](T *rec) {   // rec: start of the record
+        T *dst = rec + (isK ? a.lay.oK : a.lay.oV);
         // LDS reads first (clamped, unconditional), then the stores: no read sits under a branch
-        const long long oN = isK ? lay.oKn : lay.oVn, oT = isK ? lay.oKt : lay.oVt;
-        if (oN >= 0) {
-            Raw8<T> x[SV];
+        Raw8<T> x[SV];
 #pragma unroll
-            for (int u = 0; u < SV; ++u) {
-                const int idx = min(tid + NT * u, SVEC - 1), i = idx / (NS / 8), cg = idx - i * (NS / 8);
-                x[u].load(Sn + i * L::lds + cg * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < SV; ++u) {
-                const int idx = tid + NT * u, i = idx / (NS / 8), cg = idx - i * (NS / 8);
-                if (SVEC % NT == 0 || idx < SVEC) x[u].store(rec + oN + (size_t)i * dsrc + c0 + cg * 8);
-            }
+        for (int u = 0; u < SV; ++u) {
+            const int idx = min(tid + NT * u, SVEC - 1), i = idx / (NS / 8), cg = idx - i * (NS / 8);
+            x[u].load(Sn + i * L::lds + cg * 8);
         }
-        if (oT >= 0) {
-            Raw8<T> x[SV];
 #pragma unroll
-            for (int u = 0; u < SV; ++u) {
-                const int idx = min(tid + NT * u, SVEC - 1), c = idx / (M / 8), ig = idx - c * (M / 8);
-                x[u].load(St + c * L::ldt + ig * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < SV; ++u) {
-                const int idx = tid + NT * u, c = idx / (M / 8), ig = idx - c * (M / 8);
-                if (SVEC % NT == 0 || idx < SVEC) x[u].store(rec + oT + (size_t)(c0 + c) * M + ig * 8);
-            }
+        for (int u = 0; u < SV; ++u) {
+            const int idx = tid + NT * u, i = idx / (NS / 8), cg = idx - i * (NS / 8);
+            if (SVEC % NT == 0 || idx < SVEC) x[u].store(dst + (size_t)i * dsrc + c0 + cg * 8);
         }
     };
 
@@ -221,13 +191,13 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
             }
         }
         st.xt.store_transposed(XT, L::ldw, NS, tid);
-        snapshot_to_lds(a.lay);
+        snapshot_to_lds();
         f32x4 dcur[MI];
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) dcur[mi] = st.dec[mi];
         __syncthreads();
         if (it + 2 < nch) fetch(st, REVERSE ? n - 2 : n + 2);
-        snapshot_to_global(a.snap + ((size_t)(chunk0 + n) * H + h) * a.lay.stride, a.lay);
+        snapshot_to_global(a.snap + ((size_t)(chunk0 + n) * H + h) * a.lay.stride);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -269,9 +239,9 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
                 }
     }
     if (a.outJ) {
-        snapshot_to_lds(a.layJ);
+        snapshot_to_lds();
         __syncthreads();
-        snapshot_to_global(a.outJ + ((size_t)s * H + h) * a.layJ.stride, a.layJ);
+        snapshot_to_global(a.outJ + ((size_t)s * H + h) * a.lay.stride);
     }
 }
 
@@ -326,11 +296,10 @@ static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io
     a.initK = io.initK;
     a.initV = io.initV;
     a.snap = static_cast<T *>(io.reverse ? w.E : w.S);
-    a.lay = io.lay;
+    a.lay = pl.lay;
     a.outK = io.outK;
     a.outV = io.outV;
     a.outJ = static_cast<T *>(io.outJ);
-    a.layJ = io.layJ;
     // 64-column slices: several workgroups per CU, so that their dependent chains overlap
     if (io.reverse) return run_scan<T, M, 64, true>(pl, cm, a, st);
     return run_scan<T, M, 64, false>(pl, cm, a, st);
