@@ -167,13 +167,16 @@ def main():
         f64 = lambda t: None if t is None else t.double().numpy()
         cun = None if x["cu_seqlens"] is None else x["cu_seqlens"].numpy()
         qn, kn, vn, gn, dn = (f64(x[n]) for n in ("q", "k", "v", "g", "dO"))
+        reps, cdt = 0, 0.0
         t0 = time.perf_counter()
-        gsa_oracle.fwd(qn, kn, vn, gn, cu_seqlens=cun)
-        gsa_oracle.bwd(qn, kn, vn, gn, dn, cu_seqlens=cun)
-        cdt = time.perf_counter() - t0
-        cpu = {"value": round(tokens / cdt, 1), "unit": "tokens/s", "cores": gsa_oracle.num_threads(),
-               "kind": "oracle", "sample": "the whole %s batch (%d tokens), fp64 forward + backward, one repetition, "
-               "%.1f s" % (cfg.name, tokens, cdt)}
+        while cdt < 10.0 and reps < 64:      # a bounded sample: whole batches until about 10 s of CPU work
+            gsa_oracle.fwd(qn, kn, vn, gn, cu_seqlens=cun)
+            gsa_oracle.bwd(qn, kn, vn, gn, dn, cu_seqlens=cun)
+            reps += 1
+            cdt = time.perf_counter() - t0
+        cpu = {"value": round(reps * tokens / cdt, 1), "unit": "tokens/s", "cores": gsa_oracle.num_threads(),
+               "kind": "oracle", "sample": "the whole %s batch (%d tokens), fp64 forward + backward, %d repetitions, "
+               "%.1f s" % (cfg.name, tokens, reps, cdt)}
 
     out = {
         "metric": "gsa_layer_fwd_bwd_tokens_per_s", "value": round(tok_s, 1), "unit": "tokens/s",
