@@ -73,7 +73,10 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
     const int wcol = 16 * NIo * w;
     const bool active = wcol < ncols;
 
-    TokTile<T, C, L::NS, NT> tt;
+    // every global load of the workgroup is issued here, in the order the data is needed
+    TokTile<T, M, L::NS, NT> ts;   // the slot memory's column slice, rows = slots
+    ts.load(a.xslot + ch * a.xs_stride + cs, (size_t)a.d, M, ncols, tid);
+    TokTile<T, C, L::NS, NT> tt;   // the token tensor's column slice
     tt.load(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);
     // the two small matrices go through LDS: every wave needs all of both
     T *Ats = reinterpret_cast<T *>(smem + L::oAt), *Ass = reinterpret_cast<T *>(smem + L::oAs);
@@ -96,9 +99,6 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
             if (idx < VS) xs[u].store(Ass + t * L::lds + c8);
         }
     }
-    // the slot memory's column slice, rows = slots
-    TokTile<T, M, L::NS, NT> ts;
-    ts.load(a.xslot + ch * a.xs_stride + cs, (size_t)a.d, M, ncols, tid);
     ts.store_transposed(XT, L::ldm, ncols, tid);
     __syncthreads();
     f32x4 acc[CI][NIo];
