@@ -71,10 +71,14 @@ template <typename T, int M, int NS> struct ScanLds {
     static constexpr int PAD = Atom<T>::kPad;
     static constexpr int ldw = C + PAD;      // We [M][ldw], XT [NS][ldw]
     static constexpr int lds = NS + PAD;     // snapshot tile [M][lds]
+    // one set per parity of the chunk's position in the walk: a set is written while the other is read
+    static constexpr size_t szW = sizeof(T) * M * ldw, szX = sizeof(T) * NS * ldw, szS = sizeof(T) * M * lds;
     static constexpr size_t oW = 0;
-    static constexpr size_t oX = oW + sizeof(T) * M * ldw;
-    static constexpr size_t oSn = oX + sizeof(T) * NS * ldw;
-    static constexpr size_t bytes = oSn + sizeof(T) * M * lds;
+    static constexpr size_t oX = oW + szW;
+    static constexpr size_t oSn = oX + szX;
+    static constexpr size_t oDec = oSn + szS;             // chunk decays, fp32: [M] used, one word per thread written
+    static constexpr size_t set = oDec + sizeof(float) * Geo<T>::NT;
+    static constexpr size_t bytes = 2 * set;
 };
 
 template <typename T, int M, int NS, bool REVERSE>
@@ -87,9 +91,10 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
     constexpr int WVEC = M * C / 8, SVEC = M * NS / 8;
     constexpr int WV = (WVEC + NT - 1) / NT, SV = (SVEC + NT - 1) / NT;
     extern __shared__ __align__(16) unsigned char smem[];
-    T *We = reinterpret_cast<T *>(smem + L::oW);
-    T *XT = reinterpret_cast<T *>(smem + L::oX);
-    T *Sn = reinterpret_cast<T *>(smem + L::oSn);
+    auto We = [&](int b) { return reinterpret_cast<T *>(smem + b * L::set + L::oW); };
+    auto XT = [&](int b) { return reinterpret_cast<T *>(smem + b * L::set + L::oX); };
+    auto Sn = [&](int b) { return reinterpret_cast<T *>(smem + b * L::set + L::oSn); };
+    auto Dec = [&](int b) { return reinterpret_cast<float *>(smem + b * L::set + L::oDec); };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
@@ -136,10 +141,11 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
     struct Stage {
         Raw8<T> wreg[WV];
         TokTile<T, C, NS, NT> xt;   // transposed (and swizzled) when it enters LDS
-        f32x4 dec[MI];
+        float dec;                  // decay of slot tid (threads < M)
     };
     auto fetch = [&](Stage &st, int n) {
         const size_t ch = (size_t)(chunk0 + n) * H + h;
+        st.dec = a.dec[ch * M + (tid < M ? tid : 0)];
         const T *Wg = a.W + ch * a.w_parts * M * C + wpart;
 #pragma unroll
         for (int u = 0; u < WV; ++u) {
@@ -149,27 +155,27 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
         const int len = min(C, ntok - n * C);
         const T *Xg = src + ((size_t)(tok0 + n * C) * H + h) * dsrc + c0;
         st.xt.load(Xg, (size_t)H * dsrc, len, NS, tid);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) st.dec[mi] = *reinterpret_cast<const f32x4 *>(a.dec + ch * M + mi * 16 + g4);
     };
     // accumulator -> LDS tile [m][cols] -> whole rows of the record's key or value part
-    auto snapshot_to_lds = [&]() {
+    auto snapshot_to_lds = [&](int b) {
+        T *dstl = Sn(b);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    Sn[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
+                    dstl[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
     };
-    auto snapshot_to_global = [&](T *rec) {   // rec: start of the record
+    auto snapshot_to_global = [&](T *rec, int b) {   // rec: start of the record
         T *dst = rec + (isK ? a.lay.oK : a.lay.oV);
+        const T *srcl = Sn(b);
         // LDS reads first (clamped, unconditional), then the stores: no read sits under a branch
         Raw8<T> x[SV];
 #pragma unroll
         for (int u = 0; u < SV; ++u) {
             const int idx = min(tid + NT * u, SVEC - 1), i = idx / (NS / 8), cg = idx - i * (NS / 8);
-            x[u].load(Sn + i * L::lds + cg * 8);
+            x[u].load(srcl + i * L::lds + cg * 8);
         }
 #pragma unroll
         for (int u = 0; u < SV; ++u) {
@@ -177,54 +183,92 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
             if (SVEC % NT == 0 || idx < SVEC) x[u].store(dst + (size_t)i * dsrc + c0 + cg * 8);
         }
     };
-
-    // One chunk: staged registers -> LDS (W as is, X transposed), accumulator snapshot -> LDS and on to
-    // global memory, refill the stage with the chunk two steps on, then S <- Diag(dec) S + W X.
-    auto step = [&](Stage &st, int it) {
-        const int n = REVERSE ? nch - 1 - it : it;
+    // staged registers -> LDS set b (W as is, X transposed)
+    auto stage_to_lds = [&](const Stage &st, int b) {
+        T *w = We(b);
 #pragma unroll
         for (int u = 0; u < WV; ++u) {
             const int idx = tid + NT * u;
             if (idx < WVEC) {
                 const int i = idx / (C / 8), tg = idx - i * (C / 8);
-                st.wreg[u].store(We + i * L::ldw + tg * 8);
+                st.wreg[u].store(w + i * L::ldw + tg * 8);
             }
         }
-        st.xt.store_transposed(XT, L::ldw, NS, tid);
-        snapshot_to_lds();
-        f32x4 dcur[MI];
+        st.xt.store_transposed(XT(b), L::ldw, NS, tid);
+        Dec(b)[tid] = st.dec;   // every thread stores (threads >= M a copy of slot 0's): no branch around a loaded value
+    };
+    // position in the walk -> chunk; positions past the end repeat the last chunk, so that refills can be
+    // issued unconditionally (a refill under a branch makes the number of loads in flight unknown to the
+    // compiler, which then waits for all of them wherever it needs one)
+    auto chunk_of = [&](int it) { it = min(it, nch - 1); return REVERSE ? nch - 1 - it : it; };
+
+    // The walk, software-pipelined with ONE barrier per chunk.  At the top of step `it` LDS set it%2
+    // holds the operands of chunk `it` (written during the previous step) and the snapshot tile of
+    // the other set holds the memory the previous chunk started from.  The step
+    //   - sends that previous snapshot to global memory,
+    //   - snapshots the accumulator (the memory chunk `it` starts from) into its own set,
+    //   - applies S <- Diag(dec) S + W X with fragments read from its own set,
+    //   - writes the operands of chunk it+1 (register stage `nx`) into the other set and refills
+    //     that stage with chunk it+3,
+    // so only the accumulator update lies on the chain from one chunk to the next; everything
+    // else rides beside it.  A set is rewritten two steps after it was read, with a barrier between.
+    auto step = [&](Stage &nx, int it) {
+        const int b = it & 1;
+        if (it > 0) snapshot_to_global(a.snap + ((size_t)(chunk0 + chunk_of(it - 1)) * H + h) * a.lay.stride, b ^ 1);
+        snapshot_to_lds(b);
+        typename Atom<T>::Frag af[C / 32][MI], bf[C / 32][NI];
+        const T *w = We(b), *x = XT(b);
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) dcur[mi] = st.dec[mi];
-        __syncthreads();
-        if (it + 2 < nch) fetch(st, REVERSE ? n - 2 : n + 2);
-        snapshot_to_global(a.snap + ((size_t)(chunk0 + n) * H + h) * a.lay.stride);
+        for (int ks = 0; ks < C / 32; ++ks) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+            for (int mi = 0; mi < MI; ++mi) af[ks][mi] = Atom<T>::load(w + (mi * 16 + r) * L::ldw + ks * 32 + g8);
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) acc[mi][ni] *= dcur[mi];
+            for (int ni = 0; ni < NI; ++ni)
+                bf[ks][ni] = Atom<T>::load(x + xt_off<C>(wcol + ni * 16 + r, ks * 32 + g8, L::ldw));
+        }
 #pragma unroll
-        for (int k0 = 0; k0 < C; k0 += 32) {
-            typename Atom<T>::Frag af[MI], bf[NI];
+        for (int mi = 0; mi < MI; ++mi) {
+            const f32x4 dcur = *reinterpret_cast<const f32x4 *>(Dec(b) + mi * 16 + g4);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) af[mi] = Atom<T>::load(We + (mi * 16 + r) * L::ldw + k0 + g8);
+            for (int ni = 0; ni < NI; ++ni) acc[mi][ni] *= dcur;
+        }
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) bf[ni] = Atom<T>::load(XT + xt_off<C>(wcol + ni * 16 + r, k0 + g8, L::ldw));
+        for (int ks = 0; ks < C / 32; ++ks)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) Atom<T>::mma(acc[mi][ni], af[mi], bf[ni]);
-        }
-        __syncthreads();
+                for (int ni = 0; ni < NI; ++ni) Atom<T>::mma(acc[mi][ni], af[ks][mi], bf[ks][ni]);
+        stage_to_lds(nx, b ^ 1);
     };
+    // (the scheduling fences keep the compiler from hoisting a stage's refill above the LDS stores
+    // that read its registers: it would then load into other registers and copy them back at the
+    // end of the trip, which means waiting for loads that were only just issued)
     Stage sa, sb;
-    if (nch > 0) fetch(sa, REVERSE ? nch - 1 : 0);
-    if (nch > 1) fetch(sb, REVERSE ? nch - 2 : 1);
+    if (nch > 0) {
+        fetch(sa, chunk_of(0));
+        fetch(sb, chunk_of(1));
+        stage_to_lds(sa, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(sa, chunk_of(2));
+        __syncthreads();
+    }
     int it = 0;
     for (; it + 1 < nch; it += 2) {   // two steps per trip: each stage keeps its own registers
-        step(sa, it);
-        step(sb, it + 1);
+        step(sb, it);                 // operands in set 0; sb holds chunk it+1
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(sb, chunk_of(it + 3));
+        __syncthreads();
+        step(sa, it + 1);             // operands in set 1; sa holds chunk it+2
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(sa, chunk_of(it + 4));
+        __syncthreads();
     }
-    if (it < nch) step(sa, it);
+    if (it < nch) {
+        step(sb, it);
+        __syncthreads();
+        ++it;
+    }
+    if (nch > 0) snapshot_to_global(a.snap + ((size_t)(chunk0 + chunk_of(nch - 1)) * H + h) * a.lay.stride, (nch - 1) & 1);
     // accumulator after the last chunk
     float *ST = isK ? a.outK : a.outV;
     if (ST) {
@@ -239,9 +283,10 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H,
                 }
     }
     if (a.outJ) {
-        snapshot_to_lds();
+        __syncthreads();   // the last snapshot tile may still be on its way out
+        snapshot_to_lds(0);
         __syncthreads();
-        snapshot_to_global(a.outJ + ((size_t)s * H + h) * a.lay.stride);
+        snapshot_to_global(a.outJ + ((size_t)s * H + h) * a.lay.stride, 0);
     }
 }
 
