@@ -267,6 +267,7 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm,
             for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EK + ek[ni] + k0);
 #pragma unroll
             for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendK + ek[ni] + k0);
+            __builtin_amdgcn_sched_barrier(0);   // all loads of the step before its multiplies (see gated_scores)
 #pragma unroll
             for (int rb = 0; rb < NW; ++rb) {
 #pragma unroll
@@ -286,6 +287,7 @@ __global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm,
             for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EV + ev[ni] + k0);
 #pragma unroll
             for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendV + ev[ni] + k0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int rb = 0; rb < NW; ++rb)
 #pragma unroll

@@ -126,6 +126,10 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
             for (int ni = 0; ni < CI; ++ni) fy[ni] = Atom<T>::load(Y + xo[ni] + k0);
 #pragma unroll
             for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(St + so[ni] + k0);
+            // keep every load of the step ahead of its multiplies: left alone, the scheduler sinks loads
+            // between the multiplies to save registers and the wave ends up with one or two in flight.
+            // (A second register set for the next step's loads measured slower.)
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int rb = 0; rb < NW; ++rb) {
 #pragma unroll
