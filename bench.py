@@ -59,7 +59,7 @@ def main():
     from paper_2409_07146_amd import synth
 
     dev = torch.device("cuda:0")
-    cfg = synth.CONFIGS[args.workload]
+    cfg = synth.CONFIGS[args.workload] if args.workload in synth.CONFIGS else synth.VARIANTS[args.workload]
     x = synth.make_inputs(cfg)
     put = lambda t: None if t is None else t.to(dev)
     q, k, v, g, dO, cu = (put(x[n]) for n in ("q", "k", "v", "g", "dO", "cu_seqlens"))

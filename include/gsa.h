@@ -25,7 +25,7 @@
  *     its memories in place, that is its contract).
  *   - Errors are return codes; arguments are validated on the host before any
  *     device work is enqueued, and a failed call enqueues nothing.
- *   - Supported shapes: m in {16, 32, 64} (the decode step also takes 128); d_k and d_v
+ *   - Supported shapes: m in {16, 32, 64, 128}; d_k and d_v
  *     multiples of 64, at most 1024; H, B >= 1; T >= 0 (T = 0 does nothing).  Anything
  *     else returns GSA_ERR_UNSUPPORTED.
  */

@@ -15,8 +15,8 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 bool valid_m(int m, bool sequence_kernels)
 {
-    if (m == 16 || m == 32 || m == 64) return true;
-    return !sequence_kernels && m == 128;
+    (void)sequence_kernels;
+    return m == 16 || m == 32 || m == 64 || m == 128;
 }
 
 gsa_status make_plan(const gsa_problem *p, Plan *pl)

@@ -185,6 +185,7 @@ hipError_t launch_apply(const Plan &pl, const Work &w, const ApplyIo *io, int n,
     switch (pl.m) {                                                         \
     case 16: return launch_apply_tm<T, 16>(pl, w, io, n, slot, st);         \
     case 32: return launch_apply_tm<T, 32>(pl, w, io, n, slot, st);         \
+    case 128: return launch_apply_tm<T, 128>(pl, w, io, n, slot, st);         \
     default: return launch_apply_tm<T, 64>(pl, w, io, n, slot, st);         \
     }
     if (pl.dtype == 0) { GSA_APPLY(float) }

@@ -49,7 +49,7 @@ template <typename T, int M> struct DzLds {
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
+__global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
                                                               const T *__restrict__ v, const T *__restrict__ dO,
                                                               const float *__restrict__ g, const float *__restrict__ z,
                                                               const T *__restrict__ S, StateLayout lay,
@@ -184,7 +184,7 @@ template <typename T> struct IntraArgs {
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
+__global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
                                                                  IntraArgs<T> a)
 {
     using L = IntraLds<T, M>;
@@ -568,6 +568,7 @@ static hipError_t launch_bwd_t(const Plan &pl, const Work &w, const void *q, con
     switch (pl.m) {
     case 16: return launch_bwd_tm<T, 16>(pl, w, q, k, v, g, K0, V0, z, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0, st);
     case 32: return launch_bwd_tm<T, 32>(pl, w, q, k, v, g, K0, V0, z, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0, st);
+    case 128: return launch_bwd_tm<T, 128>(pl, w, q, k, v, g, K0, V0, z, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0, st);
     default: return launch_bwd_tm<T, 64>(pl, w, q, k, v, g, K0, V0, z, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0, st);
     }
 }

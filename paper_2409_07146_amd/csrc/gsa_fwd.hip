@@ -97,7 +97,7 @@ template <typename T, int M> struct ChunkFwdLds {
 };
 
 template <typename T, int M>
-__global__ __launch_bounds__(Geo<T>::NT, 2) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
+__global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const float *__restrict__ g,
                                                                const T *__restrict__ S, StateLayout lay,
@@ -268,6 +268,7 @@ static hipError_t launch_fwd_t(const Plan &pl, const Work &w, const void *q, con
     switch (pl.m) {
     case 16: return launch_fwd_tm<T, 16>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     case 32: return launch_fwd_tm<T, 32>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
+    case 128: return launch_fwd_tm<T, 128>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     default: return launch_fwd_tm<T, 64>(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT, st);
     }
 }

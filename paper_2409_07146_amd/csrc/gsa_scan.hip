@@ -82,7 +82,7 @@ template <typename T, int M, int NS> struct ScanLds {
 };
 
 template <typename T, int M, int NS, bool REVERSE>
-__global__ __launch_bounds__(Geo<T>::NT, 2) void scan_kernel(ChunkMap cm, int H, int d_k, int d_v, int n_seqs,
+__global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(ChunkMap cm, int H, int d_k, int d_v, int n_seqs,
                                                           ScanArgs<T> a)
 {
     using L = ScanLds<T, M, NS>;
@@ -309,6 +309,7 @@ hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, hipStream
     switch (pl.m) {                                                    \
     case 16: return launch_gates_tm<T, 16>(pl, w, g, st);              \
     case 32: return launch_gates_tm<T, 32>(pl, w, g, st);              \
+    case 128: return launch_gates_tm<T, 128>(pl, w, g, st);              \
     default: return launch_gates_tm<T, 64>(pl, w, g, st);              \
     }
     if (pl.dtype == 0) { GSA_GATES(float) }
@@ -356,6 +357,7 @@ hipError_t launch_scan(const Plan &pl, const Work &w, const ScanIo &io, hipStrea
     switch (pl.m) {                                                   \
     case 16: return launch_scan_tm<T, 16>(pl, w, io, st);             \
     case 32: return launch_scan_tm<T, 32>(pl, w, io, st);             \
+    case 128: return launch_scan_tm<T, 128>(pl, w, io, st);             \
     default: return launch_scan_tm<T, 64>(pl, w, io, st);             \
     }
     if (pl.dtype == 0) { GSA_SCAN(float) }

@@ -57,6 +57,14 @@ CONFIGS = {
                             cu_seqlens=(0, 8192, 12288, 14336, 16384), seed=4),
 }
 
+# Shape variants beyond the five workloads (Table 5 of the paper varies the number of slots;
+# Appendix D gives the 2.7B model 5 heads of 512).
+VARIANTS = {
+    "layer_1p3b_m32": GsaConfig("layer_1p3b_m32", B=8, T=2048, H=4, d_k=512, d_v=512, m=32, seed=12),
+    "layer_1p3b_m128": GsaConfig("layer_1p3b_m128", B=8, T=2048, H=4, d_k=512, d_v=512, m=128, seed=13),
+    "layer_2p7b_h5": GsaConfig("layer_2p7b_h5", B=8, T=2048, H=5, d_k=512, d_v=512, m=64, seed=14),
+}
+
 # Decode workload: 512 steps at batch 64 from random memories ~ N(0, 0.1^2).
 DECODE = dict(B=64, H=4, d_k=512, d_v=512, m=64, steps=512, state_std=0.1, seed=5)
 

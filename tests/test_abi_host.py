@@ -59,7 +59,7 @@ def test_workspace_plan(lib):
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), 2), (dict(H=0), 2), (dict(T=-1), 2), (dict(dtype=7), 2), (dict(scale=float("nan")), 2),
     (dict(B=2, cu_seqlens=0x1000, n_seqs=2), 2), (dict(B=1, cu_seqlens=0x1000, n_seqs=0), 2),
-    (dict(d_k=48), 3), (dict(d_v=2048), 3), (dict(m=24), 3), (dict(m=128), 3),
+    (dict(d_k=48), 3), (dict(d_v=2048), 3), (dict(m=24), 3), (dict(m=256), 3),
 ])
 def test_bad_problem_is_rejected(lib, kw, code):
     n = ctypes.c_size_t(0)

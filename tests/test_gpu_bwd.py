@@ -70,6 +70,7 @@ def compare_bwd(oracle, cfg, x, got, scale=1.0, heads=None, seqs=None, report=No
     (3, 17, 2, 128, 128, 64, 0.0, False),    # shorter than a chunk
     (1, 1, 1, 64, 64, 64, 0.3, True),        # single token
     (1, 700, 1, 128, 128, 64, 0.0, False),   # many chunks
+    (1, 300, 2, 128, 192, 128, 0.5, True),   # 128 slots
 ])
 def test_bwd_small_shapes(oracle, B, T, H, d_k, d_v, m, init, sg, dtype):
     from paper_2409_07146_amd.synth import GsaConfig

@@ -60,6 +60,7 @@ def test_fwd_tiny_f32(oracle):
     (1, 333, 3, 192, 64, 32, 0.5),     # several tiles and a ragged tail
     (3, 17, 2, 128, 128, 64, 0.0),     # shorter than a chunk
     (1, 1, 1, 64, 64, 64, 0.3),        # single token
+    (1, 300, 2, 128, 192, 128, 0.5),   # 128 slots
 ])
 def test_fwd_small_shapes(oracle, B, T, H, d_k, d_v, m, init, dtype):
     from paper_2409_07146_amd.synth import GsaConfig
