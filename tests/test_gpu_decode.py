@@ -64,3 +64,28 @@ def test_decode_extreme_gates(oracle):
     check("o", to_np64(o), oo, "f32")
     np.testing.assert_allclose(to_np64(o)[0], to_np64(v)[0], atol=1e-6)
     np.testing.assert_array_equal(to_np64(Kg)[1], to_np64(K)[1])   # g = 0 leaves memories untouched
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prefill_then_decode(oracle, dtype):
+    """The serving pattern of the paper's latency figure: gsa_fwd over a prompt hands its final
+    memories to a loop of gsa_decode_step calls.  The whole thing must equal the recurrence run
+    over prompt + generated tokens in one go (oracle forward over the concatenation)."""
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd.synth import GsaConfig, make_inputs
+    B, P, N, H, d_k, d_v, m = 2, 150, 24, 2, 128, 64, 32
+    cfg = GsaConfig("prefill", B=B, T=P + N, H=H, d_k=d_k, d_v=d_v, m=m, dtype=dtype, seed=21)
+    x = make_inputs(cfg)
+    dev = torch.device("cuda:0")
+    q, k, v, g = (x[n].to(dev) for n in ("q", "k", "v", "g"))
+    o_pre, _, KT, VT = gsa.gsa_fwd(q[:, :P].contiguous(), k[:, :P].contiguous(), v[:, :P].contiguous(),
+                                   g[:, :P].contiguous(), scale=0.7, final_state=True)
+    outs = [gsa.gsa_decode_step(q[:, P + t].contiguous(), k[:, P + t].contiguous(), v[:, P + t].contiguous(),
+                                g[:, P + t].contiguous(), KT, VT, scale=0.7) for t in range(N)]
+    torch.cuda.synchronize()
+    ref = oracle.fwd(*(to_np64(x[n]) for n in ("q", "k", "v", "g")), scale=0.7)
+    check("o[prompt]", to_np64(o_pre), ref["o"][:, :P], dtype)
+    got = np.stack([to_np64(t) for t in outs], axis=1)
+    check("o[generated]", got, ref["o"][:, P:], dtype)
+    check("KT", to_np64(KT), ref["KT"], dtype)
+    check("VT", to_np64(VT), ref["VT"], dtype)
