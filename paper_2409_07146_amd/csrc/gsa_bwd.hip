@@ -225,12 +225,13 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
     const T *AvT = a.tAvT + ch * C * C;
     const int rowb = 16 * w;
 
-    gate_prep<M, NT, C>(Gs, Ss, L::ldg, tot, a.g + tokh * M, (size_t)H * M, ci.len, tid);
     // ---- phase 1: contractions over the head dimension, operands straight from global memory
     //   A[t][r] = q_t . k_r (r <= t),  X[r][i] = <E[i], [k_r | v_r]>,  carry[i] = <E[i], S_end[i]>
     // Split over the waves in steps of 32 columns (see gated_scores): every wave covers all row
     // blocks over its share of the columns, the partial sums meet in LDS.
     f32x4 accA[CI], accX[MI];
+    GatePrep<M, NT, C> gp;
+    SoftmaxRows<M, C> sr;
     {
         typedef typename Atom<T>::Frag Frag;
         f32x4 acc[NW][NB];   // [row block][k blocks (causal) | slot blocks]
@@ -302,6 +303,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
             x += __shfl_xor(x, 32, 64);
             if (lane < 16) carry[w * M + ni * 16 + lane] = x;   // read after the barriers of the reduction
         }
+        // the loads of everything phase 2 needs from global memory land during the reduction
+        gp.load(a.g + tokh * M, (size_t)H * M, ci.len, tid);
+        sr.load(a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
         f32x4 own[NB];
         reduce_row_blocks<NW, NB, CI>(own, acc, reinterpret_cast<f32x4 *>(smem + L::oPf), lane, w);
 #pragma unroll
@@ -309,8 +313,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) accX[ni] = own[CI + ni];
     }
-    // p and dz tiles (they overwrite the reduction buffer, which every wave has left by now)
-    softmax_rows<M, C>(Pf, Df, L::ldg, a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
+    // gate tiles; p and dz tiles (they overwrite the reduction buffer, which every wave has left by now)
+    gp.finish(Gs, Ss, L::ldg, tot, ci.len, tid);
+    sr.finish(Pf, Df, L::ldg, ci.len, tid);
     // ---- phase 2a: transposed masked A into LDS; the slot-side operand tiles of the apply kernel
 #pragma unroll
     for (int ni = 0; ni < CI; ++ni)

@@ -319,39 +319,40 @@ __device__ __forceinline__ void store_tile(T *dst, size_t ld, const T *Os, int l
 }
 
 // Softmax over the M slots of each chunk row, from scores in global memory into an fp32
-// LDS tile Pf[C][ld]; four threads per row.  Rows >= len get zeros.  Optionally copies a
-// second [len][M] array (same global layout) into Df.  Needs NT = 4*C threads.
-template <int M, int C>
-__device__ __forceinline__ void softmax_rows(float *Pf, float *Df, int ld, const float *z, const float *dz, size_t gld,
-                                             int len, int tid)
-{
-    constexpr int Q = M / 4;
-    const int t = tid >> 2, sub = tid & 3;
-    float zv[Q];
-    float mx = -INFINITY;
-    const size_t row = (size_t)min(t, len - 1) * gld;   // clamped: the load is unconditional
+// LDS tile Pf[C][ld]; four threads per row.  Rows >= len get zeros.  Also copies a second
+// [len][M] array (same global layout) into Df.  Needs NT = 4*C threads.  load() only issues
+// the (clamped, unconditional) loads, so that it can be called ahead of other work.
+template <int M, int C> struct SoftmaxRows {
+    static constexpr int Q = M / 4;
+    float zv[Q], dv[Q];
+    __device__ __forceinline__ void load(const float *z, const float *dz, size_t gld, int len, int tid)
+    {
+        const int t = tid >> 2, sub = tid & 3;
+        const size_t row = (size_t)min(t, len - 1) * gld;
 #pragma unroll
-    for (int u = 0; u < Q; ++u) {
-        zv[u] = z[row + sub + 4 * u];
-        mx = fmaxf(mx, zv[u]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
-    float sum = 0.f;
-#pragma unroll
-    for (int u = 0; u < Q; ++u) { zv[u] = __expf(zv[u] - mx); sum += zv[u]; }
-    sum += __shfl_xor(sum, 1, 64);
-    sum += __shfl_xor(sum, 2, 64);
-    const float inv = (t < len) ? 1.f / sum : 0.f;
-#pragma unroll
-    for (int u = 0; u < Q; ++u) Pf[t * ld + sub + 4 * u] = zv[u] * inv;
-    if (Df) {
-        float dv[Q];
+        for (int u = 0; u < Q; ++u) zv[u] = z[row + sub + 4 * u];
 #pragma unroll
         for (int u = 0; u < Q; ++u) dv[u] = dz[row + sub + 4 * u];
+    }
+    __device__ __forceinline__ void finish(float *Pf, float *Df, int ld, int len, int tid)
+    {
+        const int t = tid >> 2, sub = tid & 3;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < Q; ++u) mx = fmaxf(mx, zv[u]);
+        mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+        float sum = 0.f;
+#pragma unroll
+        for (int u = 0; u < Q; ++u) { zv[u] = __expf(zv[u] - mx); sum += zv[u]; }
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        const float inv = (t < len) ? 1.f / sum : 0.f;
+#pragma unroll
+        for (int u = 0; u < Q; ++u) Pf[t * ld + sub + 4 * u] = zv[u] * inv;
 #pragma unroll
         for (int u = 0; u < Q; ++u) Df[t * ld + sub + 4 * u] = (t < len) ? dv[u] : 0.f;
     }
-}
+};
 
 }  // namespace gsa
