@@ -59,16 +59,31 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
     T *XT = reinterpret_cast<T *>(smem);
     T *Os = reinterpret_cast<T *>(smem);
 
+    // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs, each with its own
+    // L2.  The column slices of one (chunk, head, output) share the two small matrices, so they are
+    // given ids that land on the same XCD (each XCD takes a contiguous range of logical ids); without
+    // this every slice fetches its own copy through a different L2.
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    {
+        const unsigned nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+        if ((total & 7u) == 0) {
+            unsigned lin = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+            lin = (lin & 7u) * (total >> 3) + (lin >> 3);
+            bx = lin % nx;
+            by = (lin / nx) % ny;
+            bz = lin / (nx * ny);
+        }
+    }
     ChunkInfo ci;
-    if (!chunk_lookup(cm, blockIdx.y, ci)) return;
-    const int h = blockIdx.z % H, which = blockIdx.z / H;
+    if (!chunk_lookup(cm, by, ci)) return;
+    const int h = bz % H, which = bz / H;
     const ApplyOne<T> &a = args.one[which];
-    const int cs = blockIdx.x * L::NS;
+    const int cs = bx * L::NS;
     if (cs >= a.d) return;
     const int ncols = min(L::NS, a.d - cs);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
-    const size_t ch = (size_t)blockIdx.y * H + h;
+    const size_t ch = (size_t)by * H + h;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const int wcol = 16 * NIo * w;
     const bool active = wcol < ncols;
