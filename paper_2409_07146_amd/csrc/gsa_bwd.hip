@@ -44,8 +44,11 @@ template <typename T, int M> struct DzLds {
     static constexpr size_t oTot = oA;   // gate_prep's scratch, dead before As is written
     static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                   : sizeof(float) * Geo<T>::NT;
+    static constexpr size_t oVt = oA + szA;                           // Vt [M][lda]
+    static constexpr size_t oRb = oVt + sizeof(T) * M * lda;          // Rb [C/16][M] fp32
+    static constexpr size_t end = oRb + sizeof(float) * (C / 16) * M;
     static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
-    static constexpr size_t bytes = (oA + szA > szRed) ? oA + szA : szRed;
+    static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
 template <typename T, int M>
@@ -79,7 +82,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
     float dp[MI][4];
     bool unsafe;
     gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
-                          reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn,
+                          reinterpret_cast<T *>(smem + L::oVt), L::lda, static_cast<T *>(nullptr), 0,
+                          reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn,
                           (size_t)d_v, ci.len, tid);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll

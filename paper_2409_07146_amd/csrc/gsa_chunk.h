@@ -73,6 +73,43 @@ __device__ __forceinline__ void reduce_row_blocks(f32x4 (&own)[NB], const f32x4 
     }
 }
 
+// Write-intensity tiles of one chunk, referenced to the END of each token's own 16-token block:
+//   V[kk][i] = s_kk[i] * exp(G_end(kk)[i] - G_kk[i])  <= 1        (G_end = cumulative gate at the block's last token)
+// stored transposed, Vt[i][kk] (operand of contractions over tokens), and, if Vn is not NULL,
+// natural, Vn[kk][i] (operand of contractions over slots); plus the decay across each block,
+//   Rb[b][i] = exp(G_end(b)[i] - G_end(b-1)[i]).
+// With these, the weight between a token of row block w and an EARLIER block's token needs no
+// exponential of its own: exp(G_t - G_kk) = exp(G_t - G_start(w)) * prod of Rb over the blocks in
+// between * exp(G_end(kk) - G_kk), every factor <= 1 (nothing to clamp).  One (block, slot) pair
+// per thread and pass; no barrier inside.
+template <typename T, int M, int C>
+__device__ __forceinline__ void build_write_tiles(const float *Gs, const float *Ss, int ldg, T *Vt, int ldv, T *Vn,
+                                                  int ldn, float *Rb, int tid)
+{
+    constexpr int CI = C / 16, NT = Geo<T>::NT;
+    for (int idx = tid; idx < CI * M; idx += NT) {
+        const int b = idx / M, i = idx - b * M;
+        const float gend = Gs[(16 * b + 15) * ldg + i];
+        const float gstart = b ? Gs[(16 * b - 1) * ldg + i] : 0.f;
+        Rb[b * M + i] = __expf(gend - gstart);
+        float x[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int kk = 16 * b + e;
+            x[e] = Ss[kk * ldg + i] * __expf(gend - Gs[kk * ldg + i]);
+        }
+        float lo[8], hi[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { lo[e] = x[e]; hi[e] = x[8 + e]; }
+        store8<T>(Vt + i * ldv + 16 * b, lo);
+        store8<T>(Vt + i * ldv + 16 * b + 8, hi);
+        if (Vn) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) Vn[(16 * b + e) * ldn + i] = from_f32<T>(x[e]);
+        }
+    }
+}
+
 // For this wave's row block (rows t = rowb .. rowb+15), in D layout (lane holds slot
 // i = 16*ni + lane%16, rows t = rowb + 4*(lane/16) + j):
 //
@@ -90,13 +127,14 @@ __device__ __forceinline__ void reduce_row_blocks(f32x4 (&own)[NB], const f32x4 
 // The gate tiles Gs, Ss are produced in here as well (from g: [len][M] fp32, row stride gld;
 // `tot`: scratch of NT floats): the gate loads are issued after the contraction and land during
 // the reduction, and the tiles are written once the reduction buffer is dead, so Red may alias
-// Gs and Ss too.  As [C][lda] is left holding the causally masked X Y^T rounded to T.
+// Gs and Ss too.  As [C][lda] is left holding the causally masked X Y^T rounded to T, and the tiles
+// of build_write_tiles are left in Vt, Vn (may be NULL), Rb for the caller's own use.
 // All threads of the workgroup must call it.
 template <typename T, int M, int C>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
-                                             float *tot, const float *g, size_t gld, T *As, int lda, f32x4 *Red,
-                                             const T *X, const T *Y, size_t ldx, int d, const T *St, size_t ldst,
-                                             int len, int tid)
+                                             float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
+                                             T *Vn, int ldn, float *Rb, f32x4 *Red, const T *X, const T *Y,
+                                             size_t ldx, int d, const T *St, size_t ldst, int len, int tid)
 {
     constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -156,36 +194,40 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
             const int t = rowb + g4 + j, rr = ni * 16 + r;
             As[t * lda + rr] = from_f32<T>((ni <= w && rr <= t) ? accA[ni][j] : 0.f);
         }
+    build_write_tiles<T, M, C>(Gs, Ss, ldg, Vt, ldv, Vn, ldn, Rb, tid);
     __syncthreads();
     unsafe = block_unsafe<M>(Gs, ldg, rowb, lane);
-    const int kend = unsafe ? rowb : rowb + 16;   // tokens the factored contraction covers
-    f32x4 accI[MI];
+    // ---- earlier row blocks, through the end-referenced tile: `run` walks its reference from the chunk
+    // start (where it is the inter-chunk term) to the start of this wave's block, one block at a time
+    f32x4 run[MI];
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni) accI[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ni = 0; ni < MI; ++ni) run[ni] = accZ[ni];
+    for (int bp = 0; bp < w; ++bp) {
+        const typename Atom<T>::Frag16 a = Atom<T>::load16(As + (rowb + r) * lda + bp * 16 + g4);
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni) {
+            const float dec = Rb[bp * M + ni * 16 + r];
+            run[ni] *= dec;
+            const typename Atom<T>::Frag16 bfr = Atom<T>::load16(Vt + (ni * 16 + r) * ldv + bp * 16 + g4);
+            Atom<T>::mma16(run[ni], a, bfr);
+        }
+    }
+    // ---- this wave's own block: operand generated here, referenced to the block's start
     float gref[MI];
 #pragma unroll
     for (int ni = 0; ni < MI; ++ni) gref[ni] = rowb ? Gs[(rowb - 1) * ldg + ni * 16 + r] : 0.f;
-    // Every LDS read below is unconditional (tokens up to k0+31 < C exist in the tiles; the clamp keeps
-    // the unused ones finite) and masking is a register select: a read under a per-lane branch would
-    // wait out the full LDS latency element by element.
-    for (int k0 = 0; k0 < kend; k0 += 32) {
-        const typename Atom<T>::Frag a = Atom<T>::load(As + (rowb + r) * lda + k0 + g8);
+    if (!unsafe) {
+        const typename Atom<T>::Frag16 a = Atom<T>::load16(As + (rowb + r) * lda + rowb + g4);
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) {
             const int i = ni * 16 + r;
-            float sv[8], gv[8];
+            typename Atom<T>::Frag16 bfr;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                sv[e] = Ss[(k0 + g8 + e) * ldg + i];
-                gv[e] = Gs[(k0 + g8 + e) * ldg + i];
+            for (int e = 0; e < 4; ++e) {
+                const int kk = rowb + g4 + e;
+                bfr[e] = from_f32<T>(Ss[kk * ldg + i] * __expf(fminf(gref[ni] - Gs[kk * ldg + i], kExpClamp)));
             }
-            typename Atom<T>::Frag b;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float val = sv[e] * __expf(fminf(gref[ni] - gv[e], kExpClamp));
-                b[e] = from_f32<T>((k0 + g8 + e < kend) ? val : 0.f);
-            }
-            Atom<T>::mma(accI[ni], a, b);
+            Atom<T>::mma16(run[ni], a, bfr);
         }
     }
 #pragma unroll
@@ -195,7 +237,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
             const float G = Gs[t * ldg + i];
-            float val = __expf(G) * accZ[ni][j] + __expf(G - gref[ni]) * accI[ni][j];
+            float val = __expf(G - gref[ni]) * run[ni][j];
             if (unsafe) {
                 float sum = 0.f;
                 for (int rr = rowb; rr <= t; ++rr)

@@ -48,6 +48,13 @@ template <> struct Atom<bf16_t> {
     __device__ static __forceinline__ void mma(f32x4 &c, const Frag &a, const Frag &b) {
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
     }
+    // depth-16 form: lane l holds row l%16 and the four contraction indices 4*(l/16) .. +3
+    typedef bf16x4 Frag16;
+    __device__ static __forceinline__ Frag16 load16(const bf16_t *p) { return *reinterpret_cast<const Frag16 *>(p); }
+    __device__ static __forceinline__ void mma16(f32x4 &c, const Frag16 &a, const Frag16 &b) {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        c = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+    }
 };
 
 template <> struct Atom<float> {
@@ -66,6 +73,13 @@ template <> struct Atom<float> {
         // instruction e contracts k = {e, 8+e, 16+e, 24+e}: lane group l/16 supplies k = 8*(l/16)+e
 #pragma unroll
         for (int e = 0; e < 8; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], c, 0, 0, 0);
+    }
+    // depth-16 form: lane l holds row l%16 and the four contraction indices 4*(l/16) .. +3
+    typedef f32x4 Frag16;
+    __device__ static __forceinline__ Frag16 load16(const float *p) { return *reinterpret_cast<const Frag16 *>(p); }
+    __device__ static __forceinline__ void mma16(f32x4 &c, const Frag16 &a, const Frag16 &b) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], c, 0, 0, 0);
     }
 };
 

@@ -92,8 +92,12 @@ template <typename T, int M> struct ChunkFwdLds {
     static constexpr size_t szA = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                   : sizeof(float) * Geo<T>::NT;
     static constexpr size_t oP = oA + szA;
+    static constexpr size_t oVt = oP + sizeof(T) * C * ldp;           // Vt [M][lda]
+    static constexpr size_t oVn = oVt + sizeof(T) * M * lda;          // Vn [C][ldp]
+    static constexpr size_t oRb = oVn + sizeof(T) * C * ldp;          // Rb [C/16][M] fp32
+    static constexpr size_t end = oRb + sizeof(float) * (C / 16) * M;
     static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
-    static constexpr size_t bytes = (oP + sizeof(T) * C * ldp > szRed) ? oP + sizeof(T) * C * ldp : szRed;
+    static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
 template <typename T, int M>
@@ -128,8 +132,10 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
     float p[MI][4];
     bool unsafe;
-    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
-                          reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn,
+    T *Vt = reinterpret_cast<T *>(smem + L::oVt), *Vn = reinterpret_cast<T *>(smem + L::oVn);
+    float *Rb = reinterpret_cast<float *>(smem + L::oRb);
+    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Vn,
+                          L::ldp, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn,
                           (size_t)d_k, ci.len, tid);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
