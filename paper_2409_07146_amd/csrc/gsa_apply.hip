@@ -14,7 +14,7 @@
 //              dv = A2^T dO + (s e^{G_C-G}) E_v
 //
 // One workgroup per (column slice, chunk, head, output).  Both wide operands arrive with the
-// column index fastest (token rows; rows of the slot memory as the scans store it) while the
+// column index fastest (token rows; slot rows inside the tiles the scans store) while the
 // matrix cores want the contraction index fastest, so each is loaded with whole-row 16-byte
 // loads and transposed on its way into LDS (XOR-swizzled so the transposing stores spread over
 // all banks).  One LDS tile serves the slot operand, then the token operand, then the output
@@ -29,7 +29,7 @@ template <typename T> struct ApplyOne {
     const T *A_tok;       // [chunk][H][C][C]
     const T *A_slot;      // [chunk][H][C][KM]
     const T *xtok;        // [tokens][H][d]
-    const T *xslot;       // record base + block offset: [M][d] per (chunk, head)
+    const T *xslot;       // record base + offset of the part: M slots x d columns per (chunk, head), tiled
     long long xs_stride;  // elements per (chunk, head) record
     T *out;               // [tokens][H][d]
     int d;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
 
     // every global load of the workgroup is issued here, in the order the data is needed
     TokTile<T, M, L::NS, NT> ts;   // the slot memory's column slice, rows = slots
-    ts.load(a.xslot + ch * a.xs_stride + cs, (size_t)a.d, M, ncols, tid);
+    ts.load_snapshot(a.xslot + ch * a.xs_stride, cs, ncols, tid);
     TokTile<T, C, L::NS, NT> tt;   // the token tensor's column slice
     tt.load(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);
     // the two small matrices go through LDS: every wave needs all of both

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const size_t ch = (size_t)cid * H + h;
-    const T *Vn = S + ch * lay.stride + lay.oV;      // value memory at chunk start [M][d_v]
+    const T *Vn = S + ch * lay.stride + lay.oV;      // value memory at chunk start (tiled)
     const int rowb = 16 * w;
 
     float dp[MI][4];
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
     gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
                           reinterpret_cast<T *>(smem + L::oVt), L::lda, static_cast<T *>(nullptr), 0,
                           reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn,
-                          (size_t)d_v, ci.len, tid);
+                          ci.len, tid);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
     const T *EV = a.E + ch * a.lay.stride + a.lay.oV;
     int chunk0, nch, stok0, sntok;
     seq_lookup(cm, ci.seq, chunk0, nch, stok0, sntok);
-    const T *SendK, *SendV;                                  // memory at chunk end, natural
+    const T *SendK, *SendV;                                  // memory at chunk end
     if (ci.idx + 1 < nch) {
         const T *rec = a.S + (ch + H) * a.lay.stride;        // = start of the next chunk
         SendK = rec + a.lay.oK;
@@ -257,8 +257,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
         }
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) {
-            ek[ni] = (uint32_t)(ni * 16 + r) * (uint32_t)d_k + g8;
-            ev[ni] = (uint32_t)(ni * 16 + r) * (uint32_t)d_v + g8;
+            ek[ni] = ev[ni] = (uint32_t)(ni * 16 + r) * kSnapTile + g8;   // snapshot parts are tiled
         }
         const T *qb = a.q + tokh * d_k, *kb = a.k + tokh * d_k, *vb = a.v + tokh * d_v;
         // key half: A = Q K^T, X += K E_k^T
@@ -269,9 +268,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni) fk[ni] = Atom<T>::load(kb + tk[ni] + k0);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EK + ek[ni] + k0);
+            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EK + ek[ni] + snap_col<M>(k0));
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendK + ek[ni] + k0);
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendK + ek[ni] + snap_col<M>(k0));
             __builtin_amdgcn_sched_barrier(0);   // all loads of the step before its multiplies (see gated_scores)
 #pragma unroll
             for (int rb = 0; rb < NW; ++rb) {
@@ -289,9 +288,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni) fv[ni] = Atom<T>::load(vb + tv[ni] + k0);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EV + ev[ni] + k0);
+            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EV + ev[ni] + snap_col<M>(k0));
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendV + ev[ni] + k0);
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendV + ev[ni] + snap_col<M>(k0));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int rb = 0; rb < NW; ++rb)

@@ -118,8 +118,8 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // i.e. the inter-chunk plus intra-chunk parts of one gated pass whose gate sits on the
 // slot side (pass 1 of Eq. (gsa-2pass) with X=q, Y=k, St=Kt; its mirror in the backward
 // with X=dO, Y=v, St=Vt).  X, Y: [len][d] rows in global memory (row stride ldx elements);
-// St: [M][d] rows of T (stride ldst).  The contraction over d reads its operand fragments
-// straight from global memory (each lane 16 bytes of one row; no staging).  It is split over
+// St: one part of a memory snapshot (M slots, d columns, tiled as StateLayout describes).
+// The contraction over d reads its operand fragments straight from global memory (each lane 16 bytes of one row; no staging).  It is split over
 // the waves in steps of 32 columns, wave w taking steps w, w+NW, ...: neighbouring waves ask
 // for the two halves of a 128-byte line at about the same time, so each line crosses the
 // memory system once.  The partial sums meet through Red (see reduce_row_blocks; Red may
@@ -134,7 +134,7 @@ template <typename T, int M, int C>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
                                              T *Vn, int ldn, float *Rb, f32x4 *Red, const T *X, const T *Y,
-                                             size_t ldx, int d, const T *St, size_t ldst, int len, int tid)
+                                             size_t ldx, int d, const T *St, int len, int tid)
 {
     constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -154,7 +154,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) xo[ni] = (uint32_t)min(ni * 16 + r, len - 1) * (uint32_t)ldx + g8;
 #pragma unroll
-        for (int ni = 0; ni < MI; ++ni) so[ni] = (uint32_t)(ni * 16 + r) * (uint32_t)ldst + g8;
+        for (int ni = 0; ni < MI; ++ni) so[ni] = (uint32_t)(ni * 16 + r) * kSnapTile + g8;
         typedef typename Atom<T>::Frag Frag;
         for (int k0 = 32 * w; k0 < d; k0 += 32 * NW) {
             Frag fx[CI], fy[CI], fs[MI];
@@ -163,7 +163,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
 #pragma unroll
             for (int ni = 0; ni < CI; ++ni) fy[ni] = Atom<T>::load(Y + xo[ni] + k0);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(St + so[ni] + k0);
+            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(St + so[ni] + snap_col<M>(k0));
             // keep every load of the step ahead of its multiplies: left alone, the scheduler sinks loads
             // between the multiplies to save registers and the wave ends up with one or two in flight.
             // (A second register set for the next step's loads measured slower.)

@@ -422,6 +422,25 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             lb[u] = ok && 2 * rp + 1 < len;
         }
     }
+    // The same for a column slice of one part of a memory snapshot (C slots, all present; the part is
+    // tiled by kSnapTile columns): col0 = first column of the slice.
+    __device__ __forceinline__ void load_snapshot(const T *part, int col0, int ncols, int tid)
+    {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            int idx = tid + NT * u;
+            const bool in = idx < NVEC;
+            idx = in ? idx : 0;
+            const int rp = idx / (NCOLS / 8);
+            int cg = idx - rp * (NCOLS / 8);
+            const bool ok = in && cg * 8 < ncols;
+            cg = ok ? cg : 0;
+            const T *p = part + snap_col<C>(col0 + cg * 8);
+            a[u].load(p + (2 * rp) * kSnapTile);
+            b[u].load(p + (2 * rp + 1) * kSnapTile);
+            la[u] = lb[u] = ok;
+        }
+    }
     __device__ __forceinline__ void store_transposed(T *XT, int ld, int ncols, int tid) const
     {
 #pragma unroll

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     const int r = lane & 15, g4 = (lane >> 4) * 4;
     const size_t tokh = (size_t)ci.tok0 * H + h;
     const size_t ch = (size_t)cid * H + h;
-    const T *Kn = S + ch * lay.stride + lay.oK;      // key memory at chunk start [M][d_k]
+    const T *Kn = S + ch * lay.stride + lay.oK;      // key memory at chunk start (tiled)
     const int rowb = 16 * w;                          // this wave's row block
 
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     float *Rb = reinterpret_cast<float *>(smem + L::oRb);
     gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Vn,
                           L::ldp, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn,
-                          (size_t)d_k, ci.len, tid);
+                          ci.len, tid);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll

@@ -14,7 +14,8 @@
 //   * one workgroup per (sequence, head, column slice); the slice of acc lives in MFMA
 //     accumulators for the whole sequence;
 //   * the tiles of chunk n+1 are prefetched into registers while chunk n is multiplied;
-//   * snapshots leave through an LDS tile so that global stores are full rows;
+//   * snapshots leave through an LDS tile, as one contiguous block per workgroup (the records are
+//     tiled by column slice for this);
 //   * workgroups that share (sequence, head) — and therefore W and dec — are mapped to
 //     the same XCD so those re-reads hit its L2.
 #include "gsa_chunk.h"
@@ -168,7 +169,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
                     dstl[(mi * 16 + g4 + j) * L::lds + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
     };
     auto snapshot_to_global = [&](T *rec, int b) {   // rec: start of the record
-        T *dst = rec + (isK ? a.lay.oK : a.lay.oV);
+        static_assert(NS == kSnapTile, "one workgroup owns one tile of the record");
+        T *dst = rec + (isK ? a.lay.oK : a.lay.oV) + (size_t)(c0 / kSnapTile) * (M * kSnapTile);   // contiguous [M][NS]
         const T *srcl = Sn(b);
         // LDS reads first (clamped, unconditional), then the stores: no read sits under a branch
         Raw8<T> x[SV];
@@ -179,8 +181,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
         }
 #pragma unroll
         for (int u = 0; u < SV; ++u) {
-            const int idx = tid + NT * u, i = idx / (NS / 8), cg = idx - i * (NS / 8);
-            if (SVEC % NT == 0 || idx < SVEC) x[u].store(dst + (size_t)i * dsrc + c0 + cg * 8);
+            const int idx = tid + NT * u;
+            if (SVEC % NT == 0 || idx < SVEC) x[u].store(dst + (size_t)idx * 8);
         }
     };
     // staged registers -> LDS set b (W as is, X transposed)
