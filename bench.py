@@ -40,6 +40,80 @@ def per_token_head_flops(cfg, C=64):
     return fwd, bwd, alg_fwd, alg_bwd
 
 
+def prefill_decode(args):
+    """Generation workload (the shape of the paper's Figure 4c measurement): batch 1, 24 layers of
+    H=4, m=64, d=512; a 2048-token prefix through gsa_fwd, whose final memories seed a token-by-token
+    gsa_decode_step loop over the layers.  One decode token = 24 dependent launches of 4 memories each,
+    a latency-bound regime, so the loop is also replayed from a HIP graph."""
+    import torch
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd import synth
+    dev = torch.device("cuda:0")
+    L, T, ntok = 24, 2048, args.decode_steps
+    cfg = synth.GsaConfig("prefill", B=1, T=T, H=4, d_k=512, d_v=512, m=64, dtype="bf16", seed=41)
+    x = synth.make_inputs(cfg)
+    q, k, v, g = (x[n].to(dev) for n in ("q", "k", "v", "g"))
+    prob = gsa.make_problem(q, v, g, 1.0, None)
+    ws = gsa.alloc_workspace(prob, False, dev)
+
+    def prefill():
+        return [gsa.gsa_fwd(q, k, v, g, save_z=False, final_state=True, workspace=ws)[2:] for _ in range(L)]
+
+    states = prefill()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        states = prefill()
+    torch.cuda.synchronize()
+    prefill_ms = (time.perf_counter() - t0) / 3 * 1e3
+    d = synth.make_decode_inputs(1, 4, 512, 512, 64, 4, seed=42)
+    dq_, dk_, dv_, dg_ = (d[n].to(dev) for n in ("q", "k", "v", "g"))
+    out = torch.empty_like(dv_[0])
+    dws = gsa.alloc_decode_workspace(1, 4, 512, 512, 64, dev) if not args.decode_one_workgroup else None
+
+    def token(i):
+        for KT, VT in states:
+            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], KT, VT, out=out, workspace=dws)
+
+    for i in range(8):
+        token(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(ntok):
+        token(i)
+    torch.cuda.synchronize()
+    eager_us = (time.perf_counter() - t0) / ntok * 1e6
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        token(0)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        token(0)
+    for _ in range(8):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(ntok):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_us = (time.perf_counter() - t0) / ntok * 1e6
+    state_bytes = 2 * 4 * L * 4 * 64 * 1024
+    print(json.dumps({
+        "metric": "gsa_decode_tokens_per_s_batch1", "value": round(1e6 / graph_us, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": ntok, "warmup": 8, "ms_per_step": round(graph_us * 1e-3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "prefill_decode: batch 1, 24 layers x (H=4 m=64 d_k=d_v=512), 2048-token prefix "
+                               "(bf16) then one %s per layer and token (fp32 memories), HIP graph over the 24 layers"
+                               % ("gsa_decode_step" if dws is None else "gsa_decode_step_ws")},
+        "decode_token_us": {"hip_graph": round(graph_us, 2), "eager_launches": round(eager_us, 2),
+                            "per_layer_step_graph": round(graph_us / L, 2)},
+        "state_GB_per_s": round(state_bytes / graph_us / 1e3, 1),
+        "prefill": {"ms_24_layers": round(prefill_ms, 3), "tokens_per_s": round(T / (prefill_ms * 1e-3), 1)},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,11 +122,16 @@ def main():
     ap.add_argument("--workload", default="layer_1p3b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=512)
+    ap.add_argument("--decode-one-workgroup", action="store_true",
+                    help="prefill_decode: use gsa_decode_step (one workgroup per memory) instead of gsa_decode_step_ws")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the operator has no cross-GPU path); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "prefill_decode":
+        return prefill_decode(args)
 
     import torch
     import paper_2409_07146_amd as gsa

@@ -127,9 +127,22 @@ def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale
     return dq, dk, dv, dg, dK0, dV0
 
 
-def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None):
+def gsa_decode_workspace_bytes(B, H, d_k, d_v, m) -> int:
+    n = ctypes.c_size_t(0)
+    rc = _lib.load().gsa_decode_workspace_bytes(B, H, d_k, d_v, m, ctypes.byref(n))
+    if rc != 0:
+        raise GsaError(rc, "gsa_decode_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_decode_workspace(B, H, d_k, d_v, m, device) -> torch.Tensor:
+    return torch.empty(max(gsa_decode_workspace_bytes(B, H, d_k, d_v, m), 256), dtype=torch.uint8, device=device)
+
+
+def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace=None):
     """q,k [B,H,d_k], v [B,H,d_v], g [B,H,m]; K_state,V_state fp32 [B,H,m,d], updated in place.
-    Returns o [B,H,d_v]."""
+    With a workspace (alloc_decode_workspace) the call goes through gsa_decode_step_ws, which spreads
+    each memory over several workgroups when B*H is small.  Returns o [B,H,d_v]."""
     B, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     if q.dtype not in _DTYPES:
@@ -140,6 +153,13 @@ def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None):
     _check(V_state, "V_state", torch.float32, (B, H, m, d_v))
     o = torch.empty_like(v) if out is None else out
     _check(o, "out", q.dtype, (B, H, d_v))
+    if workspace is not None:
+        rc = _lib.load().gsa_decode_step_ws(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), _ptr(q), _ptr(k),
+                                            _ptr(v), _ptr(g), _ptr(K_state), _ptr(V_state), _ptr(o),
+                                            _ptr(workspace), workspace.numel(), _stream(q))
+        if rc != 0:
+            raise GsaError(rc, "gsa_decode_step_ws")
+        return o
     rc = _lib.load().gsa_decode_step(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), _ptr(q), _ptr(k),
                                      _ptr(v), _ptr(g), _ptr(K_state), _ptr(V_state), _ptr(o), _stream(q))
     if rc != 0:

@@ -103,6 +103,40 @@ gsa_status check_workspace(void *ws, size_t have, size_t need)
     return GSA_OK;
 }
 
+gsa_status decode_checks(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale)
+{
+    if (B < 0 || H < 1 || d_k < 1 || d_v < 1 || m < 1) return GSA_ERR_SHAPE;
+    if (dtype != GSA_F32 && dtype != GSA_BF16) return GSA_ERR_SHAPE;
+    if (!(scale == scale)) return GSA_ERR_SHAPE;
+    if ((int64_t)B * H > 0x7fffffff) return GSA_ERR_SHAPE;
+    if (d_k % 64 || d_v % 64 || d_k > 1024 || d_v > 1024) return GSA_ERR_UNSUPPORTED;
+    if (!valid_m(m, false)) return GSA_ERR_UNSUPPORTED;
+    return GSA_OK;
+}
+
+gsa_status decode_any(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
+                      const void *q, const void *k, const void *v, const float *g, float *K_state, float *V_state,
+                      void *o, bool with_ws, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const gsa_status st = decode_checks(B, H, d_k, d_v, m, dtype, scale);
+    if (st != GSA_OK) return st;
+    if (B == 0) return GSA_OK;
+    if (!q || !k || !v || !g || !K_state || !V_state || !o) return GSA_ERR_NULL;
+    const void *ptrs[] = {q, k, v, g, K_state, V_state, o};
+    for (const void *ptr : ptrs)
+        if (!aligned16(ptr)) return GSA_ERR_SHAPE;
+    float *scratch = nullptr;
+    if (with_ws) {
+        const size_t need = gsa::decode_scratch_floats(B * H, d_v, m) * sizeof(float);
+        const gsa_status ws = check_workspace(workspace, workspace_bytes, need);
+        if (ws != GSA_OK) return ws;
+        if (need) scratch = static_cast<float *>(workspace);
+    }
+    const hipError_t e = gsa::launch_decode(B * H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o,
+                                            scratch, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -177,20 +211,24 @@ gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32
                            const void *q, const void *k, const void *v, const float *g, float *K_state,
                            float *V_state, void *o, void *stream)
 {
-    if (B < 0 || H < 1 || d_k < 1 || d_v < 1 || m < 1) return GSA_ERR_SHAPE;
-    if (dtype != GSA_F32 && dtype != GSA_BF16) return GSA_ERR_SHAPE;
-    if (!(scale == scale)) return GSA_ERR_SHAPE;
-    if ((int64_t)B * H > 0x7fffffff) return GSA_ERR_SHAPE;
-    if (d_k % 64 || d_v % 64 || d_k > 1024 || d_v > 1024) return GSA_ERR_UNSUPPORTED;
-    if (!valid_m(m, false)) return GSA_ERR_UNSUPPORTED;
-    if (B == 0) return GSA_OK;
-    if (!q || !k || !v || !g || !K_state || !V_state || !o) return GSA_ERR_NULL;
-    const void *ptrs[] = {q, k, v, g, K_state, V_state, o};
-    for (const void *ptr : ptrs)
-        if (!aligned16(ptr)) return GSA_ERR_SHAPE;
-    const hipError_t e = gsa::launch_decode(B * H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o,
-                                            static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+    return decode_any(B, H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o, false, nullptr, 0, stream);
+}
+
+gsa_status gsa_decode_workspace_bytes(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, size_t *bytes)
+{
+    if (!bytes) return GSA_ERR_NULL;
+    const gsa_status st = decode_checks(B, H, d_k, d_v, m, GSA_F32, 1.0f);
+    if (st != GSA_OK) return st;
+    *bytes = align_up(gsa::decode_scratch_floats(B * H, d_v, m) * sizeof(float));
+    return GSA_OK;
+}
+
+gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
+                              const void *q, const void *k, const void *v, const float *g, float *K_state,
+                              float *V_state, void *o, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return decode_any(B, H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o, true, workspace,
+                      workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -7,6 +7,12 @@
 // writes back with the same mapping.  Reductions (row dots for the slot scores,
 // the slot-weighted sum for the output) go through wave shuffles and LDS in a
 // fixed order, so results are bitwise reproducible.
+//
+// With few memory pairs (small batches) one workgroup per pair leaves most of the chip idle
+// and the step is bound by what one compute unit can stream.  The split form spreads a pair
+// over m/4 workgroups of four waves (one slot row of both memories per wave); each writes its
+// unnormalised partial output with its own softmax maximum and sum to a workspace, and a second,
+// tiny kernel merges the partials of a pair in a fixed order.  No workgroup waits for another.
 #include "gsa_common.h"
 #include "gsa_internal.h"
 
@@ -14,6 +20,8 @@ namespace gsa {
 
 constexpr int kDecThreads = 1024;
 constexpr int kDecWaves = kDecThreads / kWave;
+constexpr int kSplitWaves = 4;                    // waves (= slot rows) per workgroup of the split form
+constexpr int kSplitPairsMax = 64;                // the split form is used up to this many memory pairs (measured crossover)
 
 template <typename T> __device__ __forceinline__ f32x4 load4(const T *p);
 template <> __device__ __forceinline__ f32x4 load4<float>(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
@@ -31,21 +39,28 @@ template <> __device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t *p) {
 // end with the usual rescaling.  So there is a single barrier, at the end, and no wave waits for
 // another before its stores are issued.  No load sits under a data-dependent branch: column
 // indices past the width are clamped and the lanes masked by register selects.
-template <typename T, int M, int NV, bool EARLY_V>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(int d_k, int d_v, float scale,
-                                                             const T *__restrict__ q, const T *__restrict__ k,
-                                                             const T *__restrict__ v, const float *__restrict__ g,
-                                                             float *__restrict__ Kst, float *__restrict__ Vst,
-                                                             T *__restrict__ o)
+//
+// SPLIT: the workgroup has NWAVES waves and covers NWAVES*R slots of its pair (blockIdx.x =
+// pair * nsplit + part); instead of the output it writes to `scratch`, per pair
+// [nsplit][2] (maximum, sum) followed by [nsplit][d_v] (unnormalised partial output).
+template <typename T, int M, int NV, bool EARLY_V, int NWAVES, bool SPLIT>
+__global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v, float scale,
+                                                               const T *__restrict__ q, const T *__restrict__ k,
+                                                               const T *__restrict__ v, const float *__restrict__ g,
+                                                               float *__restrict__ Kst, float *__restrict__ Vst,
+                                                               T *__restrict__ o, float *__restrict__ scratch)
 {
-    static_assert(M % kDecWaves == 0, "slots must split evenly over the waves");
-    constexpr int R = M / kDecWaves;  // rows (slots) per wave
+    static_assert(M % NWAVES == 0, "slots must split evenly over the waves");
+    constexpr int R = SPLIT ? 1 : M / NWAVES;   // rows (slots) per wave
+    constexpr int NSPLIT = SPLIT ? M / (NWAVES * R) : 1;
+    constexpr int NTHREADS = NWAVES * kWave;
     extern __shared__ float smem[];
-    float *ms = smem;                 // [kDecWaves][2] wave maximum and sum
-    float *part = smem + 128;         // [kDecWaves][d_v] partial outputs
+    float *ms = smem;                 // [NWAVES][2] wave maximum and sum
+    float *part = smem + 128;         // [NWAVES][d_v] partial outputs
 
-    const int bh = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bh = blockIdx.x / NSPLIT, piece = blockIdx.x % NSPLIT;
+    const int tid = threadIdx.x, lane = tid & 63, wave0 = tid >> 6;
+    const int wave = piece * NWAVES + wave0;      // index of this wave's first slot row, in units of R rows
     float *Kb = Kst + (size_t)bh * M * d_k;
     float *Vb = Vst + (size_t)bh * M * d_v;
     const T *qb = q + (size_t)bh * d_k, *kb = k + (size_t)bh * d_k, *vb = v + (size_t)bh * d_v;
@@ -145,72 +160,151 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(int d_k, int d_v, f
     }
 #pragma unroll
     for (int j = 0; j < NV; ++j)
-        if (okv[j]) *reinterpret_cast<f32x4 *>(part + (size_t)wave * d_v + colv[j]) = acc[j];
-    if (lane == 0) { ms[2 * wave] = mw; ms[2 * wave + 1] = sw; }
+        if (okv[j]) *reinterpret_cast<f32x4 *>(part + (size_t)wave0 * d_v + colv[j]) = acc[j];
+    if (lane == 0) { ms[2 * wave0] = mw; ms[2 * wave0 + 1] = sw; }
     __syncthreads();
-    // ---- merge the 16 wave-local softmaxes
+    // ---- merge the wave-local softmaxes of the workgroup
     float mx = ms[0];
 #pragma unroll
-    for (int w = 1; w < kDecWaves; ++w) mx = fmaxf(mx, ms[2 * w]);
-    float fw[kDecWaves], den = 0.f;
+    for (int w = 1; w < NWAVES; ++w) mx = fmaxf(mx, ms[2 * w]);
+    float fw[NWAVES], den = 0.f;
 #pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) { fw[w] = __expf(ms[2 * w] - mx); den += fw[w] * ms[2 * w + 1]; }
+    for (int w = 0; w < NWAVES; ++w) { fw[w] = __expf(ms[2 * w] - mx); den += fw[w] * ms[2 * w + 1]; }
+    if (SPLIT) {
+        float *sp = scratch + (size_t)bh * NSPLIT * (d_v + 2);
+        if (tid == 0) { sp[2 * piece] = mx; sp[2 * piece + 1] = den; }
+        float *po = sp + 2 * NSPLIT + (size_t)piece * d_v;
+        for (int c = tid; c < d_v; c += NTHREADS) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < NWAVES; ++w) sum += fw[w] * part[(size_t)w * d_v + c];
+            po[c] = sum;
+        }
+        return;
+    }
     const float inv = 1.f / den;
-    for (int c = tid; c < d_v; c += kDecThreads) {
+    for (int c = tid; c < d_v; c += NTHREADS) {
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) sum += fw[w] * part[(size_t)w * d_v + c];
+        for (int w = 0; w < NWAVES; ++w) sum += fw[w] * part[(size_t)w * d_v + c];
         o[(size_t)bh * d_v + c] = from_f32<T>(sum * inv);
     }
 }
 
+// Second kernel of the split form: merges the NSPLIT partial outputs of a pair (each with its
+// softmax maximum and sum) in index order.  One wave per (256 columns, pair); every load is
+// issued before the first use, so the kernel costs one trip to memory.
+template <typename T> __device__ __forceinline__ void store4_as(T *p, const f32x4 &x);
+template <> __device__ __forceinline__ void store4_as<float>(float *p, const f32x4 &x) { *reinterpret_cast<f32x4 *>(p) = x; }
+template <> __device__ __forceinline__ void store4_as<bf16_t>(bf16_t *p, const f32x4 &x) {
+    *reinterpret_cast<bf16x4 *>(p) = bf16x4{(bf16_t)x[0], (bf16_t)x[1], (bf16_t)x[2], (bf16_t)x[3]};
+}
+
+template <typename T, int NSPLIT>
+__global__ __launch_bounds__(kWave) void decode_merge_kernel(int d_v, const float *__restrict__ scratch, T *__restrict__ o)
+{
+    const int bh = blockIdx.y, col = 4 * (blockIdx.x * kWave + threadIdx.x);
+    const bool ok = col < d_v;
+    const int c = ok ? col : d_v - 4;
+    const float *sp = scratch + (size_t)bh * NSPLIT * (d_v + 2);
+    const float *po = sp + 2 * NSPLIT + c;
+    float mj[NSPLIT], lj[NSPLIT];
+    f32x4 pj[NSPLIT];
+#pragma unroll
+    for (int j = 0; j < NSPLIT; ++j) { mj[j] = sp[2 * j]; lj[j] = sp[2 * j + 1]; }
+#pragma unroll
+    for (int j = 0; j < NSPLIT; ++j) pj[j] = *reinterpret_cast<const f32x4 *>(po + (size_t)j * d_v);
+    float mx = mj[0];
+#pragma unroll
+    for (int j = 1; j < NSPLIT; ++j) mx = fmaxf(mx, mj[j]);
+    float den = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NSPLIT; ++j) {
+        const float f = __expf(mj[j] - mx);
+        den += f * lj[j];
+        acc += f * pj[j];
+    }
+    acc *= 1.f / den;
+    if (ok) store4_as<T>(o + (size_t)bh * d_v + col, acc);
+}
+
 template <typename T, int M, int NV>
 static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
-                                   const void *v, const float *g, float *K, float *V, void *o, hipStream_t st)
+                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
+                                   hipStream_t st)
 {
+    if (scratch && BH <= kSplitPairsMax) {
+        constexpr int nsplit = M / kSplitWaves;
+        const size_t lds = (128 + (size_t)kSplitWaves * d_v) * sizeof(float);
+        auto kern = decode_kernel<T, M, NV, true, kSplitWaves, true>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        {
+            KernelTimer kt(kSlotDecode, st);
+            hipLaunchKernelGGL(kern, dim3(BH * nsplit), dim3(kSplitWaves * kWave), lds, st, d_k, d_v, scale,
+                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        KernelTimer kt(kSlotDecodeMerge, st);
+        hipLaunchKernelGGL((decode_merge_kernel<T, nsplit>), dim3((d_v + 4 * kWave - 1) / (4 * kWave), BH), dim3(kWave), 0, st,
+                           d_v, scratch, (T *)o);
+        return hipGetLastError();
+    }
     const size_t lds = (128 + (size_t)kDecWaves * d_v) * sizeof(float);
     constexpr bool early = (NV * (M / kDecWaves) <= 8);
-    auto kern = decode_kernel<T, M, NV, early>;
+    auto kern = decode_kernel<T, M, NV, early, kDecWaves, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     KernelTimer kt(kSlotDecode, st);
     hipLaunchKernelGGL(kern, dim3(BH), dim3(kDecThreads), lds, st, d_k, d_v, scale, (const T *)q, (const T *)k,
-                       (const T *)v, g, K, V, (T *)o);
+                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr));
     return hipGetLastError();
 }
 
 template <typename T, int M>
 static hipError_t launch_decode_m(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
-                                  const void *v, const float *g, float *K, float *V, void *o, hipStream_t st)
+                                  const void *v, const float *g, float *K, float *V, void *o, float *scratch,
+                                  hipStream_t st)
 {
     const int dmax = d_k > d_v ? d_k : d_v;
     const int nv = (dmax + 255) / 256;
     switch (nv) {
-    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
-    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
-    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
-    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
+    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
     }
 }
 
 template <typename T>
 static hipError_t launch_decode_t(int BH, int d_k, int d_v, int m, float scale, const void *q, const void *k,
-                                  const void *v, const float *g, float *K, float *V, void *o, hipStream_t st)
+                                  const void *v, const float *g, float *K, float *V, void *o, float *scratch,
+                                  hipStream_t st)
 {
     switch (m) {
-    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
-    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
-    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
-    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, st);
+    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
     }
 }
 
-hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
-                         const void *v, const float *g, float *K, float *V, void *o, hipStream_t st)
+// Floats of workspace the split form needs for BH pairs (0: the split form is not used at this size).
+size_t decode_scratch_floats(int BH, int d_v, int m)
 {
-    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, st);
-    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, st);
+    if (BH > kSplitPairsMax) return 0;
+    return (size_t)BH * (m / kSplitWaves) * (d_v + 2);
+}
+
+hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
+                         const void *v, const float *g, float *K, float *V, void *o, float *scratch, hipStream_t st)
+{
+    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, st);
+    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, st);
 }
 
 }  // namespace gsa

@@ -47,7 +47,7 @@ struct Work {
 
 // Kernel slots of the optional per-kernel event timing (gsa_profile_*).
 enum KernelSlot { kSlotPrepare = 0, kSlotGates, kSlotScanFwd, kSlotChunkFwd, kSlotApplyFwd, kSlotChunkDz, kSlotScanBwd,
-                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kSlotCopyProbe, kNumKernelSlots };
+                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kSlotDecodeMerge, kSlotCopyProbe, kNumKernelSlots };
 
 // Brackets one kernel launch with events on its stream when timing is enabled; otherwise a no-op.
 class KernelTimer {
@@ -100,7 +100,9 @@ hipError_t launch_bwd(const Plan &pl, const Work &w, const void *q, const void *
                       const float *dVT, void *dq, void *dk, void *dv, float *dg, float *dK0, float *dV0,
                       hipStream_t st);
 
+// scratch: NULL (one workgroup per pair) or decode_scratch_floats(...) floats (split form, small BH).
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
-                         const void *v, const float *g, float *K, float *V, void *o, hipStream_t st);
+                         const void *v, const float *g, float *K, float *V, void *o, float *scratch, hipStream_t st);
+size_t decode_scratch_floats(int BH, int d_v, int m);
 
 }  // namespace gsa

@@ -91,6 +91,18 @@ def test_null_and_workspace_errors_without_device(lib):
     assert lib.gsa_decode_step(1, 1, 60, 64, 16, 1, 1.0, *([null] * 8)) == 3
     assert lib.gsa_decode_step(1, 0, 64, 64, 16, 1, 1.0, *([null] * 8)) == 2
     assert lib.gsa_decode_step(0, 1, 64, 64, 16, 1, 1.0, *([null] * 8)) == 0
+    # decode step with a workspace: size query, then the workspace checks come after the shape checks
+    n = ctypes.c_size_t(0)
+    assert lib.gsa_decode_workspace_bytes(1, 4, 512, 512, 64, ctypes.byref(n)) == 0
+    assert n.value >= 4 * 16 * 514 * 4 and n.value % 256 == 0
+    assert lib.gsa_decode_workspace_bytes(64, 4, 512, 512, 64, ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.gsa_decode_workspace_bytes(1, 4, 512, 500, 64, ctypes.byref(n)) == 3
+    assert lib.gsa_decode_workspace_bytes(1, 4, 512, 512, 64, None) == 1
+    assert lib.gsa_decode_step_ws(1, 1, 60, 64, 16, 1, 1.0, *([null] * 7), null, 0, null) == 3
+    assert lib.gsa_decode_step_ws(1, 1, 64, 64, 16, 1, 1.0, *([null] * 7), null, 0, null) == 1
+    assert lib.gsa_decode_step_ws(0, 1, 64, 64, 16, 1, 1.0, *([null] * 7), null, 0, null) == 0
+    assert lib.gsa_decode_step_ws(1, 1, 64, 64, 16, 1, 1.0, *([fake] * 7), null, 0, null) == 4       # no workspace
+    assert lib.gsa_decode_step_ws(1, 1, 64, 64, 16, 1, 1.0, *([fake] * 7), fake, 64, null) == 4      # too small
     assert lib.gsa_status_string(4).decode().startswith("workspace")
 
 

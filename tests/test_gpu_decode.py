@@ -8,7 +8,7 @@ from tests.util import check, to_np64
 pytestmark = pytest.mark.gpu
 
 
-def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5):
+def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5, split=False):
     import paper_2409_07146_amd as gsa
     from paper_2409_07146_amd import synth
     x = synth.make_decode_inputs(B, H, d_k, d_v, m, steps, state_std=0.1, seed=seed, dtype=dtype)
@@ -17,9 +17,10 @@ def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5):
     q, k, v, g = (x[n].to(dev) for n in ("q", "k", "v", "g"))
     Ko, Vo = to_np64(x["K"]).copy(), to_np64(x["V"]).copy()
     qn, kn, vn, gn = (to_np64(x[n]) for n in ("q", "k", "v", "g"))
+    ws = gsa.alloc_decode_workspace(B, H, d_k, d_v, m, dev) if split else None   # through gsa_decode_step_ws
     outs = []
     for t in range(steps):
-        outs.append(gsa.gsa_decode_step(q[t], k[t], v[t], g[t], Kg, Vg, scale=scale))
+        outs.append(gsa.gsa_decode_step(q[t], k[t], v[t], g[t], Kg, Vg, scale=scale, workspace=ws))
     torch.cuda.synchronize()
     worst = 0.0
     for t in range(steps):
@@ -38,6 +39,38 @@ def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5):
                                            (1, 2, 1024, 64, 64), (1, 1, 256, 256, 128)])
 def test_decode_small_shapes(oracle, B, H, d_k, d_v, m, dtype):
     _run(oracle, B, H, d_k, d_v, m, steps=5, dtype=dtype, scale=0.9)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,d_k,d_v,m", [(2, 2, 64, 64, 16), (3, 1, 128, 192, 32), (2, 3, 640, 576, 64),
+                                           (1, 2, 1024, 64, 64), (1, 1, 256, 256, 128), (1, 4, 512, 512, 64),
+                                           (32, 4, 128, 64, 32), (33, 4, 64, 64, 16)])
+def test_decode_with_workspace(oracle, B, H, d_k, d_v, m, dtype):
+    """gsa_decode_step_ws: memories spread over several workgroups up to 64 pairs (the last two cases are
+    past that and take the one-workgroup form)."""
+    _run(oracle, B, H, d_k, d_v, m, steps=5, dtype=dtype, scale=0.9, split=True)
+
+
+def test_decode_with_workspace_matches_plain_step():
+    """Both entry points on the same inputs: identical memories, outputs equal up to fp32 rounding order;
+    the split form is reproducible."""
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd import synth
+    dev = torch.device("cuda:0")
+    B, H, d, m = 1, 4, 512, 64
+    x = synth.make_decode_inputs(B, H, d, d, m, 3, seed=9, dtype="f32")
+    q, k, v, g = (x[n].to(dev) for n in ("q", "k", "v", "g"))
+    ws = gsa.alloc_decode_workspace(B, H, d, d, m, dev)
+    assert ws.numel() >= B * H * (m // 4) * (d + 2) * 4
+    runs = []
+    for use_ws in (None, ws, ws):
+        K, V = x["K"].to(dev), x["V"].to(dev)
+        outs = [gsa.gsa_decode_step(q[t], k[t], v[t], g[t], K, V, workspace=use_ws).clone() for t in range(3)]
+        runs.append((outs, K, V))
+    for t in range(3):
+        torch.testing.assert_close(runs[1][0][t], runs[0][0][t], rtol=1e-5, atol=1e-6)
+        assert torch.equal(runs[1][0][t], runs[2][0][t])
+    assert torch.equal(runs[0][1], runs[1][1]) and torch.equal(runs[0][2], runs[1][2])
 
 
 def test_decode_workload_512_steps_batch64(oracle):

@@ -8,15 +8,17 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_decode_step_in_a_graph():
+@pytest.mark.parametrize("split", [False, True])
+def test_decode_step_in_a_graph(split):
     import paper_2409_07146_amd as gsa
     from paper_2409_07146_amd import synth
     dev = torch.device(DEV)
+    ws = gsa.alloc_decode_workspace(4, 2, 128, 128, 64, dev) if split else None   # two kernels per step
     x = synth.make_decode_inputs(4, 2, 128, 128, 64, 6, seed=31)
     q, k, v, g = (x[n].to(dev) for n in ("q", "k", "v", "g"))
     # eager reference: six steps
     Ke, Ve = x["K"].to(dev), x["V"].to(dev)
-    ref = [gsa.gsa_decode_step(q[t], k[t], v[t], g[t], Ke, Ve).clone() for t in range(6)]
+    ref = [gsa.gsa_decode_step(q[t], k[t], v[t], g[t], Ke, Ve, workspace=ws).clone() for t in range(6)]
     # graph: one step reading its inputs from static buffers
     Kg, Vg = x["K"].to(dev), x["V"].to(dev)
     qs, ks, vs, gs = q[0].clone(), k[0].clone(), v[0].clone(), g[0].clone()
@@ -25,11 +27,11 @@ def test_decode_step_in_a_graph():
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):           # warm-up outside the capture (first-use attribute calls)
         Kw, Vw = Kg.clone(), Vg.clone()
-        gsa.gsa_decode_step(qs, ks, vs, gs, Kw, Vw, out=out)
+        gsa.gsa_decode_step(qs, ks, vs, gs, Kw, Vw, out=out, workspace=ws)
     torch.cuda.current_stream().wait_stream(side)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        gsa.gsa_decode_step(qs, ks, vs, gs, Kg, Vg, out=out)
+        gsa.gsa_decode_step(qs, ks, vs, gs, Kg, Vg, out=out, workspace=ws)
     for t in range(6):
         qs.copy_(q[t]); ks.copy_(k[t]); vs.copy_(v[t]); gs.copy_(g[t])
         graph.replay()
