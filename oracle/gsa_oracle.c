@@ -20,6 +20,15 @@
  * the memories after its own write.  The paper has no score scaling; scale is
  * an explicit argument (1.0 = the paper).
  *
+ * Variants (Algorithm 1 takes the write intensity I as an input of its own;
+ * Section 2.2, Eqs. (abc_recurrent)/(abc_phi); the read-out ablations of the
+ * ablation table in Section 4):
+ *   - write intensity given: s_t is read from an array `sin` instead of being
+ *     1 - exp(g_t).  With g = 0 and s = phi this is ABC, Eq. (abc_recurrent).
+ *     The backward then returns dg for the gate alone and ds for the intensity.
+ *   - read-out f instead of softmax: p_t = f(z_t) element by element,
+ *     f in {identity, Swish z*sigmoid(z), ReLU, ReLU^2}.
+ *
  * The backward pass is back-propagation through exactly those lines, walking
  * the tokens in reverse; the states needed on the way back are recomputed from
  * checkpoints taken every GSA_ORACLE_CKPT tokens.
@@ -47,6 +56,49 @@
 
 #define GSA_ORACLE_CKPT 64
 
+/* read-outs: how the slot scores z become the read weights p */
+enum { RO_SOFTMAX = 0, RO_IDENTITY = 1, RO_SWISH = 2, RO_RELU = 3, RO_RELU2 = 4 };
+
+static double sigmoid(double x) { return 1.0 / (1.0 + exp(-x)); }
+
+/* p = f(z) over the m slots */
+static void readout_fwd(int ro, int m, const double *z, double *p)
+{
+    if (ro == RO_SOFTMAX) {
+        double zmax = -INFINITY, den = 0.0;
+        for (int i = 0; i < m; ++i) if (z[i] > zmax) zmax = z[i];
+        for (int i = 0; i < m; ++i) { p[i] = exp(z[i] - zmax); den += p[i]; }
+        for (int i = 0; i < m; ++i) p[i] /= den;
+        return;
+    }
+    for (int i = 0; i < m; ++i) {
+        double x = z[i];
+        if (ro == RO_IDENTITY) p[i] = x;
+        else if (ro == RO_SWISH) p[i] = x * sigmoid(x);
+        else if (ro == RO_RELU) p[i] = x > 0.0 ? x : 0.0;
+        else p[i] = x > 0.0 ? x * x : 0.0;
+    }
+}
+
+/* dz from dp (p = f(z) as computed by readout_fwd) */
+static void readout_bwd(int ro, int m, const double *z, const double *p, const double *dp, double *dz)
+{
+    if (ro == RO_SOFTMAX) {
+        double pdp = 0.0;
+        for (int i = 0; i < m; ++i) pdp += p[i] * dp[i];
+        for (int i = 0; i < m; ++i) dz[i] = p[i] * (dp[i] - pdp);
+        return;
+    }
+    for (int i = 0; i < m; ++i) {
+        double x = z[i], d;
+        if (ro == RO_IDENTITY) d = 1.0;
+        else if (ro == RO_SWISH) { double sg = sigmoid(x); d = sg + x * sg * (1.0 - sg); }
+        else if (ro == RO_RELU) d = x > 0.0 ? 1.0 : 0.0;
+        else d = x > 0.0 ? 2.0 * x : 0.0;
+        dz[i] = d * dp[i];
+    }
+}
+
 int gsa_oracle_num_threads(void)
 {
 #ifdef _OPENMP
@@ -57,30 +109,26 @@ int gsa_oracle_num_threads(void)
 }
 
 /* One token of Eq. (gsa): update both memories in place, then read out. */
-static void step_token(int dk, int dv, int m, double scale,
-                       const double *q, const double *k, const double *v, const double *g,
+static void step_token(int dk, int dv, int m, double scale, int ro,
+                       const double *q, const double *k, const double *v, const double *g, const double *sin,
                        double *K, double *V, double *z, double *p, double *o)
 {
     for (int i = 0; i < m; ++i) {
         double a = exp(g[i]);
-        double s = -expm1(g[i]);
+        double s = sin ? sin[i] : -expm1(g[i]);
         double *Ki = K + (size_t)i * dk;
         double *Vi = V + (size_t)i * dv;
         for (int c = 0; c < dk; ++c) Ki[c] = a * Ki[c] + s * k[c];
         for (int c = 0; c < dv; ++c) Vi[c] = a * Vi[c] + s * v[c];
     }
     if (!q) return; /* state-only step (used while replaying checkpoints) */
-    double zmax = -INFINITY;
     for (int i = 0; i < m; ++i) {
         const double *Ki = K + (size_t)i * dk;
         double acc = 0.0;
         for (int c = 0; c < dk; ++c) acc += Ki[c] * q[c];
         z[i] = scale * acc;
-        if (z[i] > zmax) zmax = z[i];
     }
-    double den = 0.0;
-    for (int i = 0; i < m; ++i) { p[i] = exp(z[i] - zmax); den += p[i]; }
-    for (int i = 0; i < m; ++i) p[i] /= den;
+    readout_fwd(ro, m, z, p);
     if (!o) return;
     for (int c = 0; c < dv; ++c) o[c] = 0.0;
     for (int i = 0; i < m; ++i) {
@@ -90,13 +138,14 @@ static void step_token(int dk, int dv, int m, double scale,
 }
 
 /*
- * Forward.  K0,V0 may be NULL (zero memories, as the paper initialises them).
+ * Forward.  sin [Ttot,H,m] is the write intensity, or NULL for s = 1 - exp(g);
+ * readout is one of RO_*.  K0,V0 may be NULL (zero memories, as the paper initialises them).
  * o [Ttot,H,dv]; z_out [Ttot,H,m] (pre-softmax scores), KT,VT [n_seqs,H,m,d]
  * (memories after the last token); each of z_out, KT, VT may be NULL.
  * Returns 0, or -1 if an allocation failed.
  */
-int gsa_oracle_fwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, double scale,
-                   const double *q, const double *k, const double *v, const double *g,
+int gsa_oracle_fwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, double scale, int readout,
+                   const double *q, const double *k, const double *v, const double *g, const double *sin,
                    const double *K0, const double *V0,
                    double *o, double *z_out, double *KT, double *VT)
 {
@@ -119,8 +168,8 @@ int gsa_oracle_fwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
             if (V0) memcpy(V, V0 + sh * m * dv, sizeof(double) * (size_t)m * dv);
             for (int64_t t = cu[s]; t < cu[s + 1]; ++t) {
                 size_t th = (size_t)t * H + h;
-                step_token(dk, dv, m, scale, q + th * dk, k + th * dk, v + th * dv, g + th * m,
-                           K, V, z, p, o + th * dv);
+                step_token(dk, dv, m, scale, readout, q + th * dk, k + th * dk, v + th * dv, g + th * m,
+                           sin ? sin + th * m : NULL, K, V, z, p, o + th * dv);
                 if (z_out) memcpy(z_out + th * m, z, sizeof(double) * (size_t)m);
             }
             if (KT) memcpy(KT + sh * m * dk, K, sizeof(double) * (size_t)m * dk);
@@ -135,14 +184,16 @@ int gsa_oracle_fwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
  * Backward of L = sum_t <dO_t, o_t> + <dKT, K_T> + <dVT, V_T>.
  * dO [Ttot,H,dv]; dKT,dVT [n_seqs,H,m,d] (may be NULL = zero).
  * Outputs (double): dq,dk [Ttot,H,dk], dv [Ttot,H,dv], dg [Ttot,H,m] (gradient
- * with respect to the log forget gate g, with s = 1 - exp(g) coupled to it),
+ * with respect to the log forget gate g, with s = 1 - exp(g) coupled to it when
+ * sin is NULL; with sin given, dg is the gradient through the decay alone and
+ * dsin [Ttot,H,m] receives the gradient of the write intensity),
  * dK0,dV0 [n_seqs,H,m,d] (may be NULL).
  */
-int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, double scale,
-                   const double *q, const double *k, const double *v, const double *g,
+int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, double scale, int readout,
+                   const double *q, const double *k, const double *v, const double *g, const double *sin,
                    const double *K0, const double *V0, const double *dO,
                    const double *dKT, const double *dVT,
-                   double *dq, double *dkk, double *dvv, double *dg,
+                   double *dq, double *dkk, double *dvv, double *dg, double *dsin,
                    double *dK0, double *dV0)
 {
     int fail = 0;
@@ -183,8 +234,8 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                         memcpy(ckV + (size_t)(j / GSA_ORACLE_CKPT) * nV, V, sizeof(double) * nV);
                     }
                     size_t th = (size_t)(t0 + j) * H + h;
-                    step_token(dk, dv, m, scale, NULL, k + th * dk, v + th * dv, g + th * m,
-                               K, V, NULL, NULL, NULL);
+                    step_token(dk, dv, m, scale, readout, NULL, k + th * dk, v + th * dv, g + th * m,
+                               sin ? sin + th * m : NULL, K, V, NULL, NULL, NULL);
                 }
             }
             if (dKT) memcpy(gK, dKT + sh * nK, sizeof(double) * nK);
@@ -198,7 +249,8 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                     size_t th = (size_t)(t0 + b0 + j) * H + h;
                     memcpy(blkK + (size_t)(j + 1) * nK, blkK + (size_t)j * nK, sizeof(double) * nK);
                     memcpy(blkV + (size_t)(j + 1) * nV, blkV + (size_t)j * nV, sizeof(double) * nV);
-                    step_token(dk, dv, m, scale, NULL, k + th * dk, v + th * dv, g + th * m,
+                    step_token(dk, dv, m, scale, readout, NULL, k + th * dk, v + th * dv, g + th * m,
+                               sin ? sin + th * m : NULL,
                                blkK + (size_t)(j + 1) * nK, blkV + (size_t)(j + 1) * nV,
                                NULL, NULL, NULL);
                 }
@@ -211,15 +263,12 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                     const double *qt = q + th * dk, *kt = k + th * dk, *vt = v + th * dv;
                     const double *gt = g + th * m, *dot = dO + th * dv;
                     /* recompute z, p of this token */
-                    double zmax = -INFINITY, den = 0.0, pdp = 0.0;
                     for (int i = 0; i < m; ++i) {
                         double acc = 0.0;
                         for (int cc = 0; cc < dk; ++cc) acc += Kt[(size_t)i * dk + cc] * qt[cc];
                         z[i] = scale * acc;
-                        if (z[i] > zmax) zmax = z[i];
                     }
-                    for (int i = 0; i < m; ++i) { p[i] = exp(z[i] - zmax); den += p[i]; }
-                    for (int i = 0; i < m; ++i) p[i] /= den;
+                    readout_fwd(readout, m, z, p);
                     /* o = V^T p  =>  dV += p (x) dO,  dp = V dO */
                     for (int i = 0; i < m; ++i) {
                         double acc = 0.0;
@@ -228,10 +277,9 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                             acc += Vt[(size_t)i * dv + cc] * dot[cc];
                         }
                         dp[i] = acc;
-                        pdp += p[i] * acc;
                     }
-                    /* softmax */
-                    for (int i = 0; i < m; ++i) dz[i] = p[i] * (dp[i] - pdp);
+                    /* p = f(z) */
+                    readout_bwd(readout, m, z, p, dp, dz);
                     /* z = scale * K q  =>  dq = scale K^T dz,  dK += scale dz (x) q */
                     for (int cc = 0; cc < dk; ++cc) dq[th * dk + cc] = 0.0;
                     for (int i = 0; i < m; ++i) {
@@ -246,7 +294,7 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                     for (int cc = 0; cc < dv; ++cc) dvv[th * dv + cc] = 0.0;
                     for (int i = 0; i < m; ++i) {
                         double a = exp(gt[i]);
-                        double sw = -expm1(gt[i]);
+                        double sw = sin ? sin[th * m + i] : -expm1(gt[i]);
                         double ds = 0.0, da = 0.0;
                         for (int cc = 0; cc < dk; ++cc) {
                             double gk = gK[(size_t)i * dk + cc];
@@ -262,8 +310,12 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                             da += gv * Vp[(size_t)i * dv + cc];
                             gV[(size_t)i * dv + cc] = a * gv;
                         }
-                        /* a = exp(g), s = 1 - exp(g):  da/dg = a, ds/dg = -a */
-                        dg[th * m + i] = a * (da - ds);
+                        if (sin) {   /* a = exp(g): da/dg = a; s is an input of its own */
+                            dg[th * m + i] = a * da;
+                            dsin[th * m + i] = ds;
+                        } else {     /* a = exp(g), s = 1 - exp(g):  da/dg = a, ds/dg = -a */
+                            dg[th * m + i] = a * (da - ds);
+                        }
                     }
                 }
             }
@@ -293,8 +345,8 @@ int gsa_oracle_decode_step(int BH, int dk, int dv, int m, double scale,
             fail = 1;
             continue;
         }
-        step_token(dk, dv, m, scale, q + (size_t)b * dk, k + (size_t)b * dk, v + (size_t)b * dv,
-                   g + (size_t)b * m, K + (size_t)b * m * dk, V + (size_t)b * m * dv,
+        step_token(dk, dv, m, scale, RO_SOFTMAX, q + (size_t)b * dk, k + (size_t)b * dk, v + (size_t)b * dv,
+                   g + (size_t)b * m, NULL, K + (size_t)b * m * dk, V + (size_t)b * m * dv,
                    zp, zp + m, o + (size_t)b * dv);
         free(zp);
     }

@@ -34,14 +34,14 @@ def _lib():
         lib.gsa_oracle_num_threads.restype = ctypes.c_int
         lib.gsa_oracle_fwd.restype = ctypes.c_int
         lib.gsa_oracle_fwd.argtypes = [ctypes.c_int, _i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                       ctypes.c_int, ctypes.c_double,
-                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p,
+                                       ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p,
                                        _f64p, _f64p, _f64p, _f64p]
         lib.gsa_oracle_bwd.restype = ctypes.c_int
         lib.gsa_oracle_bwd.argtypes = [ctypes.c_int, _i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                       ctypes.c_int, ctypes.c_double,
-                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p,
-                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p]
+                                       ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p,
+                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p]
         lib.gsa_oracle_decode_step.restype = ctypes.c_int
         lib.gsa_oracle_decode_step.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_double, _f64p, _f64p, _f64p, _f64p,
@@ -73,9 +73,13 @@ def _seqs(q, cu_seqlens):
     return cu
 
 
-def fwd(q, k, v, g, cu_seqlens=None, K0=None, V0=None, scale=1.0):
-    """Returns dict(o, z, KT, VT), all float64."""
-    q, k, v, g = _f64(q), _f64(k), _f64(v), _f64(g)
+READOUTS = {"softmax": 0, "identity": 1, "swish": 2, "relu": 3, "relu2": 4}
+
+
+def fwd(q, k, v, g, cu_seqlens=None, K0=None, V0=None, scale=1.0, s=None, readout="softmax"):
+    """s: write intensity [B,T,H,m] (None: 1 - exp(g)).  Returns dict(o, z, KT, VT), all float64."""
+    q, k, v, g, s = _f64(q), _f64(k), _f64(v), _f64(g), _f64(s)
+    assert s is None or s.shape == g.shape
     B, T, H, dk = q.shape
     dv, m = v.shape[-1], g.shape[-1]
     cu = _seqs(q, cu_seqlens)
@@ -85,17 +89,19 @@ def fwd(q, k, v, g, cu_seqlens=None, K0=None, V0=None, scale=1.0):
     z = np.empty((B, T, H, m), np.float64)
     KT = np.empty((n, H, m, dk), np.float64)
     VT = np.empty((n, H, m, dv), np.float64)
-    rc = _lib().gsa_oracle_fwd(n, cu.ctypes.data_as(_i32p), H, dk, dv, m, float(scale),
-                               _p64(q), _p64(k), _p64(v), _p64(g), _p64(K0), _p64(V0),
+    rc = _lib().gsa_oracle_fwd(n, cu.ctypes.data_as(_i32p), H, dk, dv, m, float(scale), READOUTS[readout],
+                               _p64(q), _p64(k), _p64(v), _p64(g), _p64(s), _p64(K0), _p64(V0),
                                _p64(o), _p64(z), _p64(KT), _p64(VT))
     if rc != 0:
         raise MemoryError("gsa_oracle_fwd failed")
     return dict(o=o, z=z, KT=KT, VT=VT)
 
 
-def bwd(q, k, v, g, dO, cu_seqlens=None, K0=None, V0=None, dKT=None, dVT=None, scale=1.0):
-    """Returns dict(dq, dk, dv, dg, dK0, dV0), all float64."""
-    q, k, v, g, dO = _f64(q), _f64(k), _f64(v), _f64(g), _f64(dO)
+def bwd(q, k, v, g, dO, cu_seqlens=None, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, s=None,
+        readout="softmax"):
+    """Returns dict(dq, dk, dv, dg, dK0, dV0) and, when s is given, ds; all float64."""
+    q, k, v, g, dO, s = _f64(q), _f64(k), _f64(v), _f64(g), _f64(dO), _f64(s)
+    assert s is None or s.shape == g.shape
     B, T, H, dk = q.shape
     dv, m = v.shape[-1], g.shape[-1]
     cu = _seqs(q, cu_seqlens)
@@ -105,15 +111,19 @@ def bwd(q, k, v, g, dO, cu_seqlens=None, K0=None, V0=None, dKT=None, dVT=None, s
     dk_ = np.empty((B, T, H, dk), np.float64)
     dv_ = np.empty((B, T, H, dv), np.float64)
     dg = np.empty((B, T, H, m), np.float64)
+    ds = None if s is None else np.empty((B, T, H, m), np.float64)
     dK0 = np.empty((n, H, m, dk), np.float64)
     dV0 = np.empty((n, H, m, dv), np.float64)
-    rc = _lib().gsa_oracle_bwd(n, cu.ctypes.data_as(_i32p), H, dk, dv, m, float(scale),
-                               _p64(q), _p64(k), _p64(v), _p64(g), _p64(K0), _p64(V0), _p64(dO),
+    rc = _lib().gsa_oracle_bwd(n, cu.ctypes.data_as(_i32p), H, dk, dv, m, float(scale), READOUTS[readout],
+                               _p64(q), _p64(k), _p64(v), _p64(g), _p64(s), _p64(K0), _p64(V0), _p64(dO),
                                _p64(dKT), _p64(dVT),
-                               _p64(dq), _p64(dk_), _p64(dv_), _p64(dg), _p64(dK0), _p64(dV0))
+                               _p64(dq), _p64(dk_), _p64(dv_), _p64(dg), _p64(ds), _p64(dK0), _p64(dV0))
     if rc != 0:
         raise MemoryError("gsa_oracle_bwd failed")
-    return dict(dq=dq, dk=dk_, dv=dv_, dg=dg, dK0=dK0, dV0=dV0)
+    out = dict(dq=dq, dk=dk_, dv=dv_, dg=dg, dK0=dK0, dV0=dV0)
+    if ds is not None:
+        out["ds"] = ds
+    return out
 
 
 def decode_step(q, k, v, g, K, V, scale=1.0):

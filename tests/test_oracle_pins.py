@@ -8,6 +8,7 @@ the operator, so there is no golden fixture from it.
 """
 import numpy as np
 import pytest
+from scipy.special import expit as sp_expit
 from scipy.special import softmax as sp_softmax
 
 
@@ -25,10 +26,20 @@ def _rand(rng, B, T, H, dk, dv, m, gate="paper", init=False):
 
 
 # ---------------------------------------------------------------- P1
-def _brute_force(q, k, v, g, K0, V0, scale):
+_READOUT_NP = {                      # the read-outs of the ablation table, written with library functions
+    "softmax": lambda z: sp_softmax(z),
+    "identity": lambda z: z,
+    "swish": lambda z: z * sp_expit(z),
+    "relu": lambda z: np.maximum(z, 0.0),
+    "relu2": lambda z: np.maximum(z, 0.0) ** 2,
+}
+
+
+def _brute_force(q, k, v, g, K0, V0, scale, s=None, readout="softmax"):
     """Quadratic form of the two-pass view (Eq. (gsa-2pass) unrolled as Eq.
     (gla-recurrent)): explicit products D(t,r,i) = prod_{j=r+1..t} alpha_j[i],
-    no recurrence and no log-space arithmetic."""
+    no recurrence and no log-space arithmetic.  s: write intensities given as an
+    input of their own (Algorithm 1's I), else 1 - alpha."""
     T, dk = q.shape
     dv, m = v.shape[1], g.shape[1]
     alpha = np.exp(g)
@@ -40,7 +51,7 @@ def _brute_force(q, k, v, g, K0, V0, scale):
             D = np.ones(m)
             for j in range(r + 1, t + 1):
                 D = D * alpha[j]
-            w[r] = D * (1.0 - alpha[r])
+            w[r] = D * ((1.0 - alpha[r]) if s is None else s[r])
         D0 = np.ones(m)
         for j in range(t + 1):
             D0 = D0 * alpha[j]
@@ -51,8 +62,11 @@ def _brute_force(q, k, v, g, K0, V0, scale):
             if K0 is not None:
                 acc += D0[i] * float(K0[i] @ q[t])
             z[t, i] = scale * acc
-        p = np.exp(z[t] - z[t].max())
-        p = p / p.sum()
+        if readout == "softmax":
+            p = np.exp(z[t] - z[t].max())
+            p = p / p.sum()
+        else:
+            p = _READOUT_NP[readout](z[t])
         for r in range(t + 1):
             o[t] += float(p @ w[r]) * v[r]
         if V0 is not None:
@@ -346,6 +360,90 @@ def test_p9_gate_gradient_identity(oracle):
     dg_id = np.cumsum(dGam[::-1], axis=0)[::-1] - np.exp(g1) * ds
     dg = oracle.bwd(q, k, v, g, dO)["dg"][0, :, 0]
     np.testing.assert_allclose(dg, dg_id, rtol=2e-6, atol=2e-8)
+
+
+# ---------------------------------------------------------------- variants
+@pytest.mark.parametrize("readout", ["softmax", "identity", "swish", "relu", "relu2"])
+def test_v1_bruteforce_with_given_write_intensity_and_readout(oracle, readout):
+    """Write intensity as an input of its own (Algorithm 1 takes I beside A) and the read-outs of the
+    ablation table, against the explicit-product quadratic form."""
+    rng = np.random.default_rng(31)
+    T, dk, dv, m = 17, 5, 6, 4
+    q, k, v, g, K0, V0 = _rand(rng, 1, T, 1, dk, dv, m, gate="strong", init=True)
+    s = rng.uniform(0.0, 1.0, size=g.shape)
+    out = oracle.fwd(q, k, v, g, K0=K0, V0=V0, scale=0.8, s=s, readout=readout)
+    o_bf, z_bf = _brute_force(q[0, :, 0], k[0, :, 0], v[0, :, 0], g[0, :, 0], K0[0, 0], V0[0, 0], 0.8,
+                              s=s[0, :, 0], readout=readout)
+    np.testing.assert_allclose(out["z"][0, :, 0], z_bf, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(out["o"][0, :, 0], o_bf, rtol=1e-10, atol=1e-12)
+    # and the tied form is the special case s = 1 - exp(g)
+    tied = oracle.fwd(q, k, v, g, K0=K0, V0=V0, scale=0.8, readout=readout)
+    same = oracle.fwd(q, k, v, g, K0=K0, V0=V0, scale=0.8, s=-np.expm1(g), readout=readout)
+    np.testing.assert_allclose(same["o"], tied["o"], rtol=1e-13, atol=1e-15)
+
+
+def test_v2_abc_is_the_case_without_decay(oracle):
+    """Eq. (abc_recurrent) with Eq. (abc_phi): memories are plain running sums of phi_t (x) k_t and
+    phi_t (x) v_t, phi a cumulative softmax; written here with numpy prefix sums."""
+    rng = np.random.default_rng(32)
+    T, dk, dv, m = 23, 6, 5, 4
+    q = rng.standard_normal((T, dk)); k = rng.standard_normal((T, dk)) / np.sqrt(dk)
+    v = rng.standard_normal((T, dv))
+    alpha = np.exp(rng.standard_normal((T, m)))
+    phi = alpha / np.cumsum(alpha, axis=0)
+    Kt = np.cumsum(phi[:, :, None] * k[:, None, :], axis=0)       # [T, m, dk]
+    Vt = np.cumsum(phi[:, :, None] * v[:, None, :], axis=0)
+    z = np.einsum("tmd,td->tm", Kt, q)
+    o = np.einsum("tm,tmd->td", sp_softmax(z, axis=1), Vt)
+    sh = lambda x: x[None, :, None]
+    out = oracle.fwd(sh(q), sh(k), sh(v), np.zeros((1, T, 1, m)), s=sh(phi))
+    np.testing.assert_allclose(out["o"][0, :, 0], o, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(out["KT"][0, 0], Kt[-1], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("readout", ["softmax", "identity", "swish", "relu", "relu2"])
+def test_v3_variant_gradients_by_central_differences(oracle, readout):
+    rng = np.random.default_rng(33)
+    B, T, H, dk, dv, m = 1, 8, 2, 3, 4, 3
+    q, k, v, g, K0, V0 = _rand(rng, B, T, H, dk, dv, m, gate="strong", init=True)
+    s = rng.uniform(0.1, 0.9, size=g.shape)
+    dO = rng.standard_normal(v.shape)
+    dKT = rng.standard_normal(K0.shape); dVT = rng.standard_normal(V0.shape)
+    scale = 0.9
+    gr = oracle.bwd(q, k, v, g, dO, K0=K0, V0=V0, dKT=dKT, dVT=dVT, scale=scale, s=s, readout=readout)
+    args = dict(q=q, k=k, v=v, g=g, s=s, K0=K0, V0=V0)
+
+    def loss():
+        f = oracle.fwd(args["q"], args["k"], args["v"], args["g"], K0=args["K0"], V0=args["V0"], scale=scale,
+                       s=args["s"], readout=readout)
+        return float(np.sum(f["o"] * dO) + np.sum(f["KT"] * dKT) + np.sum(f["VT"] * dVT))
+
+    h = 1e-6
+    for key, gname in dict(q="dq", k="dk", v="dv", g="dg", s="ds", K0="dK0", V0="dV0").items():
+        x = args[key]
+        num = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = x[idx]
+            x[idx] = old + h; lp = loss()
+            x[idx] = old - h; lm = loss()
+            x[idx] = old
+            num[idx] = (lp - lm) / (2 * h)
+        err = np.max(np.abs(num - gr[gname])) / max(1e-12, np.max(np.abs(num)))
+        assert err < 5e-7, (readout, key, err)
+
+
+def test_v4_tied_gate_gradient_from_the_two_separate_ones(oracle):
+    """With s = 1 - exp(g) tied, the chain rule gives dg_tied = dg - exp(g) * ds."""
+    rng = np.random.default_rng(34)
+    q, k, v, g, _, _ = _rand(rng, 2, 9, 2, 4, 3, 3, gate="strong")
+    dO = rng.standard_normal(v.shape)
+    tied = oracle.bwd(q, k, v, g, dO)
+    sep = oracle.bwd(q, k, v, g, dO, s=-np.expm1(g))
+    np.testing.assert_allclose(tied["dg"], sep["dg"] - np.exp(g) * sep["ds"], rtol=1e-11, atol=1e-13)
+    for n in ("dq", "dk", "dv"):
+        np.testing.assert_allclose(tied[n], sep[n], rtol=1e-12, atol=1e-14)
 
 
 # ---------------------------------------------------------------- decode
