@@ -122,6 +122,10 @@ def main():
     ap.add_argument("--workload", default="layer_1p3b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=512)
+    ap.add_argument("--readout", default="softmax", choices=["softmax", "identity", "swish", "relu", "relu2"],
+                    help="read-out variant (gsa_fwd_ex / gsa_bwd_ex); the headline is softmax")
+    ap.add_argument("--given-intensity", action="store_true",
+                    help="write intensities as an input of their own (gsa_fwd_ex / gsa_bwd_ex)")
     ap.add_argument("--decode-one-workgroup", action="store_true",
                     help="prefill_decode: use gsa_decode_step (one workgroup per memory) instead of gsa_decode_step_ws")
     args = ap.parse_args()
@@ -145,9 +149,12 @@ def main():
     prob = gsa.make_problem(q, v, g, 1.0, cu)
     ws = gsa.alloc_workspace(prob, True, dev)
 
+    s_in = (-torch.expm1(g)).contiguous() if args.given_intensity else None
+    var = dict(s=s_in, readout=args.readout)
+
     def step():
-        o, z, _, _ = gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws)
-        return gsa.gsa_bwd(q, k, v, g, z, dO, cu_seqlens=cu, workspace=ws)
+        o, z, _, _ = gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws, **var)
+        return gsa.gsa_bwd(q, k, v, g, z, dO, cu_seqlens=cu, workspace=ws, **var)
 
     for _ in range(args.warmup):
         step()
@@ -264,7 +271,8 @@ def main():
         "config": {"workload": "%s: B=%d T=%d H=%d d_k=%d d_v=%d m=%d fwd+bwd%s" % (
             cfg.name, cfg.B, cfg.T, cfg.H, cfg.d_k, cfg.d_v, cfg.m,
             "" if cfg.cu_seqlens is None else " packed %s" % (list(cfg.cu_seqlens),)),
-            "tokens_per_step": tokens, "chunk": 64},
+            "tokens_per_step": tokens, "chunk": 64, "readout": args.readout,
+            "write_intensity": "given" if args.given_intensity else "1 - exp(g)"},
         "roofline": roofline,
         "path": {"executed_tflops": round(exec_flops / (ms_per_step * 1e-3) / 1e12, 2),
                  "frac_mfma_bf16_peak": round(exec_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),

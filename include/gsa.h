@@ -116,6 +116,42 @@ gsa_status gsa_bwd(const gsa_problem *p,
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same two calls for the variants the paper ablates (Section 4, ablation
+ * table) and the form Algorithm 1 is written in:
+ *   s       [B,T,H,m] fp32 or NULL.  The write intensity as an input of its own
+ *           (Algorithm 1 takes I beside the gates): the memories are updated as
+ *           Kt_t = Diag(exp g_t) Kt_{t-1} + s_t (x) k_t (same for Vt).  NULL means
+ *           s_t = 1 - exp(g_t), i.e. gsa_fwd/gsa_bwd.  With g = 0 and s = phi
+ *           (a cumulative softmax) this is ABC, Eqs. (abc_recurrent), (abc_phi).
+ *   readout how the slot scores z_t = scale*Kt_t q_t become the read weights:
+ *           softmax over the slots (Eq. (gsa)), or element by element the
+ *           identity, Swish z*sigmoid(z), ReLU, or ReLU squared.
+ *   gsa_bwd_ex: with s given, dg is the gradient through the decay alone and
+ *           ds [B,T,H,m] fp32 (required then) receives the gradient of s; with
+ *           s NULL, ds is not touched and dg is as in gsa_bwd.  The same s and
+ *           readout must be passed to both calls.
+ * Errors as for gsa_fwd/gsa_bwd; an unknown readout returns GSA_ERR_SHAPE.
+ * The decode step has no such variants.
+ */
+typedef enum {
+    GSA_READOUT_SOFTMAX = 0, GSA_READOUT_IDENTITY = 1, GSA_READOUT_SWISH = 2, GSA_READOUT_RELU = 3,
+    GSA_READOUT_RELU2 = 4
+} gsa_readout;
+
+gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout,
+                      const void *q, const void *k, const void *v, const float *g, const float *s,
+                      const float *K0, const float *V0,
+                      void *o, float *z_saved, float *KT, float *VT,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout,
+                      const void *q, const void *k, const void *v, const float *g, const float *s,
+                      const float *K0, const float *V0, const float *z_saved, const void *dO,
+                      const float *dKT, const float *dVT,
+                      void *dq, void *dk, void *dv, float *dg, float *ds, float *dK0, float *dV0,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * One recurrent step of Eq. (gsa) (the decode form, Figure 1) for B*H
  * independent memories, which are read, updated and written back in place.
  *   q,k [B,H,d_k]  v [B,H,d_v] (dtype)   g [B,H,m] fp32

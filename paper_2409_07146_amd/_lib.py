@@ -6,7 +6,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgsa.so")
 
 # every symbol include/gsa.h declares
-EXPORTS = ("gsa_status_string", "gsa_abi_version", "gsa_workspace_bytes", "gsa_fwd", "gsa_bwd",
+EXPORTS = ("gsa_status_string", "gsa_abi_version", "gsa_workspace_bytes", "gsa_fwd", "gsa_bwd", "gsa_fwd_ex", "gsa_bwd_ex",
            "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_decode_step_ws", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read", "gsa_profile_copy")
 
 
@@ -41,6 +41,10 @@ def load():
     lib.gsa_fwd.argtypes = [ctypes.POINTER(GsaProblem)] + [vp] * 10 + [vp, ctypes.c_size_t, vp]
     lib.gsa_bwd.restype = ctypes.c_int
     lib.gsa_bwd.argtypes = [ctypes.POINTER(GsaProblem)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_fwd_ex.restype = ctypes.c_int
+    lib.gsa_fwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_bwd_ex.restype = ctypes.c_int
+    lib.gsa_bwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32] + [vp] * 18 + [vp, ctypes.c_size_t, vp]
     lib.gsa_decode_step.restype = ctypes.c_int
     lib.gsa_decode_step.argtypes = [i32, i32, i32, i32, i32, i32, f32] + [vp] * 8
     lib.gsa_decode_workspace_bytes.restype = ctypes.c_int

@@ -76,9 +76,13 @@ def alloc_workspace(problem, want_bwd: bool, device) -> torch.Tensor:
     return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
 
 
+READOUTS = {"softmax": 0, "identity": 1, "swish": 2, "relu": 3, "relu2": 4}
+
+
 def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=True, final_state=False,
-            workspace=None):
-    """Returns (o, z_saved or None, KT or None, VT or None)."""
+            workspace=None, s=None, readout="softmax"):
+    """Returns (o, z_saved or None, KT or None, VT or None).  With s (write intensities [B,T,H,m] fp32)
+    or a readout other than "softmax" the call goes through gsa_fwd_ex."""
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     p = make_problem(q, v, g, scale, cu_seqlens)
@@ -93,6 +97,14 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
     z = torch.empty((B, T, H, m), dtype=torch.float32, device=q.device) if save_z else None
     KT = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if final_state else None
     VT = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if final_state else None
+    if s is not None or readout != "softmax":
+        _check(s, "s", torch.float32, (B, T, H, m), optional=True)
+        rc = _lib.load().gsa_fwd_ex(ctypes.byref(p), READOUTS[readout], _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
+                                    _ptr(K0), _ptr(V0), _ptr(o), _ptr(z), _ptr(KT), _ptr(VT), _ptr(workspace),
+                                    workspace.numel(), _stream(q))
+        if rc != 0:
+            raise GsaError(rc, "gsa_fwd_ex")
+        return o, z, KT, VT
     rc = _lib.load().gsa_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(K0), _ptr(V0),
                              _ptr(o), _ptr(z), _ptr(KT), _ptr(VT), _ptr(workspace), workspace.numel(),
                              _stream(q))
@@ -102,8 +114,9 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
 
 
 def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, cu_seqlens=None,
-            initial_state_grad=False, workspace=None):
-    """Returns (dq, dk, dv, dg, dK0 or None, dV0 or None)."""
+            initial_state_grad=False, workspace=None, s=None, readout="softmax"):
+    """Returns (dq, dk, dv, dg, dK0 or None, dV0 or None), plus ds as a seventh item when s is given
+    (gsa_bwd_ex; dg is then the gradient through the decay alone)."""
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     p = make_problem(q, v, g, scale, cu_seqlens)
@@ -119,6 +132,16 @@ def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale
     dg = torch.empty_like(g)
     dK0 = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if initial_state_grad else None
     dV0 = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if initial_state_grad else None
+    if s is not None or readout != "softmax":
+        _check(s, "s", torch.float32, (B, T, H, m), optional=True)
+        ds = None if s is None else torch.empty_like(g)
+        rc = _lib.load().gsa_bwd_ex(ctypes.byref(p), READOUTS[readout], _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
+                                    _ptr(K0), _ptr(V0), _ptr(z_saved), _ptr(dO), _ptr(dKT), _ptr(dVT), _ptr(dq),
+                                    _ptr(dk), _ptr(dv), _ptr(dg), _ptr(ds), _ptr(dK0), _ptr(dV0), _ptr(workspace),
+                                    workspace.numel(), _stream(q))
+        if rc != 0:
+            raise GsaError(rc, "gsa_bwd_ex")
+        return (dq, dk, dv, dg, dK0, dV0) if s is None else (dq, dk, dv, dg, dK0, dV0, ds)
     rc = _lib.load().gsa_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(K0), _ptr(V0),
                              _ptr(z_saved), _ptr(dO), _ptr(dKT), _ptr(dVT), _ptr(dq), _ptr(dk), _ptr(dv),
                              _ptr(dg), _ptr(dK0), _ptr(dV0), _ptr(workspace), workspace.numel(), _stream(q))

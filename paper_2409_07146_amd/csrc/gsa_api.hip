@@ -166,24 +166,70 @@ gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes
     return GSA_OK;
 }
 
-gsa_status gsa_fwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
-                   const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
+namespace {
+gsa_status fwd_any(const gsa_problem *p, int32_t readout, const void *q, const void *k, const void *v, const float *g,
+                   const float *s, const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
     Plan pl;
     gsa_status st = make_plan(p, &pl);
     if (st != GSA_OK) return st;
+    if (readout < GSA_READOUT_SOFTMAX || readout > GSA_READOUT_RELU2) return GSA_ERR_SHAPE;
     if (pl.tokens == 0) return GSA_OK;
     if (!q || !k || !v || !g || !o) return GSA_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) || !aligned16(K0) ||
-        !aligned16(V0) || !aligned16(z_saved) || !aligned16(KT) || !aligned16(VT))
+        !aligned16(V0) || !aligned16(z_saved) || !aligned16(KT) || !aligned16(VT) || !aligned16(s))
         return GSA_ERR_SHAPE;
     st = check_workspace(workspace, workspace_bytes, pl.total_fwd);
     if (st != GSA_OK) return st;
+    pl.s_in = s;
+    pl.readout = readout;
     const Work w = make_work(pl, workspace);
     const hipError_t e = gsa::launch_fwd(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT,
                                          static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
+
+gsa_status bwd_any(const gsa_problem *p, int32_t readout, const void *q, const void *k, const void *v, const float *g,
+                   const float *s, const float *K0, const float *V0, const float *z_saved, const void *dO,
+                   const float *dKT, const float *dVT, void *dq, void *dk, void *dv, float *dg, float *ds, float *dK0,
+                   float *dV0, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    gsa_status st = make_plan(p, &pl);
+    if (st != GSA_OK) return st;
+    if (readout < GSA_READOUT_SOFTMAX || readout > GSA_READOUT_RELU2) return GSA_ERR_SHAPE;
+    if (pl.tokens == 0) return GSA_OK;
+    if (!q || !k || !v || !g || !z_saved || !dO || !dq || !dk || !dv || !dg) return GSA_ERR_NULL;
+    if (s && !ds) return GSA_ERR_NULL;
+    const void *ptrs[] = {q, k, v, g, s, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, ds, dK0, dV0};
+    for (const void *ptr : ptrs)
+        if (!aligned16(ptr)) return GSA_ERR_SHAPE;
+    st = check_workspace(workspace, workspace_bytes, pl.total_bwd);
+    if (st != GSA_OK) return st;
+    pl.s_in = s;
+    pl.ds_out = s ? ds : nullptr;
+    pl.readout = readout;
+    const Work w = make_work(pl, workspace);
+    const hipError_t e = gsa::launch_bwd(pl, w, q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+}
+}  // namespace
+
+gsa_status gsa_fwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
+                   const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fwd_any(p, GSA_READOUT_SOFTMAX, q, k, v, g, nullptr, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes,
+                   stream);
+}
+
+gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, const void *q, const void *k, const void *v,
+                      const float *g, const float *s, const float *K0, const float *V0, void *o, float *z_saved,
+                      float *KT, float *VT, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fwd_any(p, readout, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes, stream);
 }
 
 gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
@@ -191,20 +237,17 @@ gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const voi
                    const float *dVT, void *dq, void *dk, void *dv, float *dg, float *dK0, float *dV0,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    Plan pl;
-    gsa_status st = make_plan(p, &pl);
-    if (st != GSA_OK) return st;
-    if (pl.tokens == 0) return GSA_OK;
-    if (!q || !k || !v || !g || !z_saved || !dO || !dq || !dk || !dv || !dg) return GSA_ERR_NULL;
-    const void *ptrs[] = {q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0};
-    for (const void *ptr : ptrs)
-        if (!aligned16(ptr)) return GSA_ERR_SHAPE;
-    st = check_workspace(workspace, workspace_bytes, pl.total_bwd);
-    if (st != GSA_OK) return st;
-    const Work w = make_work(pl, workspace);
-    const hipError_t e = gsa::launch_bwd(pl, w, q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0,
-                                         static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
+    return bwd_any(p, GSA_READOUT_SOFTMAX, q, k, v, g, nullptr, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, nullptr,
+                   dK0, dV0, workspace, workspace_bytes, stream);
+}
+
+gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, const void *q, const void *k, const void *v,
+                      const float *g, const float *s, const float *K0, const float *V0, const float *z_saved,
+                      const void *dO, const float *dKT, const float *dVT, void *dq, void *dk, void *dv, float *dg,
+                      float *ds, float *dK0, float *dV0, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_any(p, readout, q, k, v, g, s, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, ds, dK0, dV0, workspace,
+                   workspace_bytes, stream);
 }
 
 gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,

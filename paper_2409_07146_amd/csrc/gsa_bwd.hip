@@ -51,13 +51,15 @@ template <typename T, int M> struct DzLds {
     static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
-template <typename T, int M>
+// GEN: the general form (write intensities from `sin` when it is not NULL; read-out `readout`).
+template <typename T, int M, bool GEN>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
                                                               const T *__restrict__ v, const T *__restrict__ dO,
                                                               const float *__restrict__ g, const float *__restrict__ z,
                                                               const T *__restrict__ S, StateLayout lay,
                                                               float *__restrict__ dz, float *__restrict__ dgf,
-                                                              T *__restrict__ Wr, T *__restrict__ tAvT)
+                                                              T *__restrict__ Wr, T *__restrict__ tAvT,
+                                                              const float *__restrict__ sin, int readout)
 {
     using L = DzLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
@@ -81,10 +83,11 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
 
     float dp[MI][4];
     bool unsafe;
-    gated_scores<T, M, C>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
-                          reinterpret_cast<T *>(smem + L::oVt), L::lda, static_cast<T *>(nullptr), 0,
-                          reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v, v + tokh * d_v, (size_t)H * d_v, d_v, Vn,
-                          ci.len, tid);
+    gated_scores<T, M, C, GEN>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
+                               reinterpret_cast<T *>(smem + L::oVt), L::lda, static_cast<T *>(nullptr), 0,
+                               reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
+                               v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,
+                               (GEN && sin) ? sin + tokh * M : nullptr);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -96,20 +99,34 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
             zv[ni][j] = z[(tokh + (size_t)min(t, ci.len - 1) * H) * M + ni * 16 + r];   // clamped, never stored past len
             rmax[j] = fmaxf(rmax[j], zv[ni][j]);
         }
+    // slope[ni][j]*(dp - pdp[j]) is dz: p and <p,dp> for the softmax, f'(z) and 0 for an element-wise read-out
+    float slope[MI][4];
+    if (!GEN || readout == kReadSoftmax) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { rmax[j] = row16_max(rmax[j]); rsum[j] = 0.f; pdp[j] = 0.f; }
+        for (int j = 0; j < 4; ++j) { rmax[j] = row16_max(rmax[j]); rsum[j] = 0.f; pdp[j] = 0.f; }
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
+        for (int ni = 0; ni < MI; ++ni)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(zv[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
+            for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(zv[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
+        for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
+        for (int ni = 0; ni < MI; ++ni)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { p[ni][j] *= rsum[j]; pdp[j] += p[ni][j] * dp[ni][j]; }
+            for (int j = 0; j < 4; ++j) { p[ni][j] *= rsum[j]; pdp[j] += p[ni][j] * dp[ni][j]; slope[ni][j] = p[ni][j]; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) pdp[j] = row16_sum(pdp[j]);
+        for (int j = 0; j < 4; ++j) pdp[j] = row16_sum(pdp[j]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pdp[j] = 0.f;
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                p[ni][j] = readout_value(readout, zv[ni][j]);
+                slope[ni][j] = readout_slope(readout, zv[ni][j]);
+            }
+    }
     // dz, dgf for the intra kernel; gate-weighted transposes (scale*dz*exp G, p*exp G) for the reverse scan
     T *Wk = Wr + ch * 2 * M * C, *Wv = Wk + M * C;
 #pragma unroll
@@ -120,7 +137,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
         for (int j = 0; j < 4; ++j) {
             const int t = rowb + g4 + j;
             const bool live = t < ci.len;
-            const float dzv = live ? p[ni][j] * (dp[ni][j] - pdp[j]) : 0.f;
+            const float dzv = live ? slope[ni][j] * (dp[ni][j] - pdp[j]) : 0.f;
             const float eg = __expf(Gs[t * L::ldg + i]);
             wk[j] = from_f32<T>(scale * dzv * eg);
             wv[j] = from_f32<T>(live ? p[ni][j] * eg : 0.f);
@@ -185,9 +202,12 @@ template <typename T> struct IntraArgs {
     const T *tAvT;
     float *dg;
     T *tB, *tBT, *tA2T, *tDZe, *tSbe;
+    const float *sin;   // general form: write intensities, or NULL
+    float *ds;          // general form: their gradient (with sin)
+    int readout;
 };
 
-template <typename T, int M>
+template <typename T, int M, bool GEN>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
                                                                  IntraArgs<T> a)
 {
@@ -234,8 +254,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
     // Split over the waves in steps of 32 columns (see gated_scores): every wave covers all row
     // blocks over its share of the columns, the partial sums meet in LDS.
     f32x4 accA[CI], accX[MI];
-    GatePrep<M, NT, C> gp;
+    GatePrep<M, NT, C, GEN> gp;
     SoftmaxRows<M, C> sr;
+    const bool given = GEN && a.sin != nullptr;   // write intensities are an input of their own
     {
         typedef typename Atom<T>::Frag Frag;
         f32x4 acc[NW][NB];   // [row block][k blocks (causal) | slot blocks]
@@ -307,7 +328,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
             if (lane < 16) carry[w * M + ni * 16 + lane] = x;   // read after the barriers of the reduction
         }
         // the loads of everything phase 2 needs from global memory land during the reduction
-        gp.load(a.g + tokh * M, (size_t)H * M, ci.len, tid);
+        gp.load(a.g + tokh * M, (size_t)H * M, ci.len, tid, given ? a.sin + tokh * M : nullptr);
         sr.load(a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
         f32x4 own[NB];
         reduce_row_blocks<NW, NB, CI>(own, acc, reinterpret_cast<f32x4 *>(smem + L::oPf), lane, w);
@@ -318,7 +339,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
     }
     // gate tiles; p and dz tiles (they overwrite the reduction buffer, which every wave has left by now)
     gp.finish(Gs, Ss, L::ldg, tot, ci.len, tid);
-    sr.finish(Pf, Df, L::ldg, ci.len, tid);
+    if (!GEN || a.readout == kReadSoftmax) sr.finish(Pf, Df, L::ldg, ci.len, tid);
+    else sr.finish_elementwise(a.readout, Pf, Df, L::ldg, ci.len, tid);
     // ---- phase 2a: transposed masked A into LDS; the slot-side operand tiles of the apply kernel
 #pragma unroll
     for (int ni = 0; ni < CI; ++ni)
@@ -406,7 +428,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
                 const float fl = a.dgf[(tokh + (size_t)min(rr, ci.len - 1) * H) * M + i];
                 const float f = (rr < ci.len) ? fl : 0.f;
                 dGam[ni][j] = f - sv * ds;
-                ads[ni][j] = (1.f - sv) * ds;
+                ads[ni][j] = given ? ds : (1.f - sv) * ds;   // tied: d(1 - e^g)/dg = -e^g = -(1 - s)
             }
         }
     }
@@ -504,7 +526,15 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
         for (int pp = part + 1; pp < P; ++pp) off += tot[pp * M + i];
         for (int tt = 0; tt < TP; ++tt) {
             const int t = part * TP + tt;
-            if (t < ci.len) a.dg[(tokh + (size_t)t * H) * M + i] = Df[t * L::ldg + i] + off - Pf[t * L::ldg + i];
+            if (t < ci.len) {
+                const size_t o = (tokh + (size_t)t * H) * M + i;
+                if (given) {
+                    a.dg[o] = Df[t * L::ldg + i] + off;
+                    a.ds[o] = Pf[t * L::ldg + i];
+                } else {
+                    a.dg[o] = Df[t * L::ldg + i] + off - Pf[t * L::ldg + i];
+                }
+            }
         }
     }
 }
@@ -520,7 +550,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
 {
     const ChunkMap cm = make_chunk_map(pl, w);
     // 1. recompute the chunk-start memories (and the memories after the last token)
-    GSA_HIP_TRY(launch_gates(pl, w, g, st));
+    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, st));
     {
         const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
@@ -528,12 +558,13 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     dim3 grid(pl.chunk_slots, pl.H);
     // 2. dp, dz and the weights of the reverse scan
     {
-        auto kern = chunk_dz_kernel<T, M>;
+        auto kern = pl.general() ? chunk_dz_kernel<T, M, true> : chunk_dz_kernel<T, M, false>;
         const size_t lds = DzLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         KernelTimer kt(kSlotChunkDz, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_v, pl.scale, (const T *)v,
-                           (const T *)dO, g, z, (const T *)w.S, pl.lay, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT);
+                           (const T *)dO, g, z, (const T *)w.S, pl.lay, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT, pl.s_in,
+                           (int)pl.readout);
         GSA_HIP_TRY(hipGetLastError());
     }
     // 3. reverse scan of the memory gradient
@@ -543,7 +574,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     }
     // 4. everything chunk-local except the wide contractions
     {
-        auto kern = chunk_intra_kernel<T, M>;
+        auto kern = pl.general() ? chunk_intra_kernel<T, M, true> : chunk_intra_kernel<T, M, false>;
         const size_t lds = IntraLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         IntraArgs<T> a;
@@ -554,6 +585,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         a.tAvT = (const T *)w.tAvT;
         a.dg = dg;
         a.tB = (T *)w.tA; a.tBT = (T *)w.tBT; a.tA2T = (T *)w.tA2T; a.tDZe = (T *)w.tP; a.tSbe = (T *)w.tSbe;
+        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout;
         KernelTimer kt(kSlotChunkIntra, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, a);
         GSA_HIP_TRY(hipGetLastError());

@@ -130,11 +130,13 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // Gs and Ss too.  As [C][lda] is left holding the causally masked X Y^T rounded to T, and the tiles
 // of build_write_tiles are left in Vt, Vn (may be NULL), Rb for the caller's own use.
 // All threads of the workgroup must call it.
-template <typename T, int M, int C>
+// GEN: general form; sin = write intensities [len][M] (layout of g) or NULL for 1 - exp(g).
+template <typename T, int M, int C, bool GEN = false>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
                                              T *Vn, int ldn, float *Rb, f32x4 *Red, const T *X, const T *Y,
-                                             size_t ldx, int d, const T *St, int len, int tid)
+                                             size_t ldx, int d, const T *St, int len, int tid,
+                                             const float *sin = nullptr)
 {
     constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -176,8 +178,8 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
                 for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fx[rb], fs[ni]);
             }
         }
-        GatePrep<M, Geo<T>::NT, C> gp;
-        gp.load(g, gld, len, tid);
+        GatePrep<M, Geo<T>::NT, C, GEN> gp;
+        gp.load(g, gld, len, tid, sin);
         f32x4 own[NB];
         reduce_row_blocks<NW, NB, CI>(own, acc, Red, lane, w);
 #pragma unroll
@@ -392,6 +394,15 @@ template <int M, int C> struct SoftmaxRows {
         const float inv = (t < len) ? 1.f / sum : 0.f;
 #pragma unroll
         for (int u = 0; u < Q; ++u) Pf[t * ld + sub + 4 * u] = zv[u] * inv;
+#pragma unroll
+        for (int u = 0; u < Q; ++u) Df[t * ld + sub + 4 * u] = (t < len) ? dv[u] : 0.f;
+    }
+    // The same with an element-wise read-out p = f(z) in place of the softmax.
+    __device__ __forceinline__ void finish_elementwise(int readout, float *Pf, float *Df, int ld, int len, int tid)
+    {
+        const int t = tid >> 2, sub = tid & 3;
+#pragma unroll
+        for (int u = 0; u < Q; ++u) Pf[t * ld + sub + 4 * u] = (t < len) ? readout_value(readout, zv[u]) : 0.f;
 #pragma unroll
         for (int u = 0; u < Q; ++u) Df[t * ld + sub + 4 * u] = (t < len) ? dv[u] : 0.f;
     }

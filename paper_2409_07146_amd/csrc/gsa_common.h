@@ -320,18 +320,27 @@ __device__ __forceinline__ void seq_lookup(const ChunkMap &cm, int s, int &chunk
 // Rows t >= len are padded with g = 0.  Needs blockDim.x = NT threads, NT % M == 0,
 // C % (NT/M) == 0, and `tot` scratch of NT floats.  Ends with a __syncthreads().
 // ----------------------------------------------------------------------------
-template <int M, int NT, int C> struct GatePrep {
+// GEN: the general form, in which the write intensity may come from an array of its own
+// (sin: [len][M] fp32, same layout as g; NULL = 1 - exp(g) as above).
+template <int M, int NT, int C, bool GEN = false> struct GatePrep {
     static constexpr int P = NT / M;     // token partitions
     static constexpr int TP = C / P;     // tokens per partition
     static_assert(NT % M == 0 && C % P == 0, "gate_prep partitioning");
     float gv[TP];
+    float sv[GEN ? TP : 1];
+    bool given = false;
     // Issues the loads (rows clamped into the chunk).  May be called well before finish() so that
     // other work hides the latency.
-    __device__ __forceinline__ void load(const float *g, size_t gld, int len, int tid)
+    __device__ __forceinline__ void load(const float *g, size_t gld, int len, int tid, const float *sin = nullptr)
     {
         const int i = tid % M, part = tid / M;
 #pragma unroll
         for (int tt = 0; tt < TP; ++tt) gv[tt] = g[(size_t)min(part * TP + tt, len - 1) * gld + i];
+        if (GEN && sin) {   // uniform over the grid
+            given = true;
+#pragma unroll
+            for (int tt = 0; tt < (GEN ? TP : 1); ++tt) sv[tt] = sin[(size_t)min(part * TP + tt, len - 1) * gld + i];
+        }
     }
     // Fills Gs, Ss.  Contains barriers (all threads must call it) and ends with one.
     __device__ __forceinline__ void finish(float *Gs, float *Ss, int ldg, float *tot, int len, int tid) const
@@ -344,7 +353,9 @@ template <int M, int NT, int C> struct GatePrep {
             const float x = (t < len) ? fmaxf(gv[tt], kGateFloor) : 0.f;
             run += x;
             Gs[t * ldg + i] = run;
-            Ss[t * ldg + i] = (t < len) ? -expm1f(x) : 0.f;
+            float sx = -expm1f(x);
+            if (GEN && given) sx = sv[GEN ? tt : 0];
+            Ss[t * ldg + i] = (t < len) ? sx : 0.f;
         }
         tot[part * M + i] = run;
         __syncthreads();
@@ -358,13 +369,32 @@ template <int M, int NT, int C> struct GatePrep {
     }
 };
 
-template <int M, int NT, int C>
+template <int M, int NT, int C, bool GEN = false>
 __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *tot, const float *g, size_t gld,
-                                          int len, int tid)
+                                          int len, int tid, const float *sin = nullptr)
 {
-    GatePrep<M, NT, C> gp;
-    gp.load(g, gld, len, tid);
+    GatePrep<M, NT, C, GEN> gp;
+    gp.load(g, gld, len, tid, sin);
     gp.finish(Gs, Ss, ldg, tot, len, tid);
+}
+
+// ----------------------------------------------------------------------------
+// Read-outs: how the slot scores z become the read weights p.  Softmax over the slots is the
+// method's own (Eq. (gsa)); the element-wise ones are the ablations of Section 4 (no softmax,
+// Swish, ReLU, ReLU squared).  Values match gsa_readout in the C header.
+// ----------------------------------------------------------------------------
+enum Readout { kReadSoftmax = 0, kReadIdentity = 1, kReadSwish = 2, kReadRelu = 3, kReadRelu2 = 4 };
+
+__device__ __forceinline__ float readout_value(int ro, float z)
+{
+    const float sg = 1.f / (1.f + __expf(-z)), zp = fmaxf(z, 0.f);
+    return ro == kReadIdentity ? z : ro == kReadSwish ? z * sg : ro == kReadRelu ? zp : zp * zp;
+}
+__device__ __forceinline__ float readout_slope(int ro, float z)
+{
+    const float sg = 1.f / (1.f + __expf(-z));
+    return ro == kReadIdentity ? 1.f : ro == kReadSwish ? sg + z * sg * (1.f - sg) : ro == kReadRelu ? (z > 0.f ? 1.f : 0.f)
+                                                                                               : 2.f * fmaxf(z, 0.f);
 }
 
 // Fragment straight from global memory: 8 consecutive elements of one row.  Loads in this

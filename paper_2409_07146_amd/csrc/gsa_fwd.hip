@@ -100,13 +100,15 @@ template <typename T, int M> struct ChunkFwdLds {
     static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
-template <typename T, int M>
+// GEN: the general form (write intensities from `sin` when it is not NULL; read-out `readout`).
+template <typename T, int M, bool GEN>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const float *__restrict__ g,
                                                                const T *__restrict__ S, StateLayout lay,
                                                                float *__restrict__ z_saved, T *__restrict__ tA,
-                                                               T *__restrict__ tP)
+                                                               T *__restrict__ tP, const float *__restrict__ sin,
+                                                               int readout)
 {
     using L = ChunkFwdLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
@@ -134,9 +136,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     bool unsafe;
     T *Vt = reinterpret_cast<T *>(smem + L::oVt), *Vn = reinterpret_cast<T *>(smem + L::oVn);
     float *Rb = reinterpret_cast<float *>(smem + L::oRb);
-    gated_scores<T, M, C>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Vn,
-                          L::ldp, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k, (size_t)H * d_k, d_k, Kn,
-                          ci.len, tid);
+    gated_scores<T, M, C, GEN>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Vn,
+                               L::ldp, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
+                               (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
@@ -153,18 +155,25 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
             if (z_saved && t < ci.len) z_saved[(tokh + (size_t)t * H) * M + i] = z;
         }
     }
+    if (!GEN || readout == kReadSoftmax) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { rmax[j] = row16_max(rmax[j]); rsum[j] = 0.f; }
+        for (int j = 0; j < 4; ++j) { rmax[j] = row16_max(rmax[j]); rsum[j] = 0.f; }
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
+        for (int ni = 0; ni < MI; ++ni)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(p[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
+            for (int j = 0; j < 4; ++j) { p[ni][j] = __expf(p[ni][j] - rmax[j]); rsum[j] += p[ni][j]; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
+        for (int j = 0; j < 4; ++j) rsum[j] = 1.f / row16_sum(rsum[j]);
 #pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
+        for (int ni = 0; ni < MI; ++ni)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) p[ni][j] *= rsum[j];
+            for (int j = 0; j < 4; ++j) p[ni][j] *= rsum[j];
+    } else {   // element-wise read-out (ablations of Section 4)
+#pragma unroll
+        for (int ni = 0; ni < MI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) p[ni][j] = readout_value(readout, p[ni][j]);
+    }
     if (M < KM) {   // zero the padded slot columns once
 #pragma unroll
         for (int j = 0; j < 4; ++j) Ps[(rowb + g4 + j) * L::ldp + M + r] = from_f32<T>(0.f);
@@ -247,19 +256,20 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
                                 float *VT, hipStream_t st)
 {
     const ChunkMap cm = make_chunk_map(pl, w);
-    GSA_HIP_TRY(launch_gates(pl, w, g, st));
+    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, st));
     {
         const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     {
-        auto kern = chunk_fwd_kernel<T, M>;
+        auto kern = pl.general() ? chunk_fwd_kernel<T, M, true> : chunk_fwd_kernel<T, M, false>;
         const size_t lds = ChunkFwdLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         dim3 grid(pl.chunk_slots, pl.H);
         KernelTimer kt(kSlotChunkFwd, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.scale, (const T *)q,
-                           (const T *)k, g, (const T *)w.S, pl.lay, z_saved, (T *)w.tA, (T *)w.tP);
+                           (const T *)k, g, (const T *)w.S, pl.lay, z_saved, (T *)w.tA, (T *)w.tP, pl.s_in,
+                           (int)pl.readout);
         GSA_HIP_TRY(hipGetLastError());
     }
     const ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v};

@@ -22,6 +22,11 @@ struct Plan {
     size_t off_SF, off_Wr, off_E, off_dz, off_dgf, off_tB, off_tBT, off_tA2T, off_tAvT, off_tSbe, total_bwd;
     // layout of every memory snapshot record (elements); see gsa_layout.h
     StateLayout lay;
+    // variants (gsa_fwd_ex / gsa_bwd_ex): write intensity as an input of its own, element-wise read-outs
+    const float *s_in = nullptr;   // [B,T,H,m] device, or NULL for s = 1 - exp(g)
+    float *ds_out = nullptr;       // backward: gradient of s_in
+    int32_t readout = 0;           // Readout
+    bool general() const { return s_in != nullptr || readout != 0; }
 };
 
 // Workspace views handed to the launchers.
@@ -65,7 +70,7 @@ private:
 hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st);
 
 // Forward-scan weights and chunk decays from the log gates (chunk-parallel).
-hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, hipStream_t st);
+hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, const float *sin, hipStream_t st);
 
 // One scan over the chunks of every sequence.  Forward: x = (k, v), init = (K0, V0), snapshots go
 // to Work::S, weights come from Work::Wf.  Reverse: x = (q, dO), init = (dKT, dVT), snapshots go

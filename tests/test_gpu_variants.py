@@ -1,0 +1,109 @@
+"""GPU parity of gsa_fwd_ex / gsa_bwd_ex against the fp64 oracle: write intensity as an input of its
+own (Algorithm 1's I; ABC when g = 0) and the read-outs of the paper's ablation table."""
+import numpy as np
+import pytest
+import torch
+
+from tests.util import check, to_np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+READOUTS = ["softmax", "identity", "swish", "relu", "relu2"]
+
+
+def _inputs(B, T, H, d_k, d_v, m, dtype, seed, given, abc=False):
+    from paper_2409_07146_amd import synth
+    cfg = synth.GsaConfig("variant", B=B, T=T, H=H, d_k=d_k, d_v=d_v, m=m, dtype=dtype, seed=seed, init_state_std=0.5)
+    x = synth.make_inputs(cfg)
+    gen = torch.Generator().manual_seed(seed + 1000)
+    s = None
+    if abc:       # Eq. (abc_phi): a cumulative softmax over the tokens, no decay
+        a = torch.exp(torch.randn(B, T, H, m, generator=gen))
+        s = (a / torch.cumsum(a, dim=1)).float()
+        x["g"] = torch.zeros_like(x["g"])
+    elif given:   # independent of the gate, with the tied value 1 - exp(g) as its mean
+        s = (2.0 * torch.rand(B, T, H, m, generator=gen) * -torch.expm1(x["g"])).float()
+    x["s"] = s
+    gs = torch.Generator().manual_seed(seed + 2000)
+    x["dKT"] = torch.randn(x["K0"].shape, generator=gs) * 0.5
+    x["dVT"] = torch.randn(x["V0"].shape, generator=gs) * 0.5
+    return cfg, x
+
+
+def _run_and_compare(oracle, cfg, x, readout, scale=1.0):
+    import paper_2409_07146_amd as gsa
+    dev = torch.device(DEV)
+    put = lambda t: None if t is None else t.to(dev)
+    d = {n: put(x[n]) for n in ("q", "k", "v", "g", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    o, z, KT, VT = gsa.gsa_fwd(d["q"], d["k"], d["v"], d["g"], K0=d["K0"], V0=d["V0"], scale=scale,
+                               final_state=True, s=d["s"], readout=readout)
+    res = gsa.gsa_bwd(d["q"], d["k"], d["v"], d["g"], z, d["dO"], K0=d["K0"], V0=d["V0"], dKT=d["dKT"],
+                      dVT=d["dVT"], scale=scale, initial_state_grad=True, s=d["s"], readout=readout)
+    torch.cuda.synchronize()
+    n64 = lambda t: None if t is None else to_np64(t)
+    a = {n: n64(x[n]) for n in ("q", "k", "v", "g", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    f = oracle.fwd(a["q"], a["k"], a["v"], a["g"], K0=a["K0"], V0=a["V0"], scale=scale, s=a["s"], readout=readout)
+    check("o", to_np64(o), f["o"], cfg.dtype)
+    check("z", to_np64(z), f["z"], cfg.dtype)
+    check("KT", to_np64(KT), f["KT"], cfg.dtype)
+    check("VT", to_np64(VT), f["VT"], cfg.dtype)
+    # ReLU's slope jumps at z = 0: both sides take that decision from the same scores (the kernel's)
+    zdec = to_np64(z) if readout == "relu" else None
+    r = oracle.bwd(a["q"], a["k"], a["v"], a["g"], a["dO"], K0=a["K0"], V0=a["V0"], dKT=a["dKT"], dVT=a["dVT"],
+                   scale=scale, s=a["s"], readout=readout, z_decide=zdec)
+    names = ["dq", "dk", "dv", "dg", "dK0", "dV0"] + (["ds"] if x["s"] is not None else [])
+    for n, t in zip(names, res):
+        check(n, to_np64(t), r[n], cfg.dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("readout", READOUTS)
+@pytest.mark.parametrize("given", [False, True])
+def test_variants_small(oracle, readout, given, dtype):
+    if readout == "softmax" and not given:
+        pytest.skip("that is gsa_fwd / gsa_bwd")
+    cfg, x = _inputs(2, 150, 2, 128, 64, 32, dtype, seed=61, given=given)
+    _run_and_compare(oracle, cfg, x, readout, scale=0.9)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m", [16, 64, 128])
+def test_abc(oracle, m, dtype):
+    """No decay, write intensities a cumulative softmax: Eqs. (abc_recurrent), (abc_phi)."""
+    cfg, x = _inputs(1, 200, 2, 64, 128, m, dtype, seed=62, given=True, abc=True)
+    _run_and_compare(oracle, cfg, x, "softmax")
+
+
+@pytest.mark.parametrize("readout", ["softmax", "swish"])
+def test_variants_at_the_layer_shape(oracle, readout):
+    """d = 512, m = 64, bf16, ragged length (several chunks and a tail)."""
+    cfg, x = _inputs(1, 333, 2, 512, 512, 64, "bf16", seed=63, given=True)
+    _run_and_compare(oracle, cfg, x, readout)
+
+
+def test_given_tied_intensity_reproduces_the_plain_calls():
+    """s = 1 - exp(g) handed over explicitly: same outputs as gsa_fwd/gsa_bwd, and the two gate gradients
+    combine to the tied one by the chain rule."""
+    import paper_2409_07146_amd as gsa
+    cfg, x = _inputs(2, 130, 2, 128, 128, 64, "f32", seed=64, given=False)
+    dev = torch.device(DEV)
+    q, k, v, g, dO = (x[n].to(dev) for n in ("q", "k", "v", "g", "dO"))
+    s = -torch.expm1(g)
+    o0, z0, _, _ = gsa.gsa_fwd(q, k, v, g)
+    o1, z1, _, _ = gsa.gsa_fwd(q, k, v, g, s=s)
+    torch.testing.assert_close(o1, o0, rtol=2e-5, atol=2e-6)
+    b0 = gsa.gsa_bwd(q, k, v, g, z0, dO)
+    b1 = gsa.gsa_bwd(q, k, v, g, z1, dO, s=s)
+    for i in range(3):
+        torch.testing.assert_close(b1[i], b0[i], rtol=1e-4, atol=1e-5)
+    torch.testing.assert_close(b1[3] - torch.exp(g) * b1[6], b0[3], rtol=1e-3, atol=2e-4)
+
+
+def test_bad_readout_is_rejected():
+    import ctypes
+    from paper_2409_07146_amd import _lib
+    lib = _lib.load()
+    p = _lib.GsaProblem(B=1, T=64, H=1, d_k=64, d_v=64, m=16, dtype=1, scale=1.0, cu_seqlens=None, n_seqs=0)
+    null = ctypes.c_void_p(None)
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 7, *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_bwd_ex(ctypes.byref(p), -1, *([null] * 18), null, 0, null) == 2
