@@ -233,16 +233,21 @@ def main():
     od = torch.empty_like(dv_[0])
     state_bytes = 2 * 4 * dd["B"] * dd["H"] * dd["m"] * (dd["d_k"] + dd["d_v"])
     dec = {}
-    for label, sets in (("one_state_set", 1), ("rotating_8_state_sets", nsets)):
+    dws = gsa.alloc_decode_workspace(dd["B"], dd["H"], dd["d_k"], dd["d_v"], dd["m"], dev)
+    for label, sets, w in (("one_state_set", 1, None), ("rotating_8_state_sets", nsets, None),
+                           ("rotating_8_state_sets_with_workspace", nsets, dws)):
         for i in range(20):
-            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od)
+            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od,
+                                workspace=w)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.decode_steps):
-            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od)
+            gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od,
+                                workspace=w)
         torch.cuda.synchronize()
         us = (time.perf_counter() - t0) / args.decode_steps * 1e6
-        dec[label] = {"us_per_step": round(us, 2), "GB_per_s": round(state_bytes / us / 1e3, 1),
+        dec[label] = {"entry": "gsa_decode_step" if w is None else "gsa_decode_step_ws", "us_per_step": round(us, 2),
+                      "GB_per_s": round(state_bytes / us / 1e3, 1),
                       "frac_hbm_peak": round(state_bytes / us / 1e3 / HBM_PEAK_GBS, 4)}
 
     cpu = None

@@ -165,16 +165,17 @@ gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32
                            float *K_state, float *V_state, void *o, void *stream);
 
 /*
- * The same step (Eq. (gsa), decode form) for callers with few memories in flight
- * (small batches, the token-by-token generation loop of Figure 4c): with B*H up
- * to 64 each memory pair is spread over m/4 workgroups, whose partial read-outs
- * (each with its own softmax maximum and sum) pass through the workspace and
- * are merged by a second kernel in a fixed order; above that the call does what
- * gsa_decode_step does.  Results agree with gsa_decode_step up to fp32 rounding
- * order and are reproducible run to run.
+ * The same step (Eq. (gsa), decode form) with each memory pair spread over several
+ * workgroups, each covering some of the slots; their partial read-outs (each with
+ * its own softmax maximum and sum) pass through the workspace and are merged by a
+ * second kernel in a fixed order.  With few memories in flight (small batches, the
+ * token-by-token generation loop of Figure 4c) this is what fills the chip; with
+ * many it still overlaps the loads and stores of workgroups that share a compute
+ * unit.  Results agree with gsa_decode_step up to fp32 rounding order and are
+ * reproducible run to run.
  *   workspace: device memory, 256-byte aligned, at least
- *   gsa_decode_workspace_bytes(...) bytes (0 when the split form is not used);
- *   contents meaningless to the caller; calls sharing a workspace must not overlap.
+ *   gsa_decode_workspace_bytes(...) bytes; contents meaningless to the caller;
+ *   calls sharing a workspace must not overlap.
  * Errors as for gsa_decode_step, plus GSA_ERR_WORKSPACE.
  */
 gsa_status gsa_decode_workspace_bytes(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, size_t *bytes);

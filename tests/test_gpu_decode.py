@@ -44,10 +44,11 @@ def test_decode_small_shapes(oracle, B, H, d_k, d_v, m, dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,H,d_k,d_v,m", [(2, 2, 64, 64, 16), (3, 1, 128, 192, 32), (2, 3, 640, 576, 64),
                                            (1, 2, 1024, 64, 64), (1, 1, 256, 256, 128), (1, 4, 512, 512, 64),
-                                           (32, 4, 128, 64, 32), (33, 4, 64, 64, 16)])
+                                           (32, 4, 128, 64, 32), (33, 4, 64, 64, 16), (17, 4, 192, 128, 64),
+                                           (9, 8, 64, 1024, 128), (24, 3, 128, 64, 32)])
 def test_decode_with_workspace(oracle, B, H, d_k, d_v, m, dtype):
-    """gsa_decode_step_ws: memories spread over several workgroups up to 64 pairs (the last two cases are
-    past that and take the one-workgroup form)."""
+    """gsa_decode_step_ws: one slot row per wave up to 64 pairs, four workgroups of eight waves per pair
+    past that (the last two cases; m = 16 always takes the first form)."""
     _run(oracle, B, H, d_k, d_v, m, steps=5, dtype=dtype, scale=0.9, split=True)
 
 
