@@ -346,8 +346,8 @@ __device__ __forceinline__ f32x4 pair_weights_exact(const TW *Wf, int ldw, const
 }
 
 // Stores a C x ncols tile held in LDS (Os, row stride ldo) to global rows of `ld` elements,
-// 8 elements per thread, rows >= len skipped.
-template <typename T>
+// 8 elements per thread, rows >= len skipped.  NTS: with the non-temporal hint (final outputs).
+template <typename T, bool NTS = false>
 __device__ __forceinline__ void store_tile(T *dst, size_t ld, const T *Os, int ldo, int rows, int ncols, int len,
                                            int tid, int nthreads)
 {
@@ -357,8 +357,13 @@ __device__ __forceinline__ void store_tile(T *dst, size_t ld, const T *Os, int l
         if (t >= len) continue;
         const T *s = Os + t * ldo + c;
         T *d = dst + (size_t)t * ld + c;
-        *reinterpret_cast<f32x4 *>(d) = *reinterpret_cast<const f32x4 *>(s);
-        if (sizeof(T) == 4) *reinterpret_cast<f32x4 *>(d + 4) = *reinterpret_cast<const f32x4 *>(s + 4);
+        if (NTS) {
+            __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(s), reinterpret_cast<f32x4 *>(d));
+            if (sizeof(T) == 4) __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(s + 4), reinterpret_cast<f32x4 *>(d + 4));
+        } else {
+            *reinterpret_cast<f32x4 *>(d) = *reinterpret_cast<const f32x4 *>(s);
+            if (sizeof(T) == 4) *reinterpret_cast<f32x4 *>(d + 4) = *reinterpret_cast<const f32x4 *>(s + 4);
+        }
     }
 }
 

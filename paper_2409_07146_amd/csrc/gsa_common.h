@@ -44,6 +44,7 @@ template <> struct Atom<bf16_t> {
     typedef bf16x8 Frag;
     static constexpr int kPad = 8;  // elements of padding that keep rows 16-byte aligned
     __device__ static __forceinline__ Frag load(const bf16_t *p) { return *reinterpret_cast<const Frag *>(p); }
+    __device__ static __forceinline__ Frag load_nt(const bf16_t *p) { return __builtin_nontemporal_load(reinterpret_cast<const Frag *>(p)); }
     __device__ static __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (bf16_t)0.f; return f; }
     __device__ static __forceinline__ void mma(f32x4 &c, const Frag &a, const Frag &b) {
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -63,6 +64,14 @@ template <> struct Atom<float> {
     __device__ static __forceinline__ Frag load(const float *p) {
         const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
         const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+        Frag f;
+        f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
+        f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+        return f;
+    }
+    __device__ static __forceinline__ Frag load_nt(const float *p) {
+        const f32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        const f32x4 hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p + 4));
         Frag f;
         f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
         f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
@@ -155,12 +164,20 @@ template <> __device__ __forceinline__ void store8<float>(float *dst, const floa
     *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{v[4], v[5], v[6], v[7]};
 }
 
+// Non-temporal forms (load_nt / store_nt below and on the atom): for data a kernel touches once and
+// nobody reads again soon.  Such traffic then streams through the caches instead of displacing lines
+// that the co-resident workgroups or the next kernel still want.  Which accesses carry the hint was
+// decided by measurement, access by access: the decode memories, the apply kernel's wide operands and
+// outputs and the scans' token tiles gain; the chunk kernels' operands and the scans' snapshot stores
+// (read back by the next kernel) lose.
 // Eight elements held as loaded (no conversion): the unit of register prefetching.
 template <typename T> struct Raw8;
 template <> struct Raw8<bf16_t> {
     bf16x8 v;
     __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const bf16x8 *>(p); }
     __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<bf16x8 *>(p) = v; }
+    __device__ __forceinline__ void load_nt(const bf16_t *p) { v = __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(p)); }
+    __device__ __forceinline__ void store_nt(bf16_t *p) const { __builtin_nontemporal_store(v, reinterpret_cast<bf16x8 *>(p)); }
     __device__ __forceinline__ void zero() {
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.f;
@@ -182,6 +199,14 @@ template <> struct Raw8<float> {
     __device__ __forceinline__ void store(float *p) const {
         *reinterpret_cast<f32x4 *>(p) = lo;
         *reinterpret_cast<f32x4 *>(p + 4) = hi;
+    }
+    __device__ __forceinline__ void load_nt(const float *p) {
+        lo = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p + 4));
+    }
+    __device__ __forceinline__ void store_nt(float *p) const {
+        __builtin_nontemporal_store(lo, reinterpret_cast<f32x4 *>(p));
+        __builtin_nontemporal_store(hi, reinterpret_cast<f32x4 *>(p + 4));
     }
     __device__ __forceinline__ void zero() { lo = f32x4{0.f, 0.f, 0.f, 0.f}; hi = lo; }
     __device__ __forceinline__ float get(int e) const { return e < 4 ? lo[e] : hi[e - 4]; }
@@ -434,6 +459,7 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
     // Only issues the loads: the masking of missing rows is left to store_transposed, so that nothing
     // here waits for the data (a select right after the load would stall the wave for the full memory
     // latency before it could issue anything else).
+    template <bool NTL = false>
     __device__ __forceinline__ void load(const T *src, size_t gld, int len, int ncols, int tid)
     {
 #pragma unroll
@@ -446,14 +472,15 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             const bool ok = in && cg * 8 < ncols;
             cg = ok ? cg : 0;
             const int r0 = min(2 * rp, len - 1), r1 = min(2 * rp + 1, len - 1);
-            a[u].load(src + (size_t)r0 * gld + cg * 8);
-            b[u].load(src + (size_t)r1 * gld + cg * 8);
+            if (NTL) { a[u].load_nt(src + (size_t)r0 * gld + cg * 8); b[u].load_nt(src + (size_t)r1 * gld + cg * 8); }
+            else { a[u].load(src + (size_t)r0 * gld + cg * 8); b[u].load(src + (size_t)r1 * gld + cg * 8); }
             la[u] = ok && 2 * rp < len;
             lb[u] = ok && 2 * rp + 1 < len;
         }
     }
     // The same for a column slice of one part of a memory snapshot (C slots, all present; the part is
     // tiled by kSnapTile columns): col0 = first column of the slice.
+    template <bool NTL = false>
     __device__ __forceinline__ void load_snapshot(const T *part, int col0, int ncols, int tid)
     {
 #pragma unroll
@@ -466,8 +493,8 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             const bool ok = in && cg * 8 < ncols;
             cg = ok ? cg : 0;
             const T *p = part + snap_col<C>(col0 + cg * 8);
-            a[u].load(p + (2 * rp) * kSnapTile);
-            b[u].load(p + (2 * rp + 1) * kSnapTile);
+            if (NTL) { a[u].load_nt(p + (2 * rp) * kSnapTile); b[u].load_nt(p + (2 * rp + 1) * kSnapTile); }
+            else { a[u].load(p + (2 * rp) * kSnapTile); b[u].load(p + (2 * rp + 1) * kSnapTile); }
             la[u] = lb[u] = ok;
         }
     }

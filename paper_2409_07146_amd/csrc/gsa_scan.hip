@@ -157,7 +157,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
         }
         const int len = min(C, ntok - n * C);
         const T *Xg = src + ((size_t)(tok0 + n * C) * H + h) * dsrc + c0;
-        st.xt.load(Xg, (size_t)H * dsrc, len, NS, tid);
+        st.xt.template load<true>(Xg, (size_t)H * dsrc, len, NS, tid);
     };
     // accumulator -> LDS tile [m][cols] -> whole rows of the record's key or value part
     auto snapshot_to_lds = [&](int b) {
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
 #pragma unroll
         for (int u = 0; u < SV; ++u) {
             const int idx = tid + NT * u;
-            if (SVEC % NT == 0 || idx < SVEC) x[u].store(dst + (size_t)idx * 8);
+            if (SVEC % NT == 0 || idx < SVEC) x[u].store(dst + (size_t)idx * 8);   // read back by the next kernel: cached
         }
     };
     // staged registers -> LDS set b (W as is, X transposed)
