@@ -51,10 +51,25 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     size_t off = 0;
     pl->off_table = off;  off += align_up(p->cu_seqlens ? (size_t)slots * 4 * sizeof(int32_t) : 0);
     pl->off_seqtab = off; off += align_up(p->cu_seqlens ? (size_t)p->n_seqs * 4 * sizeof(int32_t) : 0);
+    pl->off_segbase = off; off += align_up(p->cu_seqlens ? ((size_t)p->n_seqs + 1) * sizeof(int32_t) : 0);
     pl->off_Wf = off;     off += align_up(ch * M * C * esz);
     pl->off_dec = off;    off += align_up(ch * M * sizeof(float));
     pl->off_tA = off;     off += align_up(ch * C * C * esz);
     pl->off_tP = off;     off += align_up(ch * C * KM * esz);
+    // Long sequences: the scans cut them into segments (gsa_scan.hip).  The host knows the longest a
+    // sequence can be (T tokens, also in packed form) and provides for that many segments per sequence;
+    // this is only done while the sequences alone do not fill the chip.
+    {
+        const int64_t max_nch = ((int64_t)p->T + pl->chunk - 1) / pl->chunk;
+        const int64_t nseg = (max_nch + gsa::kSegChunks - 1) / gsa::kSegChunks;
+        const int64_t wgs = (int64_t)pl->n_seqs * p->H * ((dk + dv) / 64) * nseg;
+        const bool on = max_nch > gsa::kSegChunks + gsa::kSegChunks / 2 && wgs <= 8192;
+        pl->seg_chunks = gsa::kSegChunks;
+        pl->max_seg = on ? (int32_t)nseg : 1;
+    }
+    const size_t nsum = pl->max_seg > 1 ? (size_t)pl->n_seqs * pl->max_seg * p->H : 0;
+    pl->off_sumY = off;   off += align_up(nsum * M * D * sizeof(float));
+    pl->off_sumD = off;   off += align_up(nsum * (D / 64) * M * sizeof(float));
     pl->off_S = off;
     pl->total_fwd = off + align_up(ch * M * D * esz);
     off += align_up(ch * M * D * esz);
@@ -77,8 +92,11 @@ Work make_work(const Plan &pl, void *ws)
     Work w;
     w.table = reinterpret_cast<int32_t *>(b + pl.off_table);
     w.seqtab = reinterpret_cast<int32_t *>(b + pl.off_seqtab);
+    w.segbase = reinterpret_cast<int32_t *>(b + pl.off_segbase);
     w.Wf = b + pl.off_Wf;
     w.dec = reinterpret_cast<float *>(b + pl.off_dec);
+    w.sumY = reinterpret_cast<float *>(b + pl.off_sumY);
+    w.sumD = reinterpret_cast<float *>(b + pl.off_sumD);
     w.S = b + pl.off_S;
     w.tA = b + pl.off_tA;
     w.tP = b + pl.off_tP;

@@ -275,6 +275,7 @@ __device__ __forceinline__ void stage_cols(T *dst, int ld, const Tin *src, size_
 struct ChunkMap {
     const int32_t *table;   // packed: [4 * n_chunk_slots] = {seq, tok0, len, index in seq}; batch: NULL
     const int32_t *seq_tab; // packed: [4 * n_seqs] = {first chunk id, number of chunks, first token, tokens}
+    const int32_t *seg_base; // packed: [n_seqs + 1] running count of scan segments before each sequence
     int32_t T;              // batch: tokens per sequence
     int32_t chunk;          // tokens per chunk (C in Appendix A)
     int32_t chunks_per_seq; // batch: ceil(T / chunk)

@@ -31,11 +31,12 @@ namespace gsa {
 // Packed form: build the chunk table from the device-side sequence offsets.
 // ---------------------------------------------------------------------------------------
 __global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T, int kChunk, int chunk_slots,
-                               int32_t *__restrict__ table, int32_t *__restrict__ seqtab)
+                               int seg_chunks, int32_t *__restrict__ table, int32_t *__restrict__ seqtab,
+                               int32_t *__restrict__ segbase)
 {
     __shared__ int total;
     if (threadIdx.x == 0) {
-        int c0 = 0, prev_end = 0;
+        int c0 = 0, prev_end = 0, nsegs = 0;
         for (int s = 0; s < n_seqs; ++s) {
             int b = min(max(cu[s], prev_end), T);
             int e = min(max(cu[s + 1], b), T);
@@ -44,22 +45,29 @@ __global__ void prepare_kernel(const int32_t *__restrict__ cu, int n_seqs, int T
             seqtab[4 * s + 1] = nch;
             seqtab[4 * s + 2] = b;
             seqtab[4 * s + 3] = e - b;
+            segbase[s] = nsegs;                                    // scan segments (gsa_scan.hip); an empty
+            nsegs += max(1, (nch + seg_chunks - 1) / seg_chunks);  // sequence still has one
             c0 += nch;
             prev_end = e;
         }
+        segbase[n_seqs] = nsegs;
         total = c0;
     }
     __syncthreads();
-    for (int s = threadIdx.x; s < n_seqs; s += blockDim.x) {
-        const int c0 = seqtab[4 * s + 0], nch = seqtab[4 * s + 1], b = seqtab[4 * s + 2], n = seqtab[4 * s + 3];
-        for (int j = 0; j < nch; ++j) {
-            const int c = c0 + j;
-            if (c >= chunk_slots) break;
-            table[4 * c + 0] = s;
-            table[4 * c + 1] = b + j * kChunk;
-            table[4 * c + 2] = min(kChunk, n - j * kChunk);
-            table[4 * c + 3] = j;
+    // one chunk slot per thread and pass: its sequence is the last one whose first chunk is <= the slot
+    // (a sequence without tokens shares its first-chunk index with its successor, so it is never the last)
+    const int used = min(total, chunk_slots);
+    for (int c = threadIdx.x; c < used; c += blockDim.x) {
+        int lo = 0, hi = n_seqs - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (seqtab[4 * mid + 0] <= c) lo = mid; else hi = mid - 1;
         }
+        const int j = c - seqtab[4 * lo + 0];
+        table[4 * c + 0] = lo;
+        table[4 * c + 1] = seqtab[4 * lo + 2] + j * kChunk;
+        table[4 * c + 2] = min(kChunk, seqtab[4 * lo + 3] - j * kChunk);
+        table[4 * c + 3] = j;
     }
     for (int c = total + threadIdx.x; c < chunk_slots; c += blockDim.x) {
         table[4 * c + 0] = 0; table[4 * c + 1] = 0; table[4 * c + 2] = 0; table[4 * c + 3] = 0;
@@ -71,7 +79,7 @@ hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st)
     if (!pl.cu_seqlens) return hipSuccess;
     KernelTimer kt(kSlotPrepare, st);
     hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(256), 0, st, pl.cu_seqlens, pl.n_seqs, pl.T, pl.chunk,
-                       pl.chunk_slots, w.table, w.seqtab);
+                       pl.chunk_slots, pl.seg_chunks, w.table, w.seqtab, w.segbase);
     return hipGetLastError();
 }
 

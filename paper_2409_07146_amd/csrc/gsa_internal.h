@@ -17,8 +17,9 @@ struct Plan {
     int64_t tokens;             // B*T
     int32_t chunk;              // tokens per chunk for this dtype
     int32_t chunk_slots;        // upper bound on chunks (exact in batch form)
+    int32_t seg_chunks, max_seg;   // long sequences: chunks per scan segment, segments provided per sequence (1 = off)
     // workspace offsets in bytes (256-byte aligned); 0-sized parts share an offset
-    size_t off_table, off_seqtab, off_Wf, off_dec, off_S, off_tA, off_tP, total_fwd;
+    size_t off_table, off_seqtab, off_segbase, off_Wf, off_dec, off_S, off_tA, off_tP, off_sumY, off_sumD, total_fwd;
     size_t off_SF, off_Wr, off_E, off_dz, off_dgf, off_tB, off_tBT, off_tA2T, off_tAvT, off_tSbe, total_bwd;
     // layout of every memory snapshot record (elements); see gsa_layout.h
     StateLayout lay;
@@ -33,6 +34,7 @@ struct Plan {
 struct Work {
     int32_t *table;   // [4*chunk_slots] packed form only
     int32_t *seqtab;  // [4*n_seqs]     packed form only
+    int32_t *segbase; // [n_seqs+1]     packed form only: scan segments before each sequence
     // per (chunk, head) records, element type = I/O dtype unless noted; KM = max(m, 32)
     void *Wf;         // [m][C]      forward scan weights s*exp(G_C-G)
     float *dec;       // [m]         chunk decay exp(G_C)                                  (fp32)
@@ -46,13 +48,14 @@ struct Work {
     void *tA2T;       // [C][C]      A2^T
     void *tAvT;       // [C][C]      (dO_t . v_r)^T, causally masked
     void *tSbe;       // [C][KM]     s*exp(G_C-G)
+    float *sumY, *sumD;   // scan segment summaries (fp32), see gsa_scan.hip
     float *dz;        // [tokens][H][m]                                                     (fp32)
     float *dgf;       // [tokens][H][m]   z*dz + p*dp                                       (fp32)
 };
 
 // Kernel slots of the optional per-kernel event timing (gsa_profile_*).
 enum KernelSlot { kSlotPrepare = 0, kSlotGates, kSlotScanFwd, kSlotChunkFwd, kSlotApplyFwd, kSlotChunkDz, kSlotScanBwd,
-                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kSlotDecodeMerge, kSlotCopyProbe, kNumKernelSlots };
+                  kSlotChunkIntra, kSlotApplyBwd, kSlotDecode, kSlotDecodeMerge, kSlotCopyProbe, kSlotScanSummary, kNumKernelSlots };
 
 // Brackets one kernel launch with events on its stream when timing is enabled; otherwise a no-op.
 class KernelTimer {

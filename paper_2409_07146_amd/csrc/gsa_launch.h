@@ -11,6 +11,7 @@ inline ChunkMap make_chunk_map(const Plan &pl, const Work &w)
     const bool packed = pl.cu_seqlens != nullptr;
     cm.table = packed ? w.table : nullptr;
     cm.seq_tab = packed ? w.seqtab : nullptr;
+    cm.seg_base = packed ? w.segbase : nullptr;
     cm.T = pl.T;
     cm.chunk = pl.chunk;
     cm.chunks_per_seq = (pl.T + pl.chunk - 1) / pl.chunk;

@@ -16,6 +16,10 @@ namespace gsa {
 // slice it needs on its way into LDS.  Offsets are in elements from the start of the record.
 constexpr int kSnapTile = 64;
 
+// Chunks per segment when the scans cut long sequences into segments: the length at which one
+// workgroup's chain over the chunks no longer dominates the launch (measured: 32 chunks).
+constexpr int kSegChunks = 32;
+
 struct StateLayout {
     long long stride;   // elements per record
     long long oK, oV;   // key part, value part

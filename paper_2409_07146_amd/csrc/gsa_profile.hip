@@ -23,7 +23,7 @@ struct Slot {
 };
 Slot g_slots[kNumKernelSlots] = {{"prepare_kernel"}, {"gate_kernel"},      {"scan_fwd_kernel"}, {"chunk_fwd_kernel"},
                                  {"apply_fwd_kernel"}, {"chunk_dz_kernel"}, {"scan_bwd_kernel"}, {"chunk_intra_kernel"},
-                                 {"apply_bwd_kernel"}, {"decode_kernel"}, {"decode_merge_kernel"}, {"copy_probe_kernel"}};
+                                 {"apply_bwd_kernel"}, {"decode_kernel"}, {"decode_merge_kernel"}, {"copy_probe_kernel"}, {"scan_summary_kernel"}};
 
 hipEvent_t take_event(Slot &s)
 {

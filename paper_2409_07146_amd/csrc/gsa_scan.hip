@@ -67,6 +67,11 @@ template <typename T> struct ScanArgs {
     StateLayout lay;       // layout of every record
     float *outK, *outV;    // [n_seqs][H][M][d] or NULL: acc after the last chunk
     T *outJ;               // one record per (sequence, head), or NULL: the same, element type T
+    // long sequences cut into segments (modes 1 and 2 of the kernel):
+    int seg_chunks;        // chunks per segment
+    int max_seg;           // segments per sequence the grid provides for
+    float *sumY;           // [n_seqs][max_seg][H][M][d_k+d_v]   what a segment adds, from a zero start
+    float *sumD;           // [n_seqs][max_seg][H][slices][M]    its total decay
 };
 
 template <typename T, int M, int NS> struct ScanLds {
@@ -84,7 +89,13 @@ template <typename T, int M, int NS> struct ScanLds {
     static constexpr size_t bytes = 2 * set;
 };
 
-template <typename T, int M, int NS, bool REVERSE>
+// MODE 0: one workgroup walks a whole sequence.  A sequence of many chunks leaves the chip waiting on
+// that one chain, so long sequences are cut into segments of seg_chunks chunks and walked in two
+// launches: MODE 1 walks every segment but the last of the walk from a zero start, without snapshots,
+// and leaves what the segment adds (sumY) and its total decay (sumD); MODE 2 walks every segment for
+// real, starting from the memory its predecessors leave behind, which it gets by running the
+// recurrence over their summaries (at most max_seg - 1 steps of an element-wise update).
+template <typename T, int M, int NS, bool REVERSE, int MODE>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(ChunkMap cm, int H, int d_k, int d_v, int n_seqs,
                                                           ScanArgs<T> a)
 {
@@ -103,12 +114,40 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
     const int r = lane & 15, g4 = (lane >> 4) * 4, g8 = (lane >> 4) * 8;
     const int D = d_k + d_v;
     const int nsl = D / NS;
-    // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs; give each
-    // XCD a contiguous range of logical ids so that the slices of one (sequence, head) share an L2
-    int total = nsl * H * n_seqs, bid = blockIdx.x;
-    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
-    const int slice = bid % nsl, sh = bid / nsl;
-    const int h = sh % H, s = sh / H;
+    // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs.  The slices of one
+    // (sequence, head, segment) share W and dec, so a whole group of slices is put on one XCD (one L2),
+    // and successive groups on successive XCDs (the segments of a long sequence, of which a packed
+    // batch may hold few, then spread over the whole chip).
+    const int nseg_grid = (MODE == 0) ? 1 : a.max_seg;
+    const int ngroups = H * n_seqs * nseg_grid;
+    int slice, group;
+    if ((ngroups & 7) == 0) {
+        const int x = blockIdx.x & 7, t = blockIdx.x >> 3;
+        slice = t % nsl;
+        group = (t / nsl) * 8 + x;
+    } else {
+        slice = blockIdx.x % nsl;
+        group = blockIdx.x / nsl;
+    }
+    // A group is (segment of a sequence, head), heads fastest.  The segments are numbered densely,
+    // sequence after sequence; a packed batch has fewer of them than the grid provides for (their
+    // number is only known on the device), and the surplus sits at the end of the numbering, so the
+    // real ones are spread evenly over the XCDs.
+    const int h = group % H, dense = group / H;
+    int s, seg;
+    if (MODE == 0) {
+        s = dense; seg = 0;
+    } else if (cm.seg_base) {
+        if (dense >= cm.seg_base[n_seqs]) return;   // uniform over the workgroup
+        int lo = 0, hi = n_seqs - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (cm.seg_base[mid] <= dense) lo = mid; else hi = mid - 1;
+        }
+        s = lo; seg = dense - cm.seg_base[lo];
+    } else {
+        s = dense / nseg_grid; seg = dense % nseg_grid;
+    }
     const int col0 = slice * NS;
     const bool isK = col0 < d_k;
     const T *src = isK ? a.xk : a.xv;
@@ -116,9 +155,21 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
     const int c0 = isK ? col0 : col0 - d_k;
     const size_t wpart = (a.w_parts == 2 && !isK) ? (size_t)M * C : 0;
 
-    int chunk0, nch, tok0, ntok;
-    seq_lookup(cm, s, chunk0, nch, tok0, ntok);
+    int chunk0, nch_seq, tok0, ntok;
+    seq_lookup(cm, s, chunk0, nch_seq, tok0, ntok);
     const int wcol = wave * 16 * NI;
+    // the chunks this workgroup walks: [first, first + nch) of the sequence
+    int first = 0, nch = nch_seq, nseg = 1;
+    if (MODE != 0) {
+        nseg = max(1, (nch_seq + a.seg_chunks - 1) / a.seg_chunks);
+        first = seg * a.seg_chunks;
+        nch = min(a.seg_chunks, nch_seq - first);
+        const int last_of_walk = REVERSE ? 0 : nseg - 1;
+        if (seg >= nseg || (MODE == 1 && seg == last_of_walk)) return;   // uniform over the workgroup
+        if (nch_seq == 0) nch = 0;   // a sequence without tokens still hands its initial memory through (MODE 2)
+    }
+    const bool starts_walk = (MODE == 0) || seg == (REVERSE ? nseg - 1 : 0);
+    const bool ends_walk = (MODE == 0) || seg == (REVERSE ? 0 : nseg - 1);
 
     f32x4 acc[MI][NI];
     {
@@ -130,13 +181,36 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int i = mi * 16 + g4 + j, c = c0 + wcol + ni * 16 + r;
-                    acc[mi][ni][j] = S0 ? S0[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
+                    acc[mi][ni][j] = (MODE != 1 && S0) ? S0[(((size_t)s * H + h) * M + i) * dsrc + c] : 0.f;
                 }
+        if (MODE == 2 && !starts_walk) {
+            // the memory at the start of this segment: the recurrence over the summaries of the segments
+            // walked before it, acc <- Diag(sumD) acc + sumY, in walk order
+            const int npre = REVERSE ? nseg - 1 - seg : seg;
+            for (int u = 0; u < npre; ++u) {
+                const int sg = REVERSE ? nseg - 1 - u : u;
+                const size_t rec = ((size_t)s * a.max_seg + sg) * H + h;
+                const float *Y = a.sumY + rec * M * D + col0;
+                const float *Dd = a.sumD + (rec * nsl + slice) * M;
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    const f32x4 dd = *reinterpret_cast<const f32x4 *>(Dd + mi * 16 + g4);
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[mi][ni][j] = dd[j] * acc[mi][ni][j] + Y[(size_t)(mi * 16 + g4 + j) * D + wcol + ni * 16 + r];
+                }
+            }
+        }
         // Let these loads land before the loop's prefetches are issued: otherwise the first use of the
         // accumulator inside the loop has to wait for "everything older", which the compiler can only
         // express as "everything", and that would drain the prefetches in every iteration.
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
     }
+    f32x4 dprod[MI];   // MODE 1: product of the chunk decays, rows as in acc
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) dprod[mi] = f32x4{1.f, 1.f, 1.f, 1.f};
 
     // Operands of one chunk, staged in registers: the loads of the next two chunks are in flight
     // while the current one multiplies (one chunk ahead does not cover the memory latency of a
@@ -204,7 +278,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
     // position in the walk -> chunk; positions past the end repeat the last chunk, so that refills can be
     // issued unconditionally (a refill under a branch makes the number of loads in flight unknown to the
     // compiler, which then waits for all of them wherever it needs one)
-    auto chunk_of = [&](int it) { it = min(it, nch - 1); return REVERSE ? nch - 1 - it : it; };
+    auto chunk_of = [&](int it) { it = min(it, nch - 1); return first + (REVERSE ? nch - 1 - it : it); };
 
     // The walk, software-pipelined with ONE barrier per chunk.  At the top of step `it` LDS set it%2
     // holds the operands of chunk `it` (written during the previous step) and the snapshot tile of
@@ -218,8 +292,10 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
     // else rides beside it.  A set is rewritten two steps after it was read, with a barrier between.
     auto step = [&](Stage &nx, int it) {
         const int b = it & 1;
-        if (it > 0) snapshot_to_global(a.snap + ((size_t)(chunk0 + chunk_of(it - 1)) * H + h) * a.lay.stride, b ^ 1);
-        snapshot_to_lds(b);
+        if (MODE != 1) {
+            if (it > 0) snapshot_to_global(a.snap + ((size_t)(chunk0 + chunk_of(it - 1)) * H + h) * a.lay.stride, b ^ 1);
+            snapshot_to_lds(b);
+        }
         typename Atom<T>::Frag af[C / 32][MI], bf[C / 32][NI];
         const T *w = We(b), *x = XT(b);
 #pragma unroll
@@ -233,6 +309,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const f32x4 dcur = *reinterpret_cast<const f32x4 *>(Dec(b) + mi * 16 + g4);
+            if (MODE == 1) dprod[mi] *= dcur;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) acc[mi][ni] *= dcur;
         }
@@ -272,7 +349,25 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
         __syncthreads();
         ++it;
     }
-    if (nch > 0) snapshot_to_global(a.snap + ((size_t)(chunk0 + chunk_of(nch - 1)) * H + h) * a.lay.stride, (nch - 1) & 1);
+    if (MODE != 1 && nch > 0)
+        snapshot_to_global(a.snap + ((size_t)(chunk0 + chunk_of(nch - 1)) * H + h) * a.lay.stride, (nch - 1) & 1);
+    if (MODE == 1) {   // what this segment adds and how much it decays, for its successors
+        const size_t rec = ((size_t)s * a.max_seg + seg) * H + h;
+        float *Y = a.sumY + rec * M * D + col0;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) Y[(size_t)(mi * 16 + g4 + j) * D + wcol + ni * 16 + r] = acc[mi][ni][j];
+        if (wave == 0 && r == 0) {
+            float *Dd = a.sumD + (rec * nsl + slice) * M;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) *reinterpret_cast<f32x4 *>(Dd + mi * 16 + g4) = dprod[mi];
+        }
+        return;
+    }
+    if (!ends_walk) return;
     // accumulator after the last chunk
     float *ST = isK ? a.outK : a.outV;
     if (ST) {
@@ -325,16 +420,25 @@ hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, const flo
 #undef GSA_GATES
 }
 
+template <typename T, int M, int NS, bool REVERSE, int MODE>
+static hipError_t run_scan_mode(const Plan &pl, const ChunkMap &cm, const ScanArgs<T> &a, int slot, hipStream_t st)
+{
+    auto kern = scan_kernel<T, M, NS, REVERSE, MODE>;
+    const size_t lds = ScanLds<T, M, NS>::bytes;
+    GSA_HIP_TRY(allow_lds(kern, lds));
+    const int total = (pl.d_k + pl.d_v) / NS * pl.H * pl.n_seqs * (MODE == 0 ? 1 : a.max_seg);
+    KernelTimer kt(slot, st);
+    hipLaunchKernelGGL(kern, dim3(total), dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.n_seqs, a);
+    return hipGetLastError();
+}
+
 template <typename T, int M, int NS, bool REVERSE>
 static hipError_t run_scan(const Plan &pl, const ChunkMap &cm, const ScanArgs<T> &a, hipStream_t st)
 {
-    auto kern = scan_kernel<T, M, NS, REVERSE>;
-    const size_t lds = ScanLds<T, M, NS>::bytes;
-    GSA_HIP_TRY(allow_lds(kern, lds));
-    const int total = (pl.d_k + pl.d_v) / NS * pl.H * pl.n_seqs;
-    KernelTimer kt(REVERSE ? kSlotScanBwd : kSlotScanFwd, st);
-    hipLaunchKernelGGL(kern, dim3(total), dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.n_seqs, a);
-    return hipGetLastError();
+    const int slot = REVERSE ? kSlotScanBwd : kSlotScanFwd;
+    if (a.max_seg <= 1) return run_scan_mode<T, M, NS, REVERSE, 0>(pl, cm, a, slot, st);
+    GSA_HIP_TRY((run_scan_mode<T, M, NS, REVERSE, 1>(pl, cm, a, kSlotScanSummary, st)));
+    return run_scan_mode<T, M, NS, REVERSE, 2>(pl, cm, a, slot, st);
 }
 
 template <typename T, int M>
@@ -354,6 +458,10 @@ static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io
     a.outK = io.outK;
     a.outV = io.outV;
     a.outJ = static_cast<T *>(io.outJ);
+    a.seg_chunks = pl.seg_chunks;
+    a.max_seg = pl.max_seg;
+    a.sumY = w.sumY;
+    a.sumD = w.sumD;
     // 64-column slices: several workgroups per CU, so that their dependent chains overlap
     if (io.reverse) return run_scan<T, M, 64, true>(pl, cm, a, st);
     return run_scan<T, M, 64, false>(pl, cm, a, st);

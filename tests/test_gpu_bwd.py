@@ -165,3 +165,26 @@ def test_fwd_bwd_extreme_scales(oracle, scale, dtype):
     cfg = GsaConfig("scales", B=1, T=140, H=2, d_k=64, d_v=64, m=16, dtype=dtype, init_state_std=0.5, seed=25)
     x, got = run_fwd_bwd(cfg, scale=scale)
     compare_bwd(oracle, cfg, x, got, scale=scale, abs_floor=2e-6 if dtype == "f32" else 2e-2)
+
+
+@pytest.mark.parametrize("dtype,T", [("bf16", 3400), ("f32", 1700)])
+def test_fwd_bwd_long_sequences_walked_in_segments(oracle, dtype, T):
+    """Sequences of more than 48 chunks are walked by the scans in segments of 32 chunks (two launches);
+    here 54 chunks with a ragged tail, initial memories and final-memory gradients."""
+    from paper_2409_07146_amd.synth import GsaConfig
+    cfg = GsaConfig("long", B=2, T=T, H=2, d_k=64, d_v=128, m=16, dtype=dtype, init_state_std=0.5, seed=71)
+    x, got = run_fwd_bwd(cfg, scale=1.0, with_state_grads=True)
+    compare_bwd(oracle, cfg, x, got)
+    f = oracle.fwd(to_np64(x["q"]), to_np64(x["k"]), to_np64(x["v"]), to_np64(x["g"]), K0=to_np64(x["K0"]),
+                   V0=to_np64(x["V0"]))
+    check("KT", to_np64(got["KT"]), f["KT"], dtype)
+    check("VT", to_np64(got["VT"]), f["VT"], dtype)
+
+
+def test_fwd_bwd_packed_long_and_short_sequences(oracle):
+    """Packed: a sequence of 40 chunks (two segments), a short one, an empty one and one of 24 chunks."""
+    from paper_2409_07146_amd.synth import GsaConfig
+    cfg = GsaConfig("longpacked", B=1, T=4150, H=2, d_k=64, d_v=64, m=32, dtype="bf16", init_state_std=0.5,
+                    cu_seqlens=(0, 2530, 2630, 2630, 4150), seed=72)
+    x, got = run_fwd_bwd(cfg, with_state_grads=True)
+    compare_bwd(oracle, cfg, x, got)
