@@ -84,7 +84,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
     float dp[MI][4];
     bool unsafe;
     gated_scores<T, M, C, GEN>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
-                               reinterpret_cast<T *>(smem + L::oVt), L::lda, static_cast<T *>(nullptr), 0,
+                               reinterpret_cast<T *>(smem + L::oVt), L::lda,
                                reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
                                v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,
                                (GEN && sin) ? sin + tokh * M : nullptr);

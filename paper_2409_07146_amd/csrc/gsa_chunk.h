@@ -75,16 +75,15 @@ __device__ __forceinline__ void reduce_row_blocks(f32x4 (&own)[NB], const f32x4 
 
 // Write-intensity tiles of one chunk, referenced to the END of each token's own 16-token block:
 //   V[kk][i] = s_kk[i] * exp(G_end(kk)[i] - G_kk[i])  <= 1        (G_end = cumulative gate at the block's last token)
-// stored transposed, Vt[i][kk] (operand of contractions over tokens), and, if Vn is not NULL,
-// natural, Vn[kk][i] (operand of contractions over slots); plus the decay across each block,
+// stored transposed, Vt[i][kk] (operand of contractions over tokens); plus the decay across each block,
 //   Rb[b][i] = exp(G_end(b)[i] - G_end(b-1)[i]).
 // With these, the weight between a token of row block w and an EARLIER block's token needs no
 // exponential of its own: exp(G_t - G_kk) = exp(G_t - G_start(w)) * prod of Rb over the blocks in
 // between * exp(G_end(kk) - G_kk), every factor <= 1 (nothing to clamp).  One (block, slot) pair
 // per thread and pass; no barrier inside.
 template <typename T, int M, int C>
-__device__ __forceinline__ void build_write_tiles(const float *Gs, const float *Ss, int ldg, T *Vt, int ldv, T *Vn,
-                                                  int ldn, float *Rb, int tid)
+__device__ __forceinline__ void build_write_tiles(const float *Gs, const float *Ss, int ldg, T *Vt, int ldv, float *Rb,
+                                                  int tid)
 {
     constexpr int CI = C / 16, NT = Geo<T>::NT;
     for (int idx = tid; idx < CI * M; idx += NT) {
@@ -103,10 +102,6 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
         for (int e = 0; e < 8; ++e) { lo[e] = x[e]; hi[e] = x[8 + e]; }
         store8<T>(Vt + i * ldv + 16 * b, lo);
         store8<T>(Vt + i * ldv + 16 * b + 8, hi);
-        if (Vn) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) Vn[(16 * b + e) * ldn + i] = from_f32<T>(x[e]);
-        }
     }
 }
 
@@ -128,13 +123,13 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // `tot`: scratch of NT floats): the gate loads are issued after the contraction and land during
 // the reduction, and the tiles are written once the reduction buffer is dead, so Red may alias
 // Gs and Ss too.  As [C][lda] is left holding the causally masked X Y^T rounded to T, and the tiles
-// of build_write_tiles are left in Vt, Vn (may be NULL), Rb for the caller's own use.
+// of build_write_tiles are left in Vt, Rb for the caller's own use.
 // All threads of the workgroup must call it.
 // GEN: general form; sin = write intensities [len][M] (layout of g) or NULL for 1 - exp(g).
 template <typename T, int M, int C, bool GEN = false>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
-                                             T *Vn, int ldn, float *Rb, f32x4 *Red, const T *X, const T *Y,
+                                             float *Rb, f32x4 *Red, const T *X, const T *Y,
                                              size_t ldx, int d, const T *St, int len, int tid,
                                              const float *sin = nullptr)
 {
@@ -196,7 +191,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
             const int t = rowb + g4 + j, rr = ni * 16 + r;
             As[t * lda + rr] = from_f32<T>((ni <= w && rr <= t) ? accA[ni][j] : 0.f);
         }
-    build_write_tiles<T, M, C>(Gs, Ss, ldg, Vt, ldv, Vn, ldn, Rb, tid);
+    build_write_tiles<T, M, C>(Gs, Ss, ldg, Vt, ldv, Rb, tid);
     __syncthreads();
     unsafe = block_unsafe<M>(Gs, ldg, rowb, lane);
     // ---- earlier row blocks, through the end-referenced tile: `run` walks its reference from the chunk

@@ -101,8 +101,7 @@ template <typename T, int M> struct ChunkFwdLds {
                                                                                   : sizeof(float) * Geo<T>::NT;
     static constexpr size_t oP = oA + szA;
     static constexpr size_t oVt = oP + sizeof(T) * C * ldp;           // Vt [M][lda]
-    static constexpr size_t oVn = oVt + sizeof(T) * M * lda;          // Vn [C][ldp]
-    static constexpr size_t oRb = oVn + sizeof(T) * C * ldp;          // Rb [C/16][M] fp32
+    static constexpr size_t oRb = oVt + sizeof(T) * M * lda;          // Rb [C/16][M] fp32
     static constexpr size_t end = oRb + sizeof(float) * (C / 16) * M;
     static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
     static constexpr size_t bytes = end > szRed ? end : szRed;
@@ -142,10 +141,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     // ---- pass 1: z = scale * (inter + gated intra), Eq. (gla-chunk) with the gate on the slot side
     float p[MI][4];
     bool unsafe;
-    T *Vt = reinterpret_cast<T *>(smem + L::oVt), *Vn = reinterpret_cast<T *>(smem + L::oVn);
+    T *Vt = reinterpret_cast<T *>(smem + L::oVt);
     float *Rb = reinterpret_cast<float *>(smem + L::oRb);
-    gated_scores<T, M, C, GEN>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Vn,
-                               L::ldp, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
+    gated_scores<T, M, C, GEN>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
                                (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
