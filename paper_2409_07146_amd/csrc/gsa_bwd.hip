@@ -304,21 +304,31 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
             for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[ni], fs[ni]);
         }
         // value half: X += V E_v^T
-        for (int k0 = 32 * w; k0 < d_v; k0 += 32 * NW) {
-            Frag fv[CI], fe[MI], fs[MI];
+        // (64 columns per wave and step here, as in gated_scores: the registers allow it in this half)
+        for (int kk = 64 * w; kk < d_v; kk += 64 * NW) {
+            Frag fv[2][CI], fe[2][MI], fs[2][MI];
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) fv[ni] = Atom<T>::load(vb + tv[ni] + k0);
+            for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EV + ev[ni] + snap_col<M>(k0));
+                for (int ni = 0; ni < CI; ++ni) fv[hh][ni] = Atom<T>::load(vb + tv[ni] + kk + 32 * hh);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendV + ev[ni] + snap_col<M>(k0));
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) fe[hh][ni] = Atom<T>::load(EV + ev[ni] + snap_col<M>(kk + 32 * hh));
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load(SendV + ev[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int rb = 0; rb < NW; ++rb)
+            for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fv[rb], fe[ni]);
+                for (int rb = 0; rb < NW; ++rb)
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[ni], fs[ni]);
+                    for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fv[hh][rb], fe[hh][ni]);
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[hh][ni], fs[hh][ni]);
+            }
         }
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) {

@@ -114,11 +114,11 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // slot side (pass 1 of Eq. (gsa-2pass) with X=q, Y=k, St=Kt; its mirror in the backward
 // with X=dO, Y=v, St=Vt).  X, Y: [len][d] rows in global memory (row stride ldx elements);
 // St: one part of a memory snapshot (M slots, d columns, tiled as StateLayout describes).
-// The contraction over d reads its operand fragments straight from global memory (each lane 16 bytes of one row; no staging).  It is split over
-// the waves in steps of 32 columns, wave w taking steps w, w+NW, ...: neighbouring waves ask
-// for the two halves of a 128-byte line at about the same time, so each line crosses the
+// The contraction over d reads its operand fragments straight from global memory (each lane 16
+// bytes of one row; no staging).  It is split over the waves in steps of 64 columns, wave w taking steps w, w+NW, ...: a wave asks for the two
+// halves of a 128-byte line in consecutive instructions, so each line crosses the
 // memory system once.  The partial sums meet through Red (see reduce_row_blocks; Red may
-// alias As).  d must be a multiple of 32.
+// alias As).  d must be a multiple of 64.
 // The gate tiles Gs, Ss are produced in here as well (from g: [len][M] fp32, row stride gld;
 // `tot`: scratch of NT floats): the gate loads are issued after the contraction and land during
 // the reduction, and the tiles are written once the reduction buffer is dead, so Red may alias
@@ -153,25 +153,38 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) so[ni] = (uint32_t)(ni * 16 + r) * kSnapTile + g8;
         typedef typename Atom<T>::Frag Frag;
-        for (int k0 = 32 * w; k0 < d; k0 += 32 * NW) {
-            Frag fx[CI], fy[CI], fs[MI];
+        // a wave takes 64 columns at a time: the two halves of every 128-byte line are asked for by the
+        // same wave in consecutive instructions
+        for (int kk = 64 * w; kk < d; kk += 64 * NW) {
+            Frag fx[2][CI], fy[2][CI], fs[2][MI];
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) fx[ni] = Atom<T>::load(X + xo[ni] + k0);
+            for (int hh = 0; hh < 2; ++hh) {
+                const int k0 = kk + 32 * hh;
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) fy[ni] = Atom<T>::load(Y + xo[ni] + k0);
+                for (int ni = 0; ni < CI; ++ni) fx[hh][ni] = Atom<T>::load(X + xo[ni] + k0);
+            }
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(St + so[ni] + snap_col<M>(k0));
-            // keep every load of the step ahead of its multiplies: left alone, the scheduler sinks loads
-            // between the multiplies to save registers and the wave ends up with one or two in flight.
-            // (A second register set for the next step's loads measured slower.)
+            for (int hh = 0; hh < 2; ++hh) {
+                const int k0 = kk + 32 * hh;
+#pragma unroll
+                for (int ni = 0; ni < CI; ++ni) fy[hh][ni] = Atom<T>::load(Y + xo[ni] + k0);
+            }
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int k0 = kk + 32 * hh;
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load(St + so[ni] + snap_col<M>(k0));
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int rb = 0; rb < NW; ++rb) {
+            for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                for (int cb = 0; cb <= rb; ++cb) Atom<T>::mma(acc[rb][cb], fx[rb], fy[cb]);
+                for (int rb = 0; rb < NW; ++rb) {
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fx[rb], fs[ni]);
-            }
+                    for (int cb = 0; cb <= rb; ++cb) Atom<T>::mma(acc[rb][cb], fx[hh][rb], fy[hh][cb]);
+#pragma unroll
+                    for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fx[hh][rb], fs[hh][ni]);
+                }
         }
         GatePrep<M, Geo<T>::NT, C, GEN> gp;
         gp.load(g, gld, len, tid, sin);
