@@ -282,26 +282,50 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
         }
         const T *qb = a.q + tokh * d_k, *kb = a.k + tokh * d_k, *vb = a.v + tokh * d_v;
         // key half: A = Q K^T, X += K E_k^T
-        for (int k0 = 32 * w; k0 < d_k; k0 += 32 * NW) {
-            Frag fq[CI], fk[CI], fe[MI], fs[MI];
+        // (two passes over k, each in 64-column steps like the value half: together their operand
+        // fragments would not fit the registers; the second read of k is served by the caches)
+        for (int kk = 64 * w; kk < d_k; kk += 64 * NW) {
+            Frag fq[2][CI], fk[2][CI];
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) fq[ni] = Atom<T>::load(qb + tk[ni] + k0);
+            for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-            for (int ni = 0; ni < CI; ++ni) fk[ni] = Atom<T>::load(kb + tk[ni] + k0);
+                for (int ni = 0; ni < CI; ++ni) fq[hh][ni] = Atom<T>::load(qb + tk[ni] + kk + 32 * hh);
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fe[ni] = Atom<T>::load(EK + ek[ni] + snap_col<M>(k0));
+            for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-            for (int ni = 0; ni < MI; ++ni) fs[ni] = Atom<T>::load(SendK + ek[ni] + snap_col<M>(k0));
+                for (int ni = 0; ni < CI; ++ni) fk[hh][ni] = Atom<T>::load(kb + tk[ni] + kk + 32 * hh);
             __builtin_amdgcn_sched_barrier(0);   // all loads of the step before its multiplies (see gated_scores)
 #pragma unroll
-            for (int rb = 0; rb < NW; ++rb) {
+            for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                for (int cb = 0; cb <= rb; ++cb) Atom<T>::mma(acc[rb][cb], fq[rb], fk[cb]);
+                for (int rb = 0; rb < NW; ++rb)
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fk[rb], fe[ni]);
+                    for (int cb = 0; cb <= rb; ++cb) Atom<T>::mma(acc[rb][cb], fq[hh][rb], fk[hh][cb]);
+        }
+        for (int kk = 64 * w; kk < d_k; kk += 64 * NW) {
+            Frag fk[2][CI], fe[2][MI], fs[2][MI];
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int ni = 0; ni < CI; ++ni) fk[hh][ni] = Atom<T>::load(kb + tk[ni] + kk + 32 * hh);
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) fe[hh][ni] = Atom<T>::load(EK + ek[ni] + snap_col<M>(kk + 32 * hh));
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load(SendK + ek[ni] + snap_col<M>(kk + 32 * hh));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+                for (int rb = 0; rb < NW; ++rb)
+#pragma unroll
+                    for (int ni = 0; ni < MI; ++ni) Atom<T>::mma(acc[rb][CI + ni], fk[hh][rb], fe[hh][ni]);
+#pragma unroll
+                for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[hh][ni], fs[hh][ni]);
             }
-#pragma unroll
-            for (int ni = 0; ni < MI; ++ni) cpart[ni] += frag_dot<T>(fe[ni], fs[ni]);
         }
         // value half: X += V E_v^T
         // (64 columns per wave and step here, as in gated_scores: the registers allow it in this half)
