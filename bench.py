@@ -233,9 +233,7 @@ def main():
     od = torch.empty_like(dv_[0])
     state_bytes = 2 * 4 * dd["B"] * dd["H"] * dd["m"] * (dd["d_k"] + dd["d_v"])
     dec = {}
-    dws = gsa.alloc_decode_workspace(dd["B"], dd["H"], dd["d_k"], dd["d_v"], dd["m"], dev)
-    for label, sets, w in (("one_state_set", 1, None), ("rotating_8_state_sets", nsets, None),
-                           ("rotating_8_state_sets_with_workspace", nsets, dws)):
+    for label, sets, w in (("one_state_set", 1, None), ("rotating_8_state_sets", nsets, None)):
         for i in range(20):
             gsa.gsa_decode_step(dq_[i % 4], dk_[i % 4], dv_[i % 4], dg_[i % 4], Ks[i % sets], Vs[i % sets], out=od,
                                 workspace=w)

@@ -131,7 +131,7 @@ gsa_status gsa_bwd(const gsa_problem *p,
  *           s NULL, ds is not touched and dg is as in gsa_bwd.  The same s and
  *           readout must be passed to both calls.
  * Errors as for gsa_fwd/gsa_bwd; an unknown readout returns GSA_ERR_SHAPE.
- * The decode step has no such variants.
+ * gsa_decode_step_ex (below) is the decode step with the same two options.
  */
 typedef enum {
     GSA_READOUT_SOFTMAX = 0, GSA_READOUT_IDENTITY = 1, GSA_READOUT_SWISH = 2, GSA_READOUT_RELU = 3,
@@ -165,17 +165,16 @@ gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32
                            float *K_state, float *V_state, void *o, void *stream);
 
 /*
- * The same step (Eq. (gsa), decode form) with each memory pair spread over several
- * workgroups, each covering some of the slots; their partial read-outs (each with
- * its own softmax maximum and sum) pass through the workspace and are merged by a
- * second kernel in a fixed order.  With few memories in flight (small batches, the
- * token-by-token generation loop of Figure 4c) this is what fills the chip; with
- * many it still overlaps the loads and stores of workgroups that share a compute
- * unit.  Results agree with gsa_decode_step up to fp32 rounding order and are
- * reproducible run to run.
+ * The same step (Eq. (gsa), decode form) for callers with few memories in flight
+ * (small batches, the token-by-token generation loop of Figure 4c): with B*H up
+ * to 64 each memory pair is spread over m/4 workgroups, whose partial read-outs
+ * (each with its own softmax maximum and sum) pass through the workspace and
+ * are merged by a second kernel in a fixed order; above that the call does what
+ * gsa_decode_step does.  Results agree with gsa_decode_step up to fp32 rounding
+ * order and are reproducible run to run.
  *   workspace: device memory, 256-byte aligned, at least
- *   gsa_decode_workspace_bytes(...) bytes; contents meaningless to the caller;
- *   calls sharing a workspace must not overlap.
+ *   gsa_decode_workspace_bytes(...) bytes (0 when the split form is not used);
+ *   contents meaningless to the caller; calls sharing a workspace must not overlap.
  * Errors as for gsa_decode_step, plus GSA_ERR_WORKSPACE.
  */
 gsa_status gsa_decode_workspace_bytes(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, size_t *bytes);
@@ -206,6 +205,18 @@ gsa_status gsa_profile_read(int32_t index, const char **name, double *ms, int64_
  * Timed in slot "copy_probe_kernel" while profiling is enabled.
  */
 gsa_status gsa_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/*
+ * The decode step with the options of gsa_fwd_ex: s [B,H,m] fp32 or NULL (write
+ * intensity as an input of its own), readout a gsa_readout.  workspace may be
+ * NULL (then the call behaves like gsa_decode_step) or as for
+ * gsa_decode_step_ws.
+ */
+gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
+                              int32_t dtype, float scale, int32_t readout,
+                              const void *q, const void *k, const void *v, const float *g, const float *s,
+                              float *K_state, float *V_state, void *o,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -333,11 +333,11 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
 
 /*
  * One recurrent (decode) step of Eq. (gsa) for BH independent memories,
- * updated in place.  q,k [BH,dk], v [BH,dv], g [BH,m];
+ * updated in place.  q,k [BH,dk], v [BH,dv], g [BH,m]; sin [BH,m] or NULL and readout as in the forward;
  * K [BH,m,dk], V [BH,m,dv], o [BH,dv] double.
  */
-int gsa_oracle_decode_step(int BH, int dk, int dv, int m, double scale,
-                           const double *q, const double *k, const double *v, const double *g,
+int gsa_oracle_decode_step(int BH, int dk, int dv, int m, double scale, int readout,
+                           const double *q, const double *k, const double *v, const double *g, const double *sin,
                            double *K, double *V, double *o)
 {
     int fail = 0;
@@ -349,8 +349,8 @@ int gsa_oracle_decode_step(int BH, int dk, int dv, int m, double scale,
             fail = 1;
             continue;
         }
-        step_token(dk, dv, m, scale, RO_SOFTMAX, q + (size_t)b * dk, k + (size_t)b * dk, v + (size_t)b * dv,
-                   g + (size_t)b * m, NULL, K + (size_t)b * m * dk, V + (size_t)b * m * dv,
+        step_token(dk, dv, m, scale, readout, q + (size_t)b * dk, k + (size_t)b * dk, v + (size_t)b * dv,
+                   g + (size_t)b * m, sin ? sin + (size_t)b * m : NULL, K + (size_t)b * m * dk, V + (size_t)b * m * dv,
                    zp, zp + m, o + (size_t)b * dv);
         free(zp);
     }

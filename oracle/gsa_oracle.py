@@ -44,7 +44,7 @@ def _lib():
                                        _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p]
         lib.gsa_oracle_decode_step.restype = ctypes.c_int
         lib.gsa_oracle_decode_step.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                               ctypes.c_double, _f64p, _f64p, _f64p, _f64p,
+                                               ctypes.c_double, ctypes.c_int, _f64p, _f64p, _f64p, _f64p, _f64p,
                                                _f64p, _f64p, _f64p]
         _LIB = lib
     return _LIB
@@ -128,18 +128,19 @@ def bwd(q, k, v, g, dO, cu_seqlens=None, K0=None, V0=None, dKT=None, dVT=None, s
     return out
 
 
-def decode_step(q, k, v, g, K, V, scale=1.0):
+def decode_step(q, k, v, g, K, V, scale=1.0, s=None, readout="softmax"):
     """q,k [B,H,dk], v [B,H,dv], g [B,H,m]; K [B,H,m,dk], V [B,H,m,dv] float64,
     updated IN PLACE.  Returns o [B,H,dv] float64."""
-    q, k, v, g = _f64(q), _f64(k), _f64(v), _f64(g)
+    q, k, v, g, s = _f64(q), _f64(k), _f64(v), _f64(g), _f64(s)
+    assert s is None or s.shape == g.shape
     B, H, dk = q.shape
     dv, m = v.shape[-1], g.shape[-1]
     assert K.dtype == np.float64 and V.dtype == np.float64
     assert K.flags.c_contiguous and V.flags.c_contiguous
     assert K.shape == (B, H, m, dk) and V.shape == (B, H, m, dv)
     o = np.empty((B, H, dv), np.float64)
-    rc = _lib().gsa_oracle_decode_step(B * H, dk, dv, m, float(scale),
-                                       _p64(q), _p64(k), _p64(v), _p64(g), _p64(K), _p64(V), _p64(o))
+    rc = _lib().gsa_oracle_decode_step(B * H, dk, dv, m, float(scale), READOUTS[readout],
+                                       _p64(q), _p64(k), _p64(v), _p64(g), _p64(s), _p64(K), _p64(V), _p64(o))
     if rc != 0:
         raise MemoryError("gsa_oracle_decode_step failed")
     return o

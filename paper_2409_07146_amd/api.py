@@ -162,10 +162,11 @@ def alloc_decode_workspace(B, H, d_k, d_v, m, device) -> torch.Tensor:
     return torch.empty(max(gsa_decode_workspace_bytes(B, H, d_k, d_v, m), 256), dtype=torch.uint8, device=device)
 
 
-def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace=None):
+def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace=None, s=None, readout="softmax"):
     """q,k [B,H,d_k], v [B,H,d_v], g [B,H,m]; K_state,V_state fp32 [B,H,m,d], updated in place.
     With a workspace (alloc_decode_workspace) the call goes through gsa_decode_step_ws, which spreads
-    each memory over several workgroups when B*H is small.  Returns o [B,H,d_v]."""
+    each memory over several workgroups.  With s ([B,H,m] fp32 write intensities) or a readout other than
+    "softmax" it goes through gsa_decode_step_ex.  Returns o [B,H,d_v]."""
     B, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     if q.dtype not in _DTYPES:
@@ -176,6 +177,15 @@ def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace
     _check(V_state, "V_state", torch.float32, (B, H, m, d_v))
     o = torch.empty_like(v) if out is None else out
     _check(o, "out", q.dtype, (B, H, d_v))
+    if s is not None or readout != "softmax":
+        _check(s, "s", torch.float32, (B, H, m), optional=True)
+        rc = _lib.load().gsa_decode_step_ex(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), READOUTS[readout],
+                                            _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s), _ptr(K_state),
+                                            _ptr(V_state), _ptr(o), _ptr(workspace),
+                                            0 if workspace is None else workspace.numel(), _stream(q))
+        if rc != 0:
+            raise GsaError(rc, "gsa_decode_step_ex")
+        return o
     if workspace is not None:
         rc = _lib.load().gsa_decode_step_ws(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), _ptr(q), _ptr(k),
                                             _ptr(v), _ptr(g), _ptr(K_state), _ptr(V_state), _ptr(o),

@@ -134,13 +134,15 @@ gsa_status decode_checks(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t
 
 gsa_status decode_any(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
                       const void *q, const void *k, const void *v, const float *g, float *K_state, float *V_state,
-                      void *o, bool with_ws, void *workspace, size_t workspace_bytes, void *stream)
+                      void *o, bool with_ws, void *workspace, size_t workspace_bytes, void *stream,
+                      const float *s = nullptr, int32_t readout = GSA_READOUT_SOFTMAX)
 {
     const gsa_status st = decode_checks(B, H, d_k, d_v, m, dtype, scale);
     if (st != GSA_OK) return st;
+    if (readout < GSA_READOUT_SOFTMAX || readout > GSA_READOUT_RELU2) return GSA_ERR_SHAPE;
     if (B == 0) return GSA_OK;
     if (!q || !k || !v || !g || !K_state || !V_state || !o) return GSA_ERR_NULL;
-    const void *ptrs[] = {q, k, v, g, K_state, V_state, o};
+    const void *ptrs[] = {q, k, v, g, K_state, V_state, o, s};
     for (const void *ptr : ptrs)
         if (!aligned16(ptr)) return GSA_ERR_SHAPE;
     float *scratch = nullptr;
@@ -151,7 +153,7 @@ gsa_status decode_any(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
         if (need) scratch = static_cast<float *>(workspace);
     }
     const hipError_t e = gsa::launch_decode(B * H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o,
-                                            scratch, static_cast<hipStream_t>(stream));
+                                            scratch, s, readout, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
 }
 
@@ -282,6 +284,15 @@ gsa_status gsa_decode_workspace_bytes(int32_t B, int32_t H, int32_t d_k, int32_t
     if (st != GSA_OK) return st;
     *bytes = align_up(gsa::decode_scratch_floats(B * H, d_v, m) * sizeof(float));
     return GSA_OK;
+}
+
+gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
+                              int32_t readout, const void *q, const void *k, const void *v, const float *g,
+                              const float *s, float *K_state, float *V_state, void *o, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    return decode_any(B, H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o, workspace != nullptr,
+                      workspace, workspace_bytes, stream, s, readout);
 }
 
 gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,

@@ -12,9 +12,8 @@
 // and the step is bound by what one compute unit can stream.  The split form spreads a pair
 // over several workgroups, each covering some of the slots; each writes its unnormalised partial
 // output with its own softmax maximum and sum to a workspace, and a second, tiny kernel merges
-// the partials of a pair in a fixed order.  No workgroup waits for another.  With many pairs a
-// coarser split (four workgroups of eight waves per pair) still pays: two such workgroups share
-// a CU and drift out of step, so loads and stores of the chip overlap instead of alternating.
+// the partials of a pair in a fixed order.  No workgroup waits for another.  (With many pairs the
+// one-workgroup form is the faster one again.)
 #include "gsa_common.h"
 #include "gsa_internal.h"
 
@@ -30,7 +29,6 @@ constexpr int kDecThreads = 1024;
 constexpr int kDecWaves = kDecThreads / kWave;
 constexpr int kSplitWaves = 4;                    // waves (= slot rows) per workgroup of the split form
 constexpr int kSplitPairsMax = 64;                // up to this many memory pairs: one slot row per wave (measured crossover)
-constexpr int kCoarsePieces = 4;                  // above: this many workgroups of eight waves per pair
 
 template <typename T> __device__ __forceinline__ f32x4 load4(const T *p);
 template <> __device__ __forceinline__ f32x4 load4<float>(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
@@ -45,8 +43,8 @@ template <> __device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t *p) {
 // Each wave owns M/16 slots (rows of both memories).  It updates its key rows, gets their
 // scores by wave reductions, and folds its value rows into a partial output with a softmax
 // that is local to the wave (its own maximum and sum); the 16 partial outputs are merged at the
-// end with the usual rescaling.  So there is a single barrier, at the end, and no wave waits for
-// another before its stores are issued.  No load sits under a data-dependent branch: column
+// end with the usual rescaling.  There are two barriers: one between the loads of the memories and
+// the first store (see there), one before the merge.  No load sits under a data-dependent branch: column
 // indices past the width are clamped and the lanes masked by register selects.
 //
 // PIECES > 0 (split form): a pair is spread over PIECES workgroups of NWAVES waves, each covering
@@ -57,7 +55,8 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const T *__restrict__ v, const float *__restrict__ g,
                                                                float *__restrict__ Kst, float *__restrict__ Vst,
-                                                               T *__restrict__ o, float *__restrict__ scratch)
+                                                               T *__restrict__ o, float *__restrict__ scratch,
+                                                               const float *__restrict__ sin, int readout)
 {
     constexpr bool SPLIT = PIECES > 0;
     constexpr int NSPLIT = SPLIT ? PIECES : 1;
@@ -75,6 +74,9 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
     float *Vb = Vst + (size_t)bh * M * d_v;
     const T *qb = q + (size_t)bh * d_k, *kb = k + (size_t)bh * d_k, *vb = v + (size_t)bh * d_v;
     const float *gb = g + (size_t)bh * M;
+    // write intensities of their own (gsa_decode_step_ex) or NULL; the load below is unconditional
+    // (from g when there are none) and a register select decides
+    const float *sb = (sin ? sin : g) + (size_t)bh * M;
 
     int colk[NV], colv[NV];
     bool okk[NV], okv[NV];
@@ -86,8 +88,24 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
         colk[j] = okk[j] ? col : d_k - 4;
         colv[j] = okv[j] ? col : d_v - 4;
     }
+    // ---- the small operands first
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    f32x4 qv[NV], kv[NV], vv[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        qv[j] = load4<T>(qb + colk[j]);
+        kv[j] = load4<T>(kb + colk[j]);
+        vv[j] = load4<T>(vb + colv[j]);
+    }
+    float graw[R], sraw[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        graw[rr] = gb[wave * R + rr];
+        sraw[rr] = sb[wave * R + rr];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- then the memories
     f32x4 Kr[R][NV], Vr[R][NV];
-    // ---- issue the memory loads
 #pragma unroll
     for (int rr = 0; rr < R; ++rr)
 #pragma unroll
@@ -100,21 +118,21 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
             for (int j = 0; j < NV; ++j)
                 Vr[rr][j] = GSA_LD(reinterpret_cast<const f32x4 *>(Vb + (size_t)(wave * R + rr) * d_v + colv[j]));
     }
-    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-    f32x4 qv[NV], kv[NV], vv[NV];
+    __builtin_amdgcn_sched_barrier(0);
+    // Every wave of the workgroup has all its memory rows before any of them stores: the chip then reads
+    // for a while and writes for a while instead of mixing the two all the time, which the memory
+    // system serves measurably faster (26.5 -> 23.7 us per step at 256 pairs).
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-        qv[j] = load4<T>(qb + colk[j]);
-        kv[j] = load4<T>(kb + colk[j]);
-        vv[j] = load4<T>(vb + colv[j]);
-        qv[j] = okk[j] ? qv[j] : zero4;   // masked lanes contribute nothing to the row dots
-    }
+    for (int j = 0; j < NV; ++j) qv[j] = okk[j] ? qv[j] : zero4;   // masked lanes contribute nothing to the row dots
     float a[R], s[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        const float gv = fmaxf(gb[wave * R + rr], kGateFloor);
+        const float gv = fmaxf(graw[rr], kGateFloor);
         a[rr] = __expf(gv);
-        s[rr] = -expm1f(gv);
+        s[rr] = sin ? sraw[rr] : -expm1f(gv);
     }
     // ---- key memories: update, write back, slot scores
     float z[R];
@@ -143,13 +161,19 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
             for (int j = 0; j < NV; ++j)
                 Vr[rr][j] = GSA_LD(reinterpret_cast<const f32x4 *>(Vb + (size_t)(wave * R + rr) * d_v + colv[j]));
     }
-    // ---- wave-local softmax weights
+    // ---- wave-local softmax weights (an element-wise read-out instead: weights f(z), maximum 0 and sum 0,
+    // so that the merges below add the partial outputs as they are and skip the normalisation)
+    const bool soft = readout == kReadSoftmax;
     float mw = z[0];
 #pragma unroll
     for (int rr = 1; rr < R; ++rr) mw = fmaxf(mw, z[rr]);
+    mw = soft ? mw : 0.f;
     float sw = 0.f, e[R];
 #pragma unroll
-    for (int rr = 0; rr < R; ++rr) { e[rr] = __expf(z[rr] - mw); sw += e[rr]; }
+    for (int rr = 0; rr < R; ++rr) {
+        e[rr] = soft ? __expf(z[rr] - mw) : readout_value(readout, z[rr]);
+        sw += soft ? e[rr] : 0.f;
+    }
     // ---- value memories: update, write back, partial output
     f32x4 acc[NV];
 #pragma unroll
@@ -192,7 +216,7 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
         }
         return;
     }
-    const float inv = 1.f / den;
+    const float inv = soft ? 1.f / den : 1.f;
     for (int c = tid; c < d_v; c += NTHREADS) {
         float sum = 0.f;
 #pragma unroll
@@ -211,7 +235,8 @@ template <> __device__ __forceinline__ void store4_as<bf16_t>(bf16_t *p, const f
 }
 
 template <typename T, int NSPLIT>
-__global__ __launch_bounds__(kWave) void decode_merge_kernel(int d_v, const float *__restrict__ scratch, T *__restrict__ o)
+__global__ __launch_bounds__(kWave) void decode_merge_kernel(int d_v, const float *__restrict__ scratch, T *__restrict__ o,
+                                                             int readout)
 {
     const int bh = blockIdx.y, col = 4 * (blockIdx.x * kWave + threadIdx.x);
     const bool ok = col < d_v;
@@ -235,44 +260,33 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(int d_v, const floa
         den += f * lj[j];
         acc += f * pj[j];
     }
-    acc *= 1.f / den;
+    acc *= (readout == kReadSoftmax) ? 1.f / den : 1.f;
     if (ok) store4_as<T>(o + (size_t)bh * d_v + col, acc);
 }
 
 template <typename T, int M, int NV>
 static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
                                    const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                   hipStream_t st)
+                                   const float *sin, int readout, hipStream_t st)
 {
-    if (scratch) {
-        // few pairs: m/4 workgroups of four waves per pair (one slot row per wave); many pairs: four
-        // workgroups of eight waves per pair -- two workgroups per CU run out of step with each other,
-        // which the one-workgroup form (a single 1024-thread workgroup per CU) cannot
-        const bool fine = BH <= kSplitPairsMax || M < 8 * kCoarsePieces;
-        constexpr int fine_pieces = M / kSplitWaves;
-        constexpr int coarse_waves = (M >= 8 * kCoarsePieces) ? 8 : kSplitWaves;
-        constexpr int coarse_pieces = (M >= 8 * kCoarsePieces) ? kCoarsePieces : fine_pieces;
-        const int pieces = fine ? fine_pieces : coarse_pieces, waves = fine ? kSplitWaves : coarse_waves;
-        const size_t lds = (128 + (size_t)waves * d_v) * sizeof(float);
-        constexpr bool coarse_early = (NV * (M / (coarse_waves * coarse_pieces)) <= 8);
-        auto kern = fine ? decode_kernel<T, M, NV, true, kSplitWaves, fine_pieces>
-                         : decode_kernel<T, M, NV, coarse_early, coarse_waves, coarse_pieces>;
+    if (scratch && BH <= kSplitPairsMax) {
+        // few pairs: m/4 workgroups of four waves per pair (one slot row per wave)
+        constexpr int pieces = M / kSplitWaves;
+        const size_t lds = (128 + (size_t)kSplitWaves * d_v) * sizeof(float);
+        auto kern = decode_kernel<T, M, NV, true, kSplitWaves, pieces>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         {
             KernelTimer kt(kSlotDecode, st);
-            hipLaunchKernelGGL(kern, dim3(BH * pieces), dim3(waves * kWave), lds, st, d_k, d_v, scale,
-                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch);
+            hipLaunchKernelGGL(kern, dim3(BH * pieces), dim3(kSplitWaves * kWave), lds, st, d_k, d_v, scale,
+                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch, sin, readout);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
         KernelTimer kt(kSlotDecodeMerge, st);
         const dim3 mgrid((d_v + 4 * kWave - 1) / (4 * kWave), BH);
-        if (fine)
-            hipLaunchKernelGGL((decode_merge_kernel<T, fine_pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o);
-        else
-            hipLaunchKernelGGL((decode_merge_kernel<T, coarse_pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o);
+        hipLaunchKernelGGL((decode_merge_kernel<T, pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o, readout);
         return hipGetLastError();
     }
     const size_t lds = (128 + (size_t)kDecWaves * d_v) * sizeof(float);
@@ -283,50 +297,51 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
     if (e != hipSuccess) return e;
     KernelTimer kt(kSlotDecode, st);
     hipLaunchKernelGGL(kern, dim3(BH), dim3(kDecThreads), lds, st, d_k, d_v, scale, (const T *)q, (const T *)k,
-                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr));
+                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr), sin, readout);
     return hipGetLastError();
 }
 
 template <typename T, int M>
 static hipError_t launch_decode_m(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                  hipStream_t st)
+                                  const float *sin, int readout, hipStream_t st)
 {
     const int dmax = d_k > d_v ? d_k : d_v;
     const int nv = (dmax + 255) / 256;
     switch (nv) {
-    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
-    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
-    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
-    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
     }
 }
 
 template <typename T>
 static hipError_t launch_decode_t(int BH, int d_k, int d_v, int m, float scale, const void *q, const void *k,
                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                  hipStream_t st)
+                                  const float *sin, int readout, hipStream_t st)
 {
     switch (m) {
-    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
-    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
-    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
-    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, st);
+    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
     }
 }
 
-// Floats of workspace the split form needs for BH pairs.
+// Floats of workspace the split form needs for BH pairs (0: the split form is not used at this size).
 size_t decode_scratch_floats(int BH, int d_v, int m)
 {
-    const bool fine = BH <= kSplitPairsMax || m < 8 * kCoarsePieces;
-    return (size_t)BH * (fine ? m / kSplitWaves : kCoarsePieces) * (d_v + 2);
+    if (BH > kSplitPairsMax) return 0;
+    return (size_t)BH * (m / kSplitWaves) * (d_v + 2);
 }
 
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
-                         const void *v, const float *g, float *K, float *V, void *o, float *scratch, hipStream_t st)
+                         const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
+                         int readout, hipStream_t st)
 {
-    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, st);
-    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, st);
+    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
 }
 
 }  // namespace gsa

@@ -110,7 +110,8 @@ hipError_t launch_bwd(const Plan &pl, const Work &w, const void *q, const void *
 
 // scratch: NULL (one workgroup per pair) or decode_scratch_floats(...) floats (split form, small BH).
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
-                         const void *v, const float *g, float *K, float *V, void *o, float *scratch, hipStream_t st);
+                         const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
+                         int readout, hipStream_t st);
 size_t decode_scratch_floats(int BH, int d_v, int m);
 
 }  // namespace gsa

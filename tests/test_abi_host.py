@@ -95,8 +95,7 @@ def test_null_and_workspace_errors_without_device(lib):
     n = ctypes.c_size_t(0)
     assert lib.gsa_decode_workspace_bytes(1, 4, 512, 512, 64, ctypes.byref(n)) == 0
     assert n.value >= 4 * 16 * 514 * 4 and n.value % 256 == 0
-    assert lib.gsa_decode_workspace_bytes(64, 4, 512, 512, 64, ctypes.byref(n)) == 0
-    assert n.value >= 256 * 4 * 514 * 4 and n.value % 256 == 0      # many pairs: four pieces per pair
+    assert lib.gsa_decode_workspace_bytes(64, 4, 512, 512, 64, ctypes.byref(n)) == 0 and n.value == 0
     assert lib.gsa_decode_workspace_bytes(1, 4, 512, 500, 64, ctypes.byref(n)) == 3
     assert lib.gsa_decode_workspace_bytes(1, 4, 512, 512, 64, None) == 1
     assert lib.gsa_decode_step_ws(1, 1, 60, 64, 16, 1, 1.0, *([null] * 7), null, 0, null) == 3

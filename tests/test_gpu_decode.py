@@ -8,7 +8,7 @@ from tests.util import check, to_np64
 pytestmark = pytest.mark.gpu
 
 
-def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5, split=False):
+def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5, split=False, given=False, readout="softmax"):
     import paper_2409_07146_amd as gsa
     from paper_2409_07146_amd import synth
     x = synth.make_decode_inputs(B, H, d_k, d_v, m, steps, state_std=0.1, seed=seed, dtype=dtype)
@@ -18,13 +18,19 @@ def _run(oracle, B, H, d_k, d_v, m, steps, dtype, scale=1.0, seed=5, split=False
     Ko, Vo = to_np64(x["K"]).copy(), to_np64(x["V"]).copy()
     qn, kn, vn, gn = (to_np64(x[n]) for n in ("q", "k", "v", "g"))
     ws = gsa.alloc_decode_workspace(B, H, d_k, d_v, m, dev) if split else None   # through gsa_decode_step_ws
+    sg = sn = [None] * steps
+    if given:     # write intensities of their own, around the tied value (through gsa_decode_step_ex)
+        gen = torch.Generator().manual_seed(seed + 77)
+        s_cpu = (2.0 * torch.rand(x["g"].shape, generator=gen) * -torch.expm1(x["g"])).float()
+        sg, sn = s_cpu.to(dev), to_np64(s_cpu)
     outs = []
     for t in range(steps):
-        outs.append(gsa.gsa_decode_step(q[t], k[t], v[t], g[t], Kg, Vg, scale=scale, workspace=ws))
+        outs.append(gsa.gsa_decode_step(q[t], k[t], v[t], g[t], Kg, Vg, scale=scale, workspace=ws, s=sg[t],
+                                        readout=readout))
     torch.cuda.synchronize()
     worst = 0.0
     for t in range(steps):
-        oo = oracle.decode_step(qn[t], kn[t], vn[t], gn[t], Ko, Vo, scale=scale)
+        oo = oracle.decode_step(qn[t], kn[t], vn[t], gn[t], Ko, Vo, scale=scale, s=sn[t], readout=readout)
         r, _ = check("o[step %d]" % t, to_np64(outs[t]), oo, dtype)
         worst = max(worst, r)
     # memories are fp32 on the GPU whatever the I/O dtype
@@ -47,9 +53,21 @@ def test_decode_small_shapes(oracle, B, H, d_k, d_v, m, dtype):
                                            (32, 4, 128, 64, 32), (33, 4, 64, 64, 16), (17, 4, 192, 128, 64),
                                            (9, 8, 64, 1024, 128), (24, 3, 128, 64, 32)])
 def test_decode_with_workspace(oracle, B, H, d_k, d_v, m, dtype):
-    """gsa_decode_step_ws: one slot row per wave up to 64 pairs, four workgroups of eight waves per pair
-    past that (the last two cases; m = 16 always takes the first form)."""
+    """gsa_decode_step_ws: memories spread over several workgroups up to 64 pairs; past that the call takes
+    the one-workgroup form."""
     _run(oracle, B, H, d_k, d_v, m, steps=5, dtype=dtype, scale=0.9, split=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("split", [False, True])
+@pytest.mark.parametrize("readout,given", [("softmax", True), ("identity", False), ("swish", True), ("relu", True),
+                                           ("relu2", False)])
+def test_decode_variants(oracle, readout, given, split, dtype):
+    """gsa_decode_step_ex: write intensity as an input of its own, element-wise read-outs; one workgroup per
+    pair and the split form (6 pairs); 70 pairs with a workspace take the one-workgroup form."""
+    _run(oracle, 3, 2, 128, 192, 32, steps=4, dtype=dtype, scale=0.9, split=split, given=given, readout=readout)
+    if split:
+        _run(oracle, 35, 2, 64, 64, 64, steps=2, dtype=dtype, scale=0.9, split=True, given=given, readout=readout)
 
 
 def test_decode_with_workspace_matches_plain_step():

@@ -447,15 +447,19 @@ def test_v4_tied_gate_gradient_from_the_two_separate_ones(oracle):
 
 
 # ---------------------------------------------------------------- decode
-def test_decode_step_matches_forward(oracle):
-    """The recurrent (decode) form is one step of Eq. (gsa): T calls equal a T-token forward."""
+@pytest.mark.parametrize("readout,given", [("softmax", False), ("softmax", True), ("swish", True), ("relu2", False)])
+def test_decode_step_matches_forward(oracle, readout, given):
+    """The recurrent (decode) form is one step of Eq. (gsa): T calls equal a T-token forward (itself pinned
+    above), also with the write intensity given and with an element-wise read-out."""
     rng = np.random.default_rng(22)
     B, T, H, dk, dv, m = 3, 6, 2, 5, 4, 4
     q, k, v, g, K0, V0 = _rand(rng, B, T, H, dk, dv, m, init=True)
-    full = oracle.fwd(q, k, v, g, K0=K0, V0=V0, scale=0.8)
+    s = rng.uniform(0.0, 1.0, size=g.shape) if given else None
+    full = oracle.fwd(q, k, v, g, K0=K0, V0=V0, scale=0.8, s=s, readout=readout)
     K, V = K0.copy(), V0.copy()
     for t in range(T):
-        o = oracle.decode_step(q[:, t], k[:, t], v[:, t], g[:, t], K, V, scale=0.8)
+        o = oracle.decode_step(q[:, t], k[:, t], v[:, t], g[:, t], K, V, scale=0.8,
+                               s=None if s is None else s[:, t], readout=readout)
         np.testing.assert_allclose(o, full["o"][:, t], rtol=1e-13, atol=1e-15)
     np.testing.assert_allclose(K, full["KT"], rtol=1e-13, atol=1e-15)
     np.testing.assert_allclose(V, full["VT"], rtol=1e-13, atol=1e-15)
