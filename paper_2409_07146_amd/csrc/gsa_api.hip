@@ -62,8 +62,8 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     {
         const int64_t max_nch = ((int64_t)p->T + pl->chunk - 1) / pl->chunk;
         const int64_t nseg = (max_nch + gsa::kSegChunks - 1) / gsa::kSegChunks;
-        const int64_t wgs = (int64_t)pl->n_seqs * p->H * ((dk + dv) / 64) * nseg;
-        const bool on = max_nch > gsa::kSegChunks + gsa::kSegChunks / 2 && wgs <= 8192;
+        const int64_t base = (int64_t)pl->n_seqs * p->H * ((dk + dv) / 64);   // workgroups of an unsegmented scan
+        const bool on = max_nch > gsa::kSegChunks + gsa::kSegChunks / 2 && base < 512 && base * nseg <= 8192;
         pl->seg_chunks = gsa::kSegChunks;
         pl->max_seg = on ? (int32_t)nseg : 1;
     }
