@@ -185,6 +185,18 @@ gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, in
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The decode step (Eq. (gsa), decode form) with the options of gsa_fwd_ex (Algorithm 1's
+ * separate write intensity; the read-outs of Section 4's ablation table): s [B,H,m] fp32
+ * or NULL, readout a gsa_readout.  workspace may be NULL (then the call behaves like
+ * gsa_decode_step) or as for gsa_decode_step_ws.
+ */
+gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
+                              int32_t dtype, float scale, int32_t readout,
+                              const void *q, const void *k, const void *v, const float *g, const float *s,
+                              float *K_state, float *V_state, void *o,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Per-kernel timing for roofline measurements (diagnostics; not part of the operator).
  * While enabled, every kernel the library launches is bracketed by a pair of HIP events
  * recorded on the caller's stream.  gsa_profile_read waits for the recorded events and
@@ -200,23 +212,11 @@ gsa_status gsa_profile_read(int32_t index, const char **name, double *ms, int64_
 /*
  * Bandwidth probe: copies `bytes` (a multiple of 16) from device memory `src` to device
  * memory `dst` (both 16-byte aligned, not overlapping) with one plain kernel
- * ("copy_probe_kernel") on `stream`.  It reads and writes exactly `bytes` each, which makes
+ * ("copy_probe_kernel", streaming loads and stores) on `stream`.  It reads and writes exactly `bytes` each, which makes
  * it the yardstick for hardware memory counters and for the copy rate this chip sustains.
  * Timed in slot "copy_probe_kernel" while profiling is enabled.
  */
 gsa_status gsa_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/*
- * The decode step with the options of gsa_fwd_ex: s [B,H,m] fp32 or NULL (write
- * intensity as an input of its own), readout a gsa_readout.  workspace may be
- * NULL (then the call behaves like gsa_decode_step) or as for
- * gsa_decode_step_ws.
- */
-gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
-                              int32_t dtype, float scale, int32_t readout,
-                              const void *q, const void *k, const void *v, const float *g, const float *s,
-                              float *K_state, float *V_state, void *o,
-                              void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }
