@@ -188,3 +188,33 @@ def test_fwd_bwd_packed_long_and_short_sequences(oracle):
                     cu_seqlens=(0, 2530, 2630, 2630, 4150), seed=72)
     x, got = run_fwd_bwd(cfg, with_state_grads=True)
     compare_bwd(oracle, cfg, x, got)
+
+
+def _random_config(seed):
+    from paper_2409_07146_amd.synth import GsaConfig
+    rng = np.random.default_rng(seed)
+    dtype = ["bf16", "f32"][int(rng.integers(2))]
+    m = int(rng.choice([16, 32, 64, 128]))
+    d_k, d_v = (int(64 * rng.integers(1, 4)) for _ in range(2))
+    H = int(rng.integers(1, 4))
+    init = float(rng.choice([0.0, 0.1]))   # memories as in the decode workload: N(0, 0.1^2)
+    if rng.integers(2):   # packed: a few sequences of random lengths, some of them empty
+        lens = [int(x) for x in rng.integers(0, 260, size=int(rng.integers(1, 5)))]
+        if rng.integers(2):
+            lens.insert(int(rng.integers(len(lens) + 1)), 0)
+        if sum(lens) == 0:
+            lens[0] = 37
+        cu = tuple(int(x) for x in np.concatenate([[0], np.cumsum(lens)]))
+        return GsaConfig("rand%d" % seed, B=1, T=cu[-1], H=H, d_k=d_k, d_v=d_v, m=m, dtype=dtype,
+                         init_state_std=init, cu_seqlens=cu, seed=100 + seed)
+    return GsaConfig("rand%d" % seed, B=int(rng.integers(1, 4)), T=int(rng.integers(1, 300)), H=H, d_k=d_k, d_v=d_v,
+                     m=m, dtype=dtype, init_state_std=init, seed=100 + seed)
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_fwd_bwd_random_shapes(oracle, seed):
+    """Seeded random problems: dtype, slots, head dimensions, heads, batch or packed (with empty sequences),
+    lengths that are not multiples of anything, with and without initial memories and final-memory gradients."""
+    cfg = _random_config(seed)
+    x, got = run_fwd_bwd(cfg, scale=float(0.5 + (seed % 4) * 0.25), with_state_grads=bool(seed % 2))
+    compare_bwd(oracle, cfg, x, got, scale=float(0.5 + (seed % 4) * 0.25))
