@@ -107,3 +107,9 @@ def test_bad_readout_is_rejected():
     null = ctypes.c_void_p(None)
     assert lib.gsa_fwd_ex(ctypes.byref(p), 7, *([null] * 11), null, 0, null) == 2
     assert lib.gsa_bwd_ex(ctypes.byref(p), -1, *([null] * 18), null, 0, null) == 2
+
+
+def test_variant_on_a_long_sequence(oracle):
+    """Given write intensities and an element-wise read-out on a sequence the scans walk in segments."""
+    cfg, x = _inputs(1, 3300, 2, 64, 64, 16, "bf16", seed=65, given=True)
+    _run_and_compare(oracle, cfg, x, "swish")
