@@ -126,11 +126,17 @@ gsa_status gsa_bwd(const gsa_problem *p,
  *   readout how the slot scores z_t = scale*Kt_t q_t become the read weights:
  *           softmax over the slots (Eq. (gsa)), or element by element the
  *           identity, Swish z*sigmoid(z), ReLU, or ReLU squared.
+ *   gate_tau 0: g is the log gate, as in gsa_fwd.  > 0: g holds gate LOGITS u and
+ *           the log gate is logsigmoid(u) / gate_tau, i.e. the layer's
+ *           alpha = sigmoid(W x)^(1/tau) of Section 3.2 (tau = 8 in the paper)
+ *           evaluated inside the kernels; gsa_bwd_ex then returns in dg the
+ *           gradient with respect to the logits.
  *   gsa_bwd_ex: with s given, dg is the gradient through the decay alone and
  *           ds [B,T,H,m] fp32 (required then) receives the gradient of s; with
- *           s NULL, ds is not touched and dg is as in gsa_bwd.  The same s and
- *           readout must be passed to both calls.
- * Errors as for gsa_fwd/gsa_bwd; an unknown readout returns GSA_ERR_SHAPE.
+ *           s NULL, ds is not touched and dg is as in gsa_bwd.  The same s,
+ *           readout and gate_tau must be passed to both calls.
+ * Errors as for gsa_fwd/gsa_bwd; an unknown readout or a negative or NaN
+ * gate_tau returns GSA_ERR_SHAPE.
  * gsa_decode_step_ex (below) is the decode step with the same two options.
  */
 typedef enum {
@@ -138,13 +144,13 @@ typedef enum {
     GSA_READOUT_RELU2 = 4
 } gsa_readout;
 
-gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout,
+gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau,
                       const void *q, const void *k, const void *v, const float *g, const float *s,
                       const float *K0, const float *V0,
                       void *o, float *z_saved, float *KT, float *VT,
                       void *workspace, size_t workspace_bytes, void *stream);
 
-gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout,
+gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau,
                       const void *q, const void *k, const void *v, const float *g, const float *s,
                       const float *K0, const float *V0, const float *z_saved, const void *dO,
                       const float *dKT, const float *dVT,
@@ -187,11 +193,11 @@ gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, in
 /*
  * The decode step (Eq. (gsa), decode form) with the options of gsa_fwd_ex (Algorithm 1's
  * separate write intensity; the read-outs of Section 4's ablation table): s [B,H,m] fp32
- * or NULL, readout a gsa_readout.  workspace may be NULL (then the call behaves like
+ * or NULL, readout a gsa_readout, gate_tau as there.  workspace may be NULL (then the call behaves like
  * gsa_decode_step) or as for gsa_decode_step_ws.
  */
 gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
-                              int32_t dtype, float scale, int32_t readout,
+                              int32_t dtype, float scale, int32_t readout, float gate_tau,
                               const void *q, const void *k, const void *v, const float *g, const float *s,
                               float *K_state, float *V_state, void *o,
                               void *workspace, size_t workspace_bytes, void *stream);

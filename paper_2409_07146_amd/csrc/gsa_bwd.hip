@@ -59,7 +59,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
                                                               const T *__restrict__ S, StateLayout lay,
                                                               float *__restrict__ dz, float *__restrict__ dgf,
                                                               T *__restrict__ Wr, T *__restrict__ tAvT,
-                                                              const float *__restrict__ sin, int readout)
+                                                              const float *__restrict__ sin, int readout,
+                                                              float gate_tau)
 {
     using L = DzLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
                                reinterpret_cast<T *>(smem + L::oVt), L::lda,
                                reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
                                v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,
-                               (GEN && sin) ? sin + tokh * M : nullptr);
+                               (GEN && sin) ? sin + tokh * M : nullptr, gate_tau);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -205,6 +206,7 @@ template <typename T> struct IntraArgs {
     const float *sin;   // general form: write intensities, or NULL
     float *ds;          // general form: their gradient (with sin)
     int readout;
+    float gate_tau;     // general form: > 0 when g holds gate logits
 };
 
 template <typename T, int M, bool GEN>
@@ -362,7 +364,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
             if (lane < 16) carry[w * M + ni * 16 + lane] = x;   // read after the barriers of the reduction
         }
         // the loads of everything phase 2 needs from global memory land during the reduction
-        gp.load(a.g + tokh * M, (size_t)H * M, ci.len, tid, given ? a.sin + tokh * M : nullptr);
+        gp.load(a.g + tokh * M, (size_t)H * M, ci.len, tid, given ? a.sin + tokh * M : nullptr, GEN ? a.gate_tau : 0.f);
         sr.load(a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
         f32x4 own[NB];
         reduce_row_blocks<NW, NB, CI>(own, acc, reinterpret_cast<f32x4 *>(smem + L::oPf), lane, w);
@@ -562,11 +564,13 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
             const int t = part * TP + tt;
             if (t < ci.len) {
                 const size_t o = (tokh + (size_t)t * H) * M + i;
+                // gate logits in g: the gradient goes on to the logit, d logsigmoid(u)/tau / du
+                const float chain = (GEN && a.gate_tau > 0.f) ? log_gate_slope(a.g[o], a.gate_tau) : 1.f;
                 if (given) {
-                    a.dg[o] = Df[t * L::ldg + i] + off;
+                    a.dg[o] = chain * (Df[t * L::ldg + i] + off);
                     a.ds[o] = Pf[t * L::ldg + i];
                 } else {
-                    a.dg[o] = Df[t * L::ldg + i] + off - Pf[t * L::ldg + i];
+                    a.dg[o] = chain * (Df[t * L::ldg + i] + off - Pf[t * L::ldg + i]);
                 }
             }
         }
@@ -584,7 +588,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
 {
     const ChunkMap cm = make_chunk_map(pl, w);
     // 1. recompute the chunk-start memories (and the memories after the last token)
-    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, st));
+    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
     {
         const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
@@ -598,7 +602,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         KernelTimer kt(kSlotChunkDz, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_v, pl.scale, (const T *)v,
                            (const T *)dO, g, z, (const T *)w.S, pl.lay, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT, pl.s_in,
-                           (int)pl.readout);
+                           (int)pl.readout, pl.gate_tau);
         GSA_HIP_TRY(hipGetLastError());
     }
     // 3. reverse scan of the memory gradient
@@ -619,7 +623,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         a.tAvT = (const T *)w.tAvT;
         a.dg = dg;
         a.tB = (T *)w.tA; a.tBT = (T *)w.tBT; a.tA2T = (T *)w.tA2T; a.tDZe = (T *)w.tP; a.tSbe = (T *)w.tSbe;
-        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout;
+        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout; a.gate_tau = pl.gate_tau;
         KernelTimer kt(kSlotChunkIntra, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, a);
         GSA_HIP_TRY(hipGetLastError());

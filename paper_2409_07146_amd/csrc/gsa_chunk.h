@@ -131,7 +131,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
                                              float *Rb, f32x4 *Red, const T *X, const T *Y,
                                              size_t ldx, int d, const T *St, int len, int tid,
-                                             const float *sin = nullptr)
+                                             const float *sin = nullptr, float gate_tau = 0.f)
 {
     constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -187,7 +187,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
                 }
         }
         GatePrep<M, Geo<T>::NT, C, GEN> gp;
-        gp.load(g, gld, len, tid, sin);
+        gp.load(g, gld, len, tid, sin, gate_tau);
         f32x4 own[NB];
         reduce_row_blocks<NW, NB, CI>(own, acc, Red, lane, w);
 #pragma unroll

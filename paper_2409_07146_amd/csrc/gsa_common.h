@@ -346,8 +346,17 @@ __device__ __forceinline__ void seq_lookup(const ChunkMap &cm, int s, int &chunk
 // Rows t >= len are padded with g = 0.  Needs blockDim.x = NT threads, NT % M == 0,
 // C % (NT/M) == 0, and `tot` scratch of NT floats.  Ends with a __syncthreads().
 // ----------------------------------------------------------------------------
+// log gate from a gate logit: logsigmoid(u) / tau = -(log(1 + exp(-|u|)) + max(-u, 0)) / tau, and its slope
+__device__ __forceinline__ float log_gate_from_logit(float u, float tau)
+{
+    return -(log1pf(__expf(-fabsf(u))) + fmaxf(-u, 0.f)) / tau;
+}
+__device__ __forceinline__ float log_gate_slope(float u, float tau) { return 1.f / ((1.f + __expf(u)) * tau); }
+
 // GEN: the general form, in which the write intensity may come from an array of its own
-// (sin: [len][M] fp32, same layout as g; NULL = 1 - exp(g) as above).
+// (sin: [len][M] fp32, same layout as g; NULL = 1 - exp(g) as above), and the array g may hold gate
+// LOGITS u instead of log gates: with tau > 0 the log gate is logsigmoid(u) / tau, the layer's gate
+// alpha = sigmoid(W x)^(1/tau) of Section 3.2 (tau = 0: g is the log gate itself).
 template <int M, int NT, int C, bool GEN = false> struct GatePrep {
     static constexpr int P = NT / M;     // token partitions
     static constexpr int TP = C / P;     // tokens per partition
@@ -355,10 +364,13 @@ template <int M, int NT, int C, bool GEN = false> struct GatePrep {
     float gv[TP];
     float sv[GEN ? TP : 1];
     bool given = false;
+    float tau = 0.f;
     // Issues the loads (rows clamped into the chunk).  May be called well before finish() so that
     // other work hides the latency.
-    __device__ __forceinline__ void load(const float *g, size_t gld, int len, int tid, const float *sin = nullptr)
+    __device__ __forceinline__ void load(const float *g, size_t gld, int len, int tid, const float *sin = nullptr,
+                                         float gate_tau = 0.f)
     {
+        if (GEN) tau = gate_tau;
         const int i = tid % M, part = tid / M;
 #pragma unroll
         for (int tt = 0; tt < TP; ++tt) gv[tt] = g[(size_t)min(part * TP + tt, len - 1) * gld + i];
@@ -376,7 +388,9 @@ template <int M, int NT, int C, bool GEN = false> struct GatePrep {
 #pragma unroll
         for (int tt = 0; tt < TP; ++tt) {
             const int t = part * TP + tt;
-            const float x = (t < len) ? fmaxf(gv[tt], kGateFloor) : 0.f;
+            float graw = gv[tt];
+            if (GEN && tau > 0.f) graw = log_gate_from_logit(graw, tau);
+            const float x = (t < len) ? fmaxf(graw, kGateFloor) : 0.f;
             run += x;
             Gs[t * ldg + i] = run;
             float sx = -expm1f(x);
@@ -397,10 +411,10 @@ template <int M, int NT, int C, bool GEN = false> struct GatePrep {
 
 template <int M, int NT, int C, bool GEN = false>
 __device__ __forceinline__ void gate_prep(float *Gs, float *Ss, int ldg, float *tot, const float *g, size_t gld,
-                                          int len, int tid, const float *sin = nullptr)
+                                          int len, int tid, const float *sin = nullptr, float gate_tau = 0.f)
 {
     GatePrep<M, NT, C, GEN> gp;
-    gp.load(g, gld, len, tid, sin);
+    gp.load(g, gld, len, tid, sin, gate_tau);
     gp.finish(Gs, Ss, ldg, tot, len, tid);
 }
 

@@ -56,7 +56,8 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
                                                                const T *__restrict__ v, const float *__restrict__ g,
                                                                float *__restrict__ Kst, float *__restrict__ Vst,
                                                                T *__restrict__ o, float *__restrict__ scratch,
-                                                               const float *__restrict__ sin, int readout)
+                                                               const float *__restrict__ sin, int readout,
+                                                               float gate_tau)
 {
     constexpr bool SPLIT = PIECES > 0;
     constexpr int NSPLIT = SPLIT ? PIECES : 1;
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
     float a[R], s[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        const float gv = fmaxf(graw[rr], kGateFloor);
+        const float gv = fmaxf(gate_tau > 0.f ? log_gate_from_logit(graw[rr], gate_tau) : graw[rr], kGateFloor);
         a[rr] = __expf(gv);
         s[rr] = sin ? sraw[rr] : -expm1f(gv);
     }
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(int d_v, const floa
 template <typename T, int M, int NV>
 static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
                                    const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                   const float *sin, int readout, hipStream_t st)
+                                   const float *sin, int readout, float gate_tau, hipStream_t st)
 {
     if (scratch && BH <= kSplitPairsMax) {
         // few pairs: m/4 workgroups of four waves per pair (one slot row per wave)
@@ -280,7 +281,8 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
         {
             KernelTimer kt(kSlotDecode, st);
             hipLaunchKernelGGL(kern, dim3(BH * pieces), dim3(kSplitWaves * kWave), lds, st, d_k, d_v, scale,
-                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch, sin, readout);
+                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch, sin, readout,
+                               gate_tau);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
@@ -297,35 +299,35 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
     if (e != hipSuccess) return e;
     KernelTimer kt(kSlotDecode, st);
     hipLaunchKernelGGL(kern, dim3(BH), dim3(kDecThreads), lds, st, d_k, d_v, scale, (const T *)q, (const T *)k,
-                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr), sin, readout);
+                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr), sin, readout, gate_tau);
     return hipGetLastError();
 }
 
 template <typename T, int M>
 static hipError_t launch_decode_m(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                  const float *sin, int readout, hipStream_t st)
+                                  const float *sin, int readout, float gate_tau, hipStream_t st)
 {
     const int dmax = d_k > d_v ? d_k : d_v;
     const int nv = (dmax + 255) / 256;
     switch (nv) {
-    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
     }
 }
 
 template <typename T>
 static hipError_t launch_decode_t(int BH, int d_k, int d_v, int m, float scale, const void *q, const void *k,
                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                  const float *sin, int readout, hipStream_t st)
+                                  const float *sin, int readout, float gate_tau, hipStream_t st)
 {
     switch (m) {
-    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
     }
 }
 
@@ -338,10 +340,10 @@ size_t decode_scratch_floats(int BH, int d_v, int m)
 
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
                          const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
-                         int readout, hipStream_t st)
+                         int readout, float gate_tau, hipStream_t st)
 {
-    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
-    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, st);
+    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
 }
 
 }  // namespace gsa

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
                                                                const T *__restrict__ S, StateLayout lay,
                                                                float *__restrict__ z_saved, T *__restrict__ tA,
                                                                T *__restrict__ tP, const float *__restrict__ sin,
-                                                               int readout)
+                                                               int readout, float gate_tau)
 {
     using L = ChunkFwdLds<T, M>;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
@@ -144,7 +144,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     T *Vt = reinterpret_cast<T *>(smem + L::oVt);
     float *Rb = reinterpret_cast<float *>(smem + L::oRb);
     gated_scores<T, M, C, GEN>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
-                               (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr);
+                               (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr,
+                               gate_tau);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
@@ -262,7 +263,7 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
                                 float *VT, hipStream_t st)
 {
     const ChunkMap cm = make_chunk_map(pl, w);
-    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, st));
+    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
     {
         const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
@@ -275,7 +276,7 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
         KernelTimer kt(kSlotChunkFwd, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.scale, (const T *)q,
                            (const T *)k, g, (const T *)w.S, pl.lay, z_saved, (T *)w.tA, (T *)w.tP, pl.s_in,
-                           (int)pl.readout);
+                           (int)pl.readout, pl.gate_tau);
         GSA_HIP_TRY(hipGetLastError());
     }
     const ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v};

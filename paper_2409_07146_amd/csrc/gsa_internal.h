@@ -27,7 +27,8 @@ struct Plan {
     const float *s_in = nullptr;   // [B,T,H,m] device, or NULL for s = 1 - exp(g)
     float *ds_out = nullptr;       // backward: gradient of s_in
     int32_t readout = 0;           // Readout
-    bool general() const { return s_in != nullptr || readout != 0; }
+    float gate_tau = 0.f;          // > 0: g holds gate logits, the log gate is logsigmoid(g) / gate_tau
+    bool general() const { return s_in != nullptr || readout != 0 || gate_tau > 0.f; }
 };
 
 // Workspace views handed to the launchers.
@@ -73,7 +74,7 @@ private:
 hipError_t launch_prepare(const Plan &pl, const Work &w, hipStream_t st);
 
 // Forward-scan weights and chunk decays from the log gates (chunk-parallel).
-hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, const float *sin, hipStream_t st);
+hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, const float *sin, float tau, hipStream_t st);
 
 // One scan over the chunks of every sequence.  Forward: x = (k, v), init = (K0, V0), snapshots go
 // to Work::S, weights come from Work::Wf.  Reverse: x = (q, dO), init = (dKT, dVT), snapshots go
@@ -111,7 +112,7 @@ hipError_t launch_bwd(const Plan &pl, const Work &w, const void *q, const void *
 // scratch: NULL (one workgroup per pair) or decode_scratch_floats(...) floats (split form, small BH).
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
                          const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
-                         int readout, hipStream_t st);
+                         int readout, float gate_tau, hipStream_t st);
 size_t decode_scratch_floats(int BH, int d_v, int m);
 
 }  // namespace gsa

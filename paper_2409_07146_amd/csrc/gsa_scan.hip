@@ -28,8 +28,8 @@ namespace gsa {
 // ---------------------------------------------------------------------------------------
 template <typename T, int M, bool GEN>
 __global__ __launch_bounds__(Geo<T>::NT) void gate_kernel(ChunkMap cm, int H, const float *__restrict__ g,
-                                                          const float *__restrict__ sin, T *__restrict__ Wf,
-                                                          float *__restrict__ dec)
+                                                          const float *__restrict__ sin, float gate_tau,
+                                                          T *__restrict__ Wf, float *__restrict__ dec)
 {
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
     constexpr int ldg = M + 1;   // odd row stride: the column reads below spread over all banks
@@ -41,7 +41,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void gate_kernel(ChunkMap cm, int H, co
     const int h = blockIdx.y, tid = threadIdx.x;
     const size_t ch = (size_t)blockIdx.x * H + h;
     const size_t goff = ((size_t)ci.tok0 * H + h) * M;
-    gate_prep<M, NT, C, GEN>(Gs, Ss, ldg, tot, g + goff, (size_t)H * M, ci.len, tid, (GEN && sin) ? sin + goff : nullptr);
+    gate_prep<M, NT, C, GEN>(Gs, Ss, ldg, tot, g + goff, (size_t)H * M, ci.len, tid, (GEN && sin) ? sin + goff : nullptr,
+                             gate_tau);
     T *W = Wf + ch * M * C;
     for (int idx = tid; idx < M * C / 8; idx += NT) {   // eight consecutive tokens of one slot per thread
         const int i = idx / (C / 8), t8 = (idx - i * (C / 8)) * 8;
@@ -393,27 +394,28 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
 // Launchers
 // ---------------------------------------------------------------------------------------
 template <typename T, int M>
-static hipError_t launch_gates_tm(const Plan &pl, const Work &w, const float *g, const float *sin, hipStream_t st)
+static hipError_t launch_gates_tm(const Plan &pl, const Work &w, const float *g, const float *sin, float tau,
+                                  hipStream_t st)
 {
     const ChunkMap cm = make_chunk_map(pl, w);
     KernelTimer kt(kSlotGates, st);
-    if (sin)
+    if (sin || tau > 0.f)
         hipLaunchKernelGGL((gate_kernel<T, M, true>), dim3(pl.chunk_slots, pl.H), dim3(Geo<T>::NT), 0, st, cm, pl.H, g,
-                           sin, (T *)w.Wf, w.dec);
+                           sin, tau, (T *)w.Wf, w.dec);
     else
         hipLaunchKernelGGL((gate_kernel<T, M, false>), dim3(pl.chunk_slots, pl.H), dim3(Geo<T>::NT), 0, st, cm, pl.H, g,
-                           sin, (T *)w.Wf, w.dec);
+                           sin, 0.f, (T *)w.Wf, w.dec);
     return hipGetLastError();
 }
 
-hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, const float *sin, hipStream_t st)
+hipError_t launch_gates(const Plan &pl, const Work &w, const float *g, const float *sin, float tau, hipStream_t st)
 {
 #define GSA_GATES(T)                                                   \
     switch (pl.m) {                                                    \
-    case 16: return launch_gates_tm<T, 16>(pl, w, g, sin, st);         \
-    case 32: return launch_gates_tm<T, 32>(pl, w, g, sin, st);         \
-    case 128: return launch_gates_tm<T, 128>(pl, w, g, sin, st);       \
-    default: return launch_gates_tm<T, 64>(pl, w, g, sin, st);         \
+    case 16: return launch_gates_tm<T, 16>(pl, w, g, sin, tau, st);         \
+    case 32: return launch_gates_tm<T, 32>(pl, w, g, sin, tau, st);         \
+    case 128: return launch_gates_tm<T, 128>(pl, w, g, sin, tau, st);       \
+    default: return launch_gates_tm<T, 64>(pl, w, g, sin, tau, st);         \
     }
     if (pl.dtype == 0) { GSA_GATES(float) }
     GSA_GATES(bf16_t)

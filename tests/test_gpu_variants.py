@@ -105,11 +105,59 @@ def test_bad_readout_is_rejected():
     lib = _lib.load()
     p = _lib.GsaProblem(B=1, T=64, H=1, d_k=64, d_v=64, m=16, dtype=1, scale=1.0, cu_seqlens=None, n_seqs=0)
     null = ctypes.c_void_p(None)
-    assert lib.gsa_fwd_ex(ctypes.byref(p), 7, *([null] * 11), null, 0, null) == 2
-    assert lib.gsa_bwd_ex(ctypes.byref(p), -1, *([null] * 18), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 7, 0.0, *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_bwd_ex(ctypes.byref(p), -1, 0.0, *([null] * 18), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, -1.0, *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, float("nan"), *([null] * 11), null, 0, null) == 2
 
 
 def test_variant_on_a_long_sequence(oracle):
     """Given write intensities and an element-wise read-out on a sequence the scans walk in segments."""
     cfg, x = _inputs(1, 3300, 2, 64, 64, 16, "bf16", seed=65, given=True)
     _run_and_compare(oracle, cfg, x, "swish")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("readout,given", [("softmax", False), ("swish", True)])
+def test_gate_logits_evaluated_inside(oracle, readout, given, dtype):
+    """gate_tau > 0: the g argument holds gate logits u, the kernels use logsigmoid(u)/tau (the layer's
+    alpha = sigmoid(W x)^(1/tau), Section 3.2) and dg comes back as the gradient with respect to u.  The oracle
+    gets the log gate computed here in fp64, and its dg goes through the chain rule here as well."""
+    import paper_2409_07146_amd as gsa
+    from scipy.special import expit, log_expit
+    tau = 8.0
+    cfg, x = _inputs(2, 150, 2, 128, 64, 32, dtype, seed=66, given=given)
+    gen = torch.Generator().manual_seed(67)
+    u = (torch.randn(x["g"].shape, generator=gen) * 2.0).float()
+    g64 = log_expit(to_np64(u)) / tau
+    if given:
+        x["s"] = (2.0 * torch.rand(u.shape, generator=gen) * -torch.expm1(torch.from_numpy(g64).float())).float()
+    dev = torch.device(DEV)
+    put = lambda t: None if t is None else t.to(dev)
+    d = {n: put(x[n]) for n in ("q", "k", "v", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    ud = u.to(dev)
+    o, z, KT, VT = gsa.gsa_fwd(d["q"], d["k"], d["v"], ud, K0=d["K0"], V0=d["V0"], final_state=True, s=d["s"],
+                               readout=readout, gate_tau=tau)
+    res = gsa.gsa_bwd(d["q"], d["k"], d["v"], ud, z, d["dO"], K0=d["K0"], V0=d["V0"], dKT=d["dKT"], dVT=d["dVT"],
+                      initial_state_grad=True, s=d["s"], readout=readout, gate_tau=tau)
+    torch.cuda.synchronize()
+    a = {n: (None if x[n] is None else to_np64(x[n])) for n in ("q", "k", "v", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    f = oracle.fwd(a["q"], a["k"], a["v"], g64, K0=a["K0"], V0=a["V0"], s=a["s"], readout=readout)
+    check("o", to_np64(o), f["o"], dtype)
+    check("KT", to_np64(KT), f["KT"], dtype)
+    r = oracle.bwd(a["q"], a["k"], a["v"], g64, a["dO"], K0=a["K0"], V0=a["V0"], dKT=a["dKT"], dVT=a["dVT"],
+                   s=a["s"], readout=readout)
+    r["dg"] = r["dg"] * (1.0 - expit(to_np64(u))) / tau
+    names = ["dq", "dk", "dv", "dg", "dK0", "dV0"] + (["ds"] if given else [])
+    for n, t in zip(names, res):
+        check(n, to_np64(t), r[n], dtype)
+    # decode step with the same option, continuing from the final memories
+    q1, k1, v1, u1 = (t[:, -1].contiguous() for t in (d["q"], d["k"], d["v"], ud))
+    s1 = None if d["s"] is None else d["s"][:, -1].contiguous()
+    Kc, Vc = KT.clone(), VT.clone()
+    o1 = gsa.gsa_decode_step(q1, k1, v1, u1, Kc, Vc, s=s1, readout=readout, gate_tau=tau)
+    Ko, Vo = f["KT"].copy(), f["VT"].copy()
+    oo = oracle.decode_step(a["q"][:, -1], a["k"][:, -1], a["v"][:, -1], g64[:, -1], Ko, Vo,
+                            s=None if a["s"] is None else a["s"][:, -1], readout=readout)
+    check("decode o", to_np64(o1), oo, dtype)
+    check("decode K", to_np64(Kc), Ko, dtype)
