@@ -50,7 +50,9 @@ template <> __device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t *p) {
 // PIECES > 0 (split form): a pair is spread over PIECES workgroups of NWAVES waves, each covering
 // M/PIECES slots (blockIdx.x = pair * PIECES + piece); instead of the output the workgroup writes to
 // `scratch`, per pair [PIECES][2] (maximum, sum) followed by [PIECES][d_v] (unnormalised partial output).
-template <typename T, int M, int NV, bool EARLY_V, int NWAVES, int PIECES>
+// GEN: the general form (write intensities from `sin` when given, read-out `readout`, gate logits with
+// gate_tau > 0); the plain calls run GEN = false, where none of this is compiled in.
+template <typename T, int M, int NV, bool EARLY_V, int NWAVES, int PIECES, bool GEN>
 __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const T *__restrict__ v, const float *__restrict__ g,
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
     const float *gb = g + (size_t)bh * M;
     // write intensities of their own (gsa_decode_step_ex) or NULL; the load below is unconditional
     // (from g when there are none) and a register select decides
-    const float *sb = (sin ? sin : g) + (size_t)bh * M;
+    const float *sb = ((GEN && sin) ? sin : g) + (size_t)bh * M;
 
     int colk[NV], colv[NV];
     bool okk[NV], okv[NV];
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         graw[rr] = gb[wave * R + rr];
-        sraw[rr] = sb[wave * R + rr];
+        sraw[rr] = GEN ? sb[wave * R + rr] : 0.f;
     }
     __builtin_amdgcn_sched_barrier(0);
     // ---- then the memories
@@ -131,9 +133,9 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
     float a[R], s[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        const float gv = fmaxf(gate_tau > 0.f ? log_gate_from_logit(graw[rr], gate_tau) : graw[rr], kGateFloor);
+        const float gv = fmaxf((GEN && gate_tau > 0.f) ? log_gate_from_logit(graw[rr], gate_tau) : graw[rr], kGateFloor);
         a[rr] = __expf(gv);
-        s[rr] = sin ? sraw[rr] : -expm1f(gv);
+        s[rr] = (GEN && sin) ? sraw[rr] : -expm1f(gv);
     }
     // ---- key memories: update, write back, slot scores
     float z[R];
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
     }
     // ---- wave-local softmax weights (an element-wise read-out instead: weights f(z), maximum 0 and sum 0,
     // so that the merges below add the partial outputs as they are and skip the normalisation)
-    const bool soft = readout == kReadSoftmax;
+    const bool soft = !GEN || readout == kReadSoftmax;
     float mw = z[0];
 #pragma unroll
     for (int rr = 1; rr < R; ++rr) mw = fmaxf(mw, z[rr]);
@@ -274,7 +276,9 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
         // few pairs: m/4 workgroups of four waves per pair (one slot row per wave)
         constexpr int pieces = M / kSplitWaves;
         const size_t lds = (128 + (size_t)kSplitWaves * d_v) * sizeof(float);
-        auto kern = decode_kernel<T, M, NV, true, kSplitWaves, pieces>;
+        const bool gen = sin != nullptr || readout != kReadSoftmax || gate_tau > 0.f;
+        auto kern = gen ? decode_kernel<T, M, NV, true, kSplitWaves, pieces, true>
+                        : decode_kernel<T, M, NV, true, kSplitWaves, pieces, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -293,7 +297,8 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
     }
     const size_t lds = (128 + (size_t)kDecWaves * d_v) * sizeof(float);
     constexpr bool early = (NV * (M / kDecWaves) <= 8);
-    auto kern = decode_kernel<T, M, NV, early, kDecWaves, 0>;
+    const bool gen = sin != nullptr || readout != kReadSoftmax || gate_tau > 0.f;
+    auto kern = gen ? decode_kernel<T, M, NV, early, kDecWaves, 0, true> : decode_kernel<T, M, NV, early, kDecWaves, 0, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
