@@ -47,7 +47,9 @@ template <typename T, int M> struct DzLds {
     static constexpr size_t oVt = oA + szA;                           // Vt [M][lda]
     static constexpr size_t oRb = oVt + sizeof(T) * M * lda;          // Rb [C/16][M] fp32
     static constexpr size_t end = oRb + sizeof(float) * (C / 16) * M;
-    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
+    static constexpr int kRpr = 2;                 // row blocks per round of the reduction
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) *
+                                    reduce_fragments<C / 16, C / 16 + M / 16, C / 16, kRpr>();   // from offset 0: dead before the tiles are written
     static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
 
     float dp[MI][4];
     bool unsafe;
-    gated_scores<T, M, C, GEN>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
+    gated_scores<T, M, C, GEN, L::kRpr>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
                                reinterpret_cast<T *>(smem + L::oVt), L::lda,
                                reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
                                v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,

@@ -44,31 +44,54 @@ __device__ __forceinline__ bool block_unsafe(const float *Gs, int ldg, int rowb,
 // Red: LDS, NW*NB*64 f32x4 (fragments are exchanged lane for lane, so any wave's layout
 // is every wave's layout).  w must be wave-uniform.  Contains barriers: all threads of the
 // workgroup must call it.
-template <int NW, int NB, int CAUSAL>
+// RPR row blocks are exchanged per round (RPR divides NW): fewer, fuller rounds need fewer barriers
+// and keep more waves busy adding, at the price of a larger buffer, reduce_fragments<..>() * NW * 64 f32x4.
+template <int NW, int NB, int CAUSAL, int RPR> constexpr int reduce_fragments()
+{
+    int worst = 0;
+    for (int rb0 = 0; rb0 < NW; rb0 += RPR) {
+        int n = 0;
+        for (int rb = rb0; rb < rb0 + RPR; ++rb)
+            for (int cb = 0; cb < NB; ++cb)
+                if (!(cb < CAUSAL && cb > rb)) ++n;
+        worst = n > worst ? n : worst;
+    }
+    return worst;
+}
+
+template <int NW, int NB, int CAUSAL, int RPR = 1>
 __device__ __forceinline__ void reduce_row_blocks(f32x4 (&own)[NB], const f32x4 (&acc)[NW][NB], f32x4 *Red, int lane,
                                                   int w)
 {
+    static_assert(NW % RPR == 0, "row blocks per round");
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) own[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // One round per row block: every wave posts its partial of that block, the block's owner adds
+    // Per round: every wave posts its partials of the round's row blocks, each block's owner adds
     // them in wave order.  (Register arrays are indexed by constants only; the wave index enters
-    // through LDS addresses.)
+    // through LDS addresses.)  Slot numbers count the posted fragments of a round in (rb, cb) order.
 #pragma unroll
-    for (int rb = 0; rb < NW; ++rb) {
+    for (int rb0 = 0; rb0 < NW; rb0 += RPR) {
+        int slot = 0;
 #pragma unroll
-        for (int cb = 0; cb < NB; ++cb)
-            if (!(cb < CAUSAL && cb > rb)) Red[(w * NB + cb) * kWave + lane] = acc[rb][cb];
+        for (int rb = rb0; rb < rb0 + RPR; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb)
+                if (!(cb < CAUSAL && cb > rb)) { Red[(slot * NW + w) * kWave + lane] = acc[rb][cb]; ++slot; }
         __syncthreads();
-        if (w == rb) {
+        slot = 0;
+#pragma unroll
+        for (int rb = rb0; rb < rb0 + RPR; ++rb)
 #pragma unroll
             for (int cb = 0; cb < NB; ++cb) {
                 if (cb < CAUSAL && cb > rb) continue;
-                f32x4 x = Red[cb * kWave + lane];
+                if (w == rb) {
+                    f32x4 x = Red[(slot * NW) * kWave + lane];
 #pragma unroll
-                for (int u = 1; u < NW; ++u) x += Red[(u * NB + cb) * kWave + lane];
-                own[cb] = x;
+                    for (int u = 1; u < NW; ++u) x += Red[(slot * NW + u) * kWave + lane];
+                    own[cb] = x;
+                }
+                ++slot;
             }
-        }
         __syncthreads();
     }
 }
@@ -126,7 +149,8 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // of build_write_tiles are left in Vt, Rb for the caller's own use.
 // All threads of the workgroup must call it.
 // GEN: general form; sin = write intensities [len][M] (layout of g) or NULL for 1 - exp(g).
-template <typename T, int M, int C, bool GEN = false>
+// RPR: row blocks per round of the reduction (Red must hold reduce_fragments<..., RPR>() * NW * 64 f32x4).
+template <typename T, int M, int C, bool GEN = false, int RPR = 1>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
                                              float *Rb, f32x4 *Red, const T *X, const T *Y,
@@ -189,7 +213,7 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
         GatePrep<M, Geo<T>::NT, C, GEN> gp;
         gp.load(g, gld, len, tid, sin, gate_tau);
         f32x4 own[NB];
-        reduce_row_blocks<NW, NB, CI>(own, acc, Red, lane, w);
+        reduce_row_blocks<NW, NB, CI, RPR>(own, acc, Red, lane, w);
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) accA[ni] = own[ni];
 #pragma unroll

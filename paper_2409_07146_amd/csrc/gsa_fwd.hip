@@ -103,7 +103,9 @@ template <typename T, int M> struct ChunkFwdLds {
     static constexpr size_t oVt = oP + sizeof(T) * C * ldp;           // Vt [M][lda]
     static constexpr size_t oRb = oVt + sizeof(T) * M * lda;          // Rb [C/16][M] fp32
     static constexpr size_t end = oRb + sizeof(float) * (C / 16) * M;
-    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // from offset 0: dead before the tiles are written
+    static constexpr int kRpr = 2;                 // row blocks per round of the reduction
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) *
+                                    reduce_fragments<C / 16, C / 16 + M / 16, C / 16, kRpr>();   // from offset 0: dead before the tiles are written
     static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     bool unsafe;
     T *Vt = reinterpret_cast<T *>(smem + L::oVt);
     float *Rb = reinterpret_cast<float *>(smem + L::oRb);
-    gated_scores<T, M, C, GEN>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
+    gated_scores<T, M, C, GEN, L::kRpr>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
                                (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr,
                                gate_tau);
     // ---- softmax over the slots, in registers
