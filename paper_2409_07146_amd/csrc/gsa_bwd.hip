@@ -192,8 +192,10 @@ template <typename T, int M> struct IntraLds {
     static constexpr size_t oTot = oAT;   // gate_prep's and the suffix sum's scratch (ATs is dead by then)
     static constexpr size_t szAT = sizeof(T) * C * lda > sizeof(float) * Geo<T>::NT ? sizeof(T) * C * lda
                                                                                    : sizeof(float) * Geo<T>::NT;
-    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) * (C / 16 + M / 16);   // aliases Pf, Df, ATs
-    static constexpr size_t oCarry = (oAT + szAT > oPf + szRed) ? oAT + szAT : oPf + szRed;
+    static constexpr int kRpr = 2;        // row blocks per round of the reduction
+    static constexpr size_t szRed = sizeof(f32x4) * kWave * (C / 16) *
+                                    reduce_fragments<C / 16, C / 16 + M / 16, C / 16, kRpr>();   // from offset 0: every tile is written after it
+    static constexpr size_t oCarry = (oAT + szAT > szRed) ? oAT + szAT : szRed;
     static constexpr size_t bytes = oCarry + sizeof(float) * (C / 16) * M;   // per-wave partial carries
 };
 
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
         gp.load(a.g + tokh * M, (size_t)H * M, ci.len, tid, given ? a.sin + tokh * M : nullptr, GEN ? a.gate_tau : 0.f);
         sr.load(a.z + tokh * M, a.dz + tokh * M, (size_t)H * M, ci.len, tid);
         f32x4 own[NB];
-        reduce_row_blocks<NW, NB, CI>(own, acc, reinterpret_cast<f32x4 *>(smem + L::oPf), lane, w);
+        reduce_row_blocks<NW, NB, CI, L::kRpr>(own, acc, reinterpret_cast<f32x4 *>(smem), lane, w);
 #pragma unroll
         for (int ni = 0; ni < CI; ++ni) accA[ni] = own[ni];
 #pragma unroll
