@@ -6,3 +6,4 @@ from .api import (GsaError, alloc_decode_workspace, alloc_workspace, gsa_bwd, gs
                   gsa_decode_workspace_bytes, gsa_fwd,
                   gsa_profile_copy, gsa_profile_enable, gsa_profile_read, gsa_profile_reset, gsa_workspace_bytes,
                   make_problem)
+from .autograd import gsa_attention  # noqa: F401,E402
