@@ -86,7 +86,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
 
     float dp[MI][4];
     bool unsafe;
-    gated_scores<T, M, C, GEN, L::kRpr>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
+    // dO is hinted; v and the chunk-start value memory are read again by chunk_intra and stay cached
+    gated_scores<T, M, C, GEN, L::kRpr, kHintX>(dp, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda,
                                reinterpret_cast<T *>(smem + L::oVt), L::lda,
                                reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
                                v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,
@@ -290,12 +291,14 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
         // key half: A = Q K^T, X += K E_k^T
         // (two passes over k, each in 64-column steps like the value half: together their operand
         // fragments would not fit the registers; the second read of k is served by the caches)
+        // Non-temporal loads for what is read here for the last time in this call (q, v, the chunk-end
+        // memories); k comes twice and the apply kernel right after reads E again, so those stay cached.
         for (int kk = 64 * w; kk < d_k; kk += 64 * NW) {
             Frag fq[2][CI], fk[2][CI];
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                for (int ni = 0; ni < CI; ++ni) fq[hh][ni] = Atom<T>::load(qb + tk[ni] + kk + 32 * hh);
+                for (int ni = 0; ni < CI; ++ni) fq[hh][ni] = Atom<T>::load_nt(qb + tk[ni] + kk + 32 * hh);
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load(SendK + ek[ni] + snap_col<M>(kk + 32 * hh));
+                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load_nt(SendK + ek[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
@@ -340,7 +343,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                for (int ni = 0; ni < CI; ++ni) fv[hh][ni] = Atom<T>::load(vb + tv[ni] + kk + 32 * hh);
+                for (int ni = 0; ni < CI; ++ni) fv[hh][ni] = Atom<T>::load_nt(vb + tv[ni] + kk + 32 * hh);
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -348,7 +351,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load(SendV + ev[ni] + snap_col<M>(kk + 32 * hh));
+                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load_nt(SendV + ev[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {

@@ -150,7 +150,11 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // All threads of the workgroup must call it.
 // GEN: general form; sin = write intensities [len][M] (layout of g) or NULL for 1 - exp(g).
 // RPR: row blocks per round of the reduction (Red must hold reduce_fragments<..., RPR>() * NW * 64 f32x4).
-template <typename T, int M, int C, bool GEN = false, int RPR = 1>
+// HINT: which operands are loaded with the non-temporal hint (kHintX | kHintY | kHintSt) -- those the
+// caller knows nobody reads again soon.  Both halves of every 128-byte line are asked for by the
+// same wave in the same step, so a hinted line is never dropped between its two readers.
+constexpr int kHintX = 1, kHintY = 2, kHintSt = 4;
+template <typename T, int M, int C, bool GEN = false, int RPR = 1, int HINT = 0>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
                                              float *Rb, f32x4 *Red, const T *X, const T *Y,
@@ -185,19 +189,19 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
             for (int hh = 0; hh < 2; ++hh) {
                 const int k0 = kk + 32 * hh;
 #pragma unroll
-                for (int ni = 0; ni < CI; ++ni) fx[hh][ni] = Atom<T>::load(X + xo[ni] + k0);
+                for (int ni = 0; ni < CI; ++ni) fx[hh][ni] = (HINT & kHintX) ? Atom<T>::load_nt(X + xo[ni] + k0) : Atom<T>::load(X + xo[ni] + k0);
             }
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
                 const int k0 = kk + 32 * hh;
 #pragma unroll
-                for (int ni = 0; ni < CI; ++ni) fy[hh][ni] = Atom<T>::load(Y + xo[ni] + k0);
+                for (int ni = 0; ni < CI; ++ni) fy[hh][ni] = (HINT & kHintY) ? Atom<T>::load_nt(Y + xo[ni] + k0) : Atom<T>::load(Y + xo[ni] + k0);
             }
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
                 const int k0 = kk + 32 * hh;
 #pragma unroll
-                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load(St + so[ni] + snap_col<M>(k0));
+                for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = (HINT & kHintSt) ? Atom<T>::load_nt(St + so[ni] + snap_col<M>(k0)) : Atom<T>::load(St + so[ni] + snap_col<M>(k0));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll

@@ -145,7 +145,10 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     bool unsafe;
     T *Vt = reinterpret_cast<T *>(smem + L::oVt);
     float *Rb = reinterpret_cast<float *>(smem + L::oRb);
-    gated_scores<T, M, C, GEN, L::kRpr>(p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb, reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
+    // q, k and the key memory are not read again by this forward call: all three hinted
+    gated_scores<T, M, C, GEN, L::kRpr, kHintX | kHintY | kHintSt>(
+        p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb,
+        reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
                                (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr,
                                gate_tau);
     // ---- softmax over the slots, in registers
