@@ -126,6 +126,9 @@ def main():
                     help="read-out variant (gsa_fwd_ex / gsa_bwd_ex); the headline is softmax")
     ap.add_argument("--given-intensity", action="store_true",
                     help="write intensities as an input of their own (gsa_fwd_ex / gsa_bwd_ex)")
+    ap.add_argument("--feature-map", default="none", choices=["none", "swish"],
+                    help="q, k, v as raw projections with the Swish feature map applied inside the kernels; also "
+                         "times the same work with the feature map as element-wise passes of their own")
     ap.add_argument("--decode-one-workgroup", action="store_true",
                     help="prefill_decode: use gsa_decode_step (one workgroup per memory) instead of gsa_decode_step_ws")
     args = ap.parse_args()
@@ -150,7 +153,7 @@ def main():
     ws = gsa.alloc_workspace(prob, True, dev)
 
     s_in = (-torch.expm1(g)).contiguous() if args.given_intensity else None
-    var = dict(s=s_in, readout=args.readout)
+    var = dict(s=s_in, readout=args.readout, feature_map=args.feature_map)
 
     def step():
         o, z, _, _ = gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws, **var)
@@ -167,6 +170,29 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens = cfg.tokens
     tok_s = tokens / (dt / args.steps)
+
+    # the same work with the feature map outside the operator: three element-wise passes before the
+    # forward, three through the slope after the backward (torch's kernels; a comparison leg only)
+    outside_ms = None
+    if args.feature_map != "none":
+        var0 = dict(var, feature_map="none")
+        F = torch.nn.functional
+
+        def step_outside():
+            pq, pk, pv = F.silu(q), F.silu(k), F.silu(v)
+            o, z, _, _ = gsa.gsa_fwd(pq, pk, pv, g, cu_seqlens=cu, workspace=ws, **var0)
+            r = gsa.gsa_bwd(pq, pk, pv, g, z, dO, cu_seqlens=cu, workspace=ws, **var0)
+            return (torch.ops.aten.silu_backward(r[0], q), torch.ops.aten.silu_backward(r[1], k),
+                    torch.ops.aten.silu_backward(r[2], v))
+
+        for _ in range(args.warmup):
+            step_outside()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_outside()
+        torch.cuda.synchronize()
+        outside_ms = (time.perf_counter() - t0) / args.steps * 1e3
 
     # per-kernel durations, HIP events on the launch stream (second pass, same work)
     gsa.gsa_profile_reset()
@@ -275,7 +301,9 @@ def main():
             cfg.name, cfg.B, cfg.T, cfg.H, cfg.d_k, cfg.d_v, cfg.m,
             "" if cfg.cu_seqlens is None else " packed %s" % (list(cfg.cu_seqlens),)),
             "tokens_per_step": tokens, "chunk": 64, "readout": args.readout,
-            "write_intensity": "given" if args.given_intensity else "1 - exp(g)"},
+            "write_intensity": "given" if args.given_intensity else "1 - exp(g)",
+            "feature_map": args.feature_map},
+        **({} if outside_ms is None else {"feature_map_outside_ms_per_step": round(outside_ms, 4)}),
         "roofline": roofline,
         "path": {"executed_tflops": round(exec_flops / (ms_per_step * 1e-3) / 1e12, 2),
                  "frac_mfma_bf16_peak": round(exec_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),

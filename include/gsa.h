@@ -131,26 +131,33 @@ gsa_status gsa_bwd(const gsa_problem *p,
  *           alpha = sigmoid(W x)^(1/tau) of Section 3.2 (tau = 8 in the paper)
  *           evaluated inside the kernels; gsa_bwd_ex then returns in dg the
  *           gradient with respect to the logits.
+ *   feature_map GSA_FEATURE_NONE: q, k, v enter Eq. (gsa) as given.  GSA_FEATURE_SWISH:
+ *           they hold the layer's raw projections W_q x, W_k x, W_v x and the
+ *           kernels apply phi(x) = x*sigmoid(x) of Section 3.2 to them as they load
+ *           them (rounded once more to dtype, since they feed the matrix
+ *           cores); gsa_bwd_ex then returns dq, dk, dv with respect to the raw
+ *           values.
  *   gsa_bwd_ex: with s given, dg is the gradient through the decay alone and
  *           ds [B,T,H,m] fp32 (required then) receives the gradient of s; with
  *           s NULL, ds is not touched and dg is as in gsa_bwd.  The same s,
- *           readout and gate_tau must be passed to both calls.
- * Errors as for gsa_fwd/gsa_bwd; an unknown readout or a negative or NaN
- * gate_tau returns GSA_ERR_SHAPE.
- * gsa_decode_step_ex (below) is the decode step with the same two options.
+ *           readout, gate_tau and feature_map must be passed to both calls.
+ * Errors as for gsa_fwd/gsa_bwd; an unknown readout or feature_map or a
+ * negative or NaN gate_tau returns GSA_ERR_SHAPE.
+ * gsa_decode_step_ex (below) is the decode step with the same options.
  */
 typedef enum {
     GSA_READOUT_SOFTMAX = 0, GSA_READOUT_IDENTITY = 1, GSA_READOUT_SWISH = 2, GSA_READOUT_RELU = 3,
     GSA_READOUT_RELU2 = 4
 } gsa_readout;
+typedef enum { GSA_FEATURE_NONE = 0, GSA_FEATURE_SWISH = 1 } gsa_feature_map;
 
-gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau,
+gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map,
                       const void *q, const void *k, const void *v, const float *g, const float *s,
                       const float *K0, const float *V0,
                       void *o, float *z_saved, float *KT, float *VT,
                       void *workspace, size_t workspace_bytes, void *stream);
 
-gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau,
+gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map,
                       const void *q, const void *k, const void *v, const float *g, const float *s,
                       const float *K0, const float *V0, const float *z_saved, const void *dO,
                       const float *dKT, const float *dVT,
@@ -193,11 +200,11 @@ gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, in
 /*
  * The decode step (Eq. (gsa), decode form) with the options of gsa_fwd_ex (Algorithm 1's
  * separate write intensity; the read-outs of Section 4's ablation table): s [B,H,m] fp32
- * or NULL, readout a gsa_readout, gate_tau as there.  workspace may be NULL (then the call behaves like
+ * or NULL, readout a gsa_readout, gate_tau and feature_map as there.  workspace may be NULL (then the call behaves like
  * gsa_decode_step) or as for gsa_decode_step_ws.
  */
 gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
-                              int32_t dtype, float scale, int32_t readout, float gate_tau,
+                              int32_t dtype, float scale, int32_t readout, float gate_tau, int32_t feature_map,
                               const void *q, const void *k, const void *v, const float *g, const float *s,
                               float *K_state, float *V_state, void *o,
                               void *workspace, size_t workspace_bytes, void *stream);

@@ -42,9 +42,9 @@ def load():
     lib.gsa_bwd.restype = ctypes.c_int
     lib.gsa_bwd.argtypes = [ctypes.POINTER(GsaProblem)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
     lib.gsa_fwd_ex.restype = ctypes.c_int
-    lib.gsa_fwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_fwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32, i32] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
     lib.gsa_bwd_ex.restype = ctypes.c_int
-    lib.gsa_bwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32] + [vp] * 18 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_bwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32, i32] + [vp] * 18 + [vp, ctypes.c_size_t, vp]
     lib.gsa_decode_step.restype = ctypes.c_int
     lib.gsa_decode_step.argtypes = [i32, i32, i32, i32, i32, i32, f32] + [vp] * 8
     lib.gsa_decode_workspace_bytes.restype = ctypes.c_int
@@ -52,7 +52,7 @@ def load():
     lib.gsa_decode_step_ws.restype = ctypes.c_int
     lib.gsa_decode_step_ws.argtypes = [i32, i32, i32, i32, i32, i32, f32] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
     lib.gsa_decode_step_ex.restype = ctypes.c_int
-    lib.gsa_decode_step_ex.argtypes = [i32, i32, i32, i32, i32, i32, f32, i32, f32] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_decode_step_ex.argtypes = [i32, i32, i32, i32, i32, i32, f32, i32, f32, i32] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
     lib.gsa_profile_enable.restype = ctypes.c_int
     lib.gsa_profile_enable.argtypes = [ctypes.c_int]
     lib.gsa_profile_reset.restype = ctypes.c_int

@@ -77,13 +77,15 @@ def alloc_workspace(problem, want_bwd: bool, device) -> torch.Tensor:
 
 
 READOUTS = {"softmax": 0, "identity": 1, "swish": 2, "relu": 3, "relu2": 4}
+FEATURE_MAPS = {"none": 0, "swish": 1}
 
 
 def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=True, final_state=False,
-            workspace=None, s=None, readout="softmax", gate_tau=0.0):
+            workspace=None, s=None, readout="softmax", gate_tau=0.0, feature_map="none"):
     """Returns (o, z_saved or None, KT or None, VT or None).  With s (write intensities [B,T,H,m] fp32),
-    a readout other than "softmax" or gate_tau > 0 (g holds gate logits, log gate = logsigmoid(g)/gate_tau)
-    the call goes through gsa_fwd_ex."""
+    a readout other than "softmax", gate_tau > 0 (g holds gate logits, log gate = logsigmoid(g)/gate_tau)
+    or feature_map "swish" (q, k, v hold raw projections, the kernels apply x*sigmoid(x) to them) the call
+    goes through gsa_fwd_ex."""
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     p = make_problem(q, v, g, scale, cu_seqlens)
@@ -98,9 +100,9 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
     z = torch.empty((B, T, H, m), dtype=torch.float32, device=q.device) if save_z else None
     KT = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if final_state else None
     VT = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if final_state else None
-    if s is not None or readout != "softmax" or gate_tau:
+    if s is not None or readout != "softmax" or gate_tau or feature_map != "none":
         _check(s, "s", torch.float32, (B, T, H, m), optional=True)
-        rc = _lib.load().gsa_fwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
+        rc = _lib.load().gsa_fwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map], _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
                                     _ptr(K0), _ptr(V0), _ptr(o), _ptr(z), _ptr(KT), _ptr(VT), _ptr(workspace),
                                     workspace.numel(), _stream(q))
         if rc != 0:
@@ -115,7 +117,8 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
 
 
 def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, cu_seqlens=None,
-            initial_state_grad=False, workspace=None, s=None, readout="softmax", gate_tau=0.0):
+            initial_state_grad=False, workspace=None, s=None, readout="softmax", gate_tau=0.0,
+            feature_map="none"):
     """Returns (dq, dk, dv, dg, dK0 or None, dV0 or None), plus ds as a seventh item when s is given
     (gsa_bwd_ex; dg is then the gradient through the decay alone)."""
     B, T, H, d_k = q.shape
@@ -133,10 +136,10 @@ def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale
     dg = torch.empty_like(g)
     dK0 = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if initial_state_grad else None
     dV0 = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if initial_state_grad else None
-    if s is not None or readout != "softmax" or gate_tau:
+    if s is not None or readout != "softmax" or gate_tau or feature_map != "none":
         _check(s, "s", torch.float32, (B, T, H, m), optional=True)
         ds = None if s is None else torch.empty_like(g)
-        rc = _lib.load().gsa_bwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
+        rc = _lib.load().gsa_bwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map], _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
                                     _ptr(K0), _ptr(V0), _ptr(z_saved), _ptr(dO), _ptr(dKT), _ptr(dVT), _ptr(dq),
                                     _ptr(dk), _ptr(dv), _ptr(dg), _ptr(ds), _ptr(dK0), _ptr(dV0), _ptr(workspace),
                                     workspace.numel(), _stream(q))
@@ -164,11 +167,11 @@ def alloc_decode_workspace(B, H, d_k, d_v, m, device) -> torch.Tensor:
 
 
 def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace=None, s=None, readout="softmax",
-                    gate_tau=0.0):
+                    gate_tau=0.0, feature_map="none"):
     """q,k [B,H,d_k], v [B,H,d_v], g [B,H,m]; K_state,V_state fp32 [B,H,m,d], updated in place.
     With a workspace (alloc_decode_workspace) the call goes through gsa_decode_step_ws, which spreads
-    each memory over several workgroups.  With s ([B,H,m] fp32 write intensities) or a readout other than
-    "softmax" it goes through gsa_decode_step_ex.  Returns o [B,H,d_v]."""
+    each memory over several workgroups.  With s ([B,H,m] fp32 write intensities), a readout other than
+    "softmax", gate_tau > 0 or feature_map "swish" it goes through gsa_decode_step_ex.  Returns o [B,H,d_v]."""
     B, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     if q.dtype not in _DTYPES:
@@ -179,10 +182,10 @@ def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace
     _check(V_state, "V_state", torch.float32, (B, H, m, d_v))
     o = torch.empty_like(v) if out is None else out
     _check(o, "out", q.dtype, (B, H, d_v))
-    if s is not None or readout != "softmax" or gate_tau:
+    if s is not None or readout != "softmax" or gate_tau or feature_map != "none":
         _check(s, "s", torch.float32, (B, H, m), optional=True)
         rc = _lib.load().gsa_decode_step_ex(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), READOUTS[readout],
-                                            float(gate_tau),
+                                            float(gate_tau), FEATURE_MAPS[feature_map],
                                             _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s), _ptr(K_state),
                                             _ptr(V_state), _ptr(o), _ptr(workspace),
                                             0 if workspace is None else workspace.numel(), _stream(q))

@@ -13,11 +13,12 @@ from . import api
 
 class _Gsa(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, k, v, g, s, K0, V0, scale, cu_seqlens, readout, gate_tau, want_final):
+    def forward(ctx, q, k, v, g, s, K0, V0, scale, cu_seqlens, readout, gate_tau, feature_map, want_final):
         o, z, KT, VT = api.gsa_fwd(q, k, v, g, K0=K0, V0=V0, scale=scale, cu_seqlens=cu_seqlens, save_z=True,
-                                   final_state=want_final, s=s, readout=readout, gate_tau=gate_tau)
+                                   final_state=want_final, s=s, readout=readout, gate_tau=gate_tau,
+                                   feature_map=feature_map)
         ctx.save_for_backward(q, k, v, g, z, s, K0, V0)
-        ctx.opts = (scale, cu_seqlens, readout, gate_tau)
+        ctx.opts = (scale, cu_seqlens, readout, gate_tau, feature_map)
         if want_final:
             return o, KT, VT
         return o
@@ -25,26 +26,28 @@ class _Gsa(torch.autograd.Function):
     @staticmethod
     def backward(ctx, dO, dKT=None, dVT=None):
         q, k, v, g, z, s, K0, V0 = ctx.saved_tensors
-        scale, cu_seqlens, readout, gate_tau = ctx.opts
+        scale, cu_seqlens, readout, gate_tau, feature_map = ctx.opts
         need_init = (K0 is not None and ctx.needs_input_grad[5]) or (V0 is not None and ctx.needs_input_grad[6])
         res = api.gsa_bwd(q, k, v, g, z, dO.contiguous(), K0=K0, V0=V0,
                           dKT=None if dKT is None else dKT.contiguous(),
                           dVT=None if dVT is None else dVT.contiguous(), scale=scale, cu_seqlens=cu_seqlens,
-                          initial_state_grad=need_init, s=s, readout=readout, gate_tau=gate_tau)
+                          initial_state_grad=need_init, s=s, readout=readout, gate_tau=gate_tau,
+                          feature_map=feature_map)
         dq, dk, dv, dg, dK0, dV0 = res[:6]
         ds = res[6] if s is not None else None
         return (dq, dk, dv, dg, ds, dK0 if K0 is not None else None, dV0 if V0 is not None else None,
-                None, None, None, None, None)
+                None, None, None, None, None, None)
 
 
 def gsa_attention(q, k, v, g, s=None, K0=None, V0=None, scale=1.0, cu_seqlens=None, readout="softmax", gate_tau=0.0,
-                  output_final_state=False):
+                  feature_map="none", output_final_state=False):
     """q,k [B,T,H,d_k], v [B,T,H,d_v] (bf16 or fp32), g [B,T,H,m] fp32 log forget gates (or gate logits with
-    gate_tau > 0); s optional write intensities [B,T,H,m]; K0,V0 optional initial memories [n,H,m,d] fp32.
+    gate_tau > 0); s optional write intensities [B,T,H,m]; K0,V0 optional initial memories [n,H,m,d] fp32;
+    feature_map "swish": q, k, v are raw projections, x*sigmoid(x) is applied inside the kernels.
     Returns o, or (o, (KT, VT)) with output_final_state."""
     out = _Gsa.apply(q.contiguous(), k.contiguous(), v.contiguous(), g.contiguous(),
                      None if s is None else s.contiguous(), K0, V0, float(scale), cu_seqlens, readout,
-                     float(gate_tau), bool(output_final_state))
+                     float(gate_tau), feature_map, bool(output_final_state))
     if output_final_state:
         return out[0], (out[1], out[2])
     return out

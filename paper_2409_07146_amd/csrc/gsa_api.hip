@@ -135,11 +135,13 @@ gsa_status decode_checks(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t
 gsa_status decode_any(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
                       const void *q, const void *k, const void *v, const float *g, float *K_state, float *V_state,
                       void *o, bool with_ws, void *workspace, size_t workspace_bytes, void *stream,
-                      const float *s = nullptr, int32_t readout = GSA_READOUT_SOFTMAX, float gate_tau = 0.f)
+                      const float *s = nullptr, int32_t readout = GSA_READOUT_SOFTMAX, float gate_tau = 0.f,
+                      int32_t feature_map = GSA_FEATURE_NONE)
 {
     const gsa_status st = decode_checks(B, H, d_k, d_v, m, dtype, scale);
     if (st != GSA_OK) return st;
     if (readout < GSA_READOUT_SOFTMAX || readout > GSA_READOUT_RELU2 || !(gate_tau >= 0.f)) return GSA_ERR_SHAPE;
+    if (feature_map != GSA_FEATURE_NONE && feature_map != GSA_FEATURE_SWISH) return GSA_ERR_SHAPE;
     if (B == 0) return GSA_OK;
     if (!q || !k || !v || !g || !K_state || !V_state || !o) return GSA_ERR_NULL;
     const void *ptrs[] = {q, k, v, g, K_state, V_state, o, s};
@@ -153,7 +155,8 @@ gsa_status decode_any(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
         if (need) scratch = static_cast<float *>(workspace);
     }
     const hipError_t e = gsa::launch_decode(B * H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o,
-                                            scratch, s, readout, gate_tau, static_cast<hipStream_t>(stream));
+                                            scratch, s, readout | (feature_map ? gsa::kFeatureMapBit : 0), gate_tau,
+                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
 }
 
@@ -187,7 +190,7 @@ gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes
 }
 
 namespace {
-gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, const void *q, const void *k, const void *v, const float *g,
+gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v, const float *g,
                    const float *s, const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -196,6 +199,7 @@ gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, const 
     if (st != GSA_OK) return st;
     if (readout < GSA_READOUT_SOFTMAX || readout > GSA_READOUT_RELU2) return GSA_ERR_SHAPE;
     if (!(gate_tau >= 0.f)) return GSA_ERR_SHAPE;
+    if (feature_map != GSA_FEATURE_NONE && feature_map != GSA_FEATURE_SWISH) return GSA_ERR_SHAPE;
     if (pl.tokens == 0) return GSA_OK;
     if (!q || !k || !v || !g || !o) return GSA_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) || !aligned16(K0) ||
@@ -206,13 +210,14 @@ gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, const 
     pl.s_in = s;
     pl.readout = readout;
     pl.gate_tau = gate_tau;
+    pl.phi = feature_map;
     const Work w = make_work(pl, workspace);
     const hipError_t e = gsa::launch_fwd(pl, w, q, k, v, g, K0, V0, o, z_saved, KT, VT,
                                          static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
 }
 
-gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, const void *q, const void *k, const void *v, const float *g,
+gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v, const float *g,
                    const float *s, const float *K0, const float *V0, const float *z_saved, const void *dO,
                    const float *dKT, const float *dVT, void *dq, void *dk, void *dv, float *dg, float *ds, float *dK0,
                    float *dV0, void *workspace, size_t workspace_bytes, void *stream)
@@ -222,6 +227,7 @@ gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, const 
     if (st != GSA_OK) return st;
     if (readout < GSA_READOUT_SOFTMAX || readout > GSA_READOUT_RELU2) return GSA_ERR_SHAPE;
     if (!(gate_tau >= 0.f)) return GSA_ERR_SHAPE;
+    if (feature_map != GSA_FEATURE_NONE && feature_map != GSA_FEATURE_SWISH) return GSA_ERR_SHAPE;
     if (pl.tokens == 0) return GSA_OK;
     if (!q || !k || !v || !g || !z_saved || !dO || !dq || !dk || !dv || !dg) return GSA_ERR_NULL;
     if (s && !ds) return GSA_ERR_NULL;
@@ -234,6 +240,7 @@ gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, const 
     pl.ds_out = s ? ds : nullptr;
     pl.readout = readout;
     pl.gate_tau = gate_tau;
+    pl.phi = feature_map;
     const Work w = make_work(pl, workspace);
     const hipError_t e = gsa::launch_bwd(pl, w, q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0,
                                          static_cast<hipStream_t>(stream));
@@ -245,15 +252,15 @@ gsa_status gsa_fwd(const gsa_problem *p, const void *q, const void *k, const voi
                    const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    return fwd_any(p, GSA_READOUT_SOFTMAX, 0.f, q, k, v, g, nullptr, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes,
+    return fwd_any(p, GSA_READOUT_SOFTMAX, 0.f, GSA_FEATURE_NONE, q, k, v, g, nullptr, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes,
                    stream);
 }
 
-gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, const void *q, const void *k, const void *v,
+gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v,
                       const float *g, const float *s, const float *K0, const float *V0, void *o, float *z_saved,
                       float *KT, float *VT, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return fwd_any(p, readout, gate_tau, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes, stream);
+    return fwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes, stream);
 }
 
 gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
@@ -261,16 +268,16 @@ gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const voi
                    const float *dVT, void *dq, void *dk, void *dv, float *dg, float *dK0, float *dV0,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    return bwd_any(p, GSA_READOUT_SOFTMAX, 0.f, q, k, v, g, nullptr, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, nullptr,
+    return bwd_any(p, GSA_READOUT_SOFTMAX, 0.f, GSA_FEATURE_NONE, q, k, v, g, nullptr, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, nullptr,
                    dK0, dV0, workspace, workspace_bytes, stream);
 }
 
-gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, const void *q, const void *k, const void *v,
+gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v,
                       const float *g, const float *s, const float *K0, const float *V0, const float *z_saved,
                       const void *dO, const float *dKT, const float *dVT, void *dq, void *dk, void *dv, float *dg,
                       float *ds, float *dK0, float *dV0, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return bwd_any(p, readout, gate_tau, q, k, v, g, s, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, ds, dK0, dV0, workspace,
+    return bwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, ds, dK0, dV0, workspace,
                    workspace_bytes, stream);
 }
 
@@ -291,12 +298,12 @@ gsa_status gsa_decode_workspace_bytes(int32_t B, int32_t H, int32_t d_k, int32_t
 }
 
 gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
-                              int32_t readout, float gate_tau, const void *q, const void *k, const void *v,
-                              const float *g, const float *s, float *K_state, float *V_state, void *o, void *workspace,
+                              int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k,
+                              const void *v, const float *g, const float *s, float *K_state, float *V_state, void *o, void *workspace,
                               size_t workspace_bytes, void *stream)
 {
     return decode_any(B, H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o, workspace != nullptr,
-                      workspace, workspace_bytes, stream, s, readout, gate_tau);
+                      workspace, workspace_bytes, stream, s, readout, gate_tau, feature_map);
 }
 
 gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,

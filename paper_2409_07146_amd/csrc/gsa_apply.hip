@@ -33,6 +33,8 @@ template <typename T> struct ApplyOne {
     long long xs_stride;  // elements per (chunk, head) record
     T *out;               // [tokens][H][d]
     int d;
+    bool phi_tok;         // feature map on xtok on its way into LDS
+    const T *raw;         // [tokens][H][d] or NULL: out leaves multiplied by the feature map's slope at raw
 };
 template <typename T> struct ApplyArgs { ApplyOne<T> one[3]; };
 
@@ -48,7 +50,9 @@ template <typename T, int M> struct ApplyLds {
     static constexpr size_t bytes = oAs + sizeof(T) * C * lds;
 };
 
-template <typename T, int M>
+// PHI: compiled with the feature-map options (ApplyOne::phi_tok, ApplyOne::raw); the plain calls run
+// PHI = false, where those fields are ignored.
+template <typename T, int M, bool PHI>
 __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, ApplyArgs<T> args)
 {
     using L = ApplyLds<T, M>;
@@ -96,6 +100,18 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
     ts.template load_snapshot<true>(a.xslot + ch * a.xs_stride, cs, ncols, tid);
     TokTile<T, C, L::NS, NT> tt;   // the token tensor's column slice
     tt.template load<true>(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);
+    // the raw values under this workgroup's output tile, in the thread mapping of the final store
+    constexpr int OV = C * (L::NS / 8), OPER = (OV + NT - 1) / NT;
+    Raw8<T> rawv[PHI ? OPER : 1];
+    const bool chain = PHI && a.raw != nullptr;
+    if (chain) {
+        const int vpr = ncols >> 3;
+#pragma unroll
+        for (int u = 0; u < OPER; ++u) {
+            const int idx = min(tid + u * NT, C * vpr - 1), t = min(idx / vpr, ci.len - 1), c = (idx - (idx / vpr) * vpr) << 3;
+            rawv[PHI ? u : 0].load_nt(a.raw + tokh * a.d + cs + (size_t)t * H * a.d + c);
+        }
+    }
     // the two small matrices go through LDS: every wave needs all of both
     T *Ats = reinterpret_cast<T *>(smem + L::oAt), *Ass = reinterpret_cast<T *>(smem + L::oAs);
     {
@@ -141,7 +157,8 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
         }
     }
     __syncthreads();   // the slot tile is dead: the token tile takes its place
-    tt.store_transposed(XT, L::lda, ncols, tid);
+    if (PHI && a.phi_tok) tt.template store_transposed<true>(XT, L::lda, ncols, tid);
+    else tt.store_transposed(XT, L::lda, ncols, tid);
     __syncthreads();
     if (active) {
 #pragma unroll
@@ -169,6 +186,25 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
                     Os[(mi * 16 + g4 + j) * L::ldo + wcol + ni * 16 + r] = from_f32<T>(acc[mi][ni][j]);
     }
     __syncthreads();
+    if (chain) {
+        // out = tile * phi'(raw): same walk as store_tile, one 8-element piece per thread and step
+        const int vpr = ncols >> 3;
+        T *dst = a.out + tokh * a.d + cs;
+#pragma unroll
+        for (int u = 0; u < OPER; ++u) {
+            const int idx = tid + u * NT, t = idx / vpr, c = (idx - t * vpr) << 3;
+            if (idx < C * vpr && t < ci.len) {
+                Raw8<T> x;
+                x.load(Os + t * L::ldo + c);
+                Raw8<T> y;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    y.set(e, from_f32<T>((float)x.get(e) * swish_slope((float)rawv[PHI ? u : 0].get(e))));
+                y.store_nt(dst + (size_t)t * H * a.d + c);
+            }
+        }
+        return;
+    }
     store_tile<T, true>(a.out + tokh * a.d + cs, (size_t)H * a.d, Os, L::ldo, C, ncols, ci.len, tid, NT);
 }
 
@@ -188,12 +224,15 @@ static hipError_t launch_apply_tm(const Plan &pl, const Work &w, const ApplyIo *
         o.xs_stride = s.xslot_stride;
         o.out = static_cast<T *>(s.out);
         o.d = s.d;
+        o.phi_tok = s.phi_tok;
+        o.raw = static_cast<const T *>(s.raw);
         if (i < n && s.d > dmax) dmax = s.d;
     }
     constexpr int NS = ApplyLds<T, M>::NS;
     dim3 grid((dmax + NS - 1) / NS, pl.chunk_slots, pl.H * n);
     KernelTimer kt(slot, st);
-    hipLaunchKernelGGL((apply_kernel<T, M>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    if (pl.phi) hipLaunchKernelGGL((apply_kernel<T, M, true>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    else hipLaunchKernelGGL((apply_kernel<T, M, false>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
     return hipGetLastError();
 }
 

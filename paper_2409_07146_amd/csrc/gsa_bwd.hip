@@ -53,7 +53,8 @@ template <typename T, int M> struct DzLds {
     static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
-// GEN: the general form (write intensities from `sin` when it is not NULL; read-out `readout`).
+// GEN: the general form (write intensities from `sin` when it is not NULL; opts: read-out in the low
+// byte, kFeatureMapBit for the feature map on v).
 template <typename T, int M, bool GEN>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
                                                               const T *__restrict__ v, const T *__restrict__ dO,
@@ -61,10 +62,11 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
                                                               const T *__restrict__ S, StateLayout lay,
                                                               float *__restrict__ dz, float *__restrict__ dgf,
                                                               T *__restrict__ Wr, T *__restrict__ tAvT,
-                                                              const float *__restrict__ sin, int readout,
+                                                              const float *__restrict__ sin, int opts,
                                                               float gate_tau)
 {
     using L = DzLds<T, M>;
+    const int readout = opts & kReadoutMask;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
     constexpr int MI = M / 16;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
                                reinterpret_cast<T *>(smem + L::oVt), L::lda,
                                reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
                                v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,
-                               (GEN && sin) ? sin + tokh * M : nullptr, gate_tau);
+                               (GEN && sin) ? sin + tokh * M : nullptr, gate_tau,
+                               (GEN && (opts & kFeatureMapBit)) ? kHintY : 0);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -212,6 +215,7 @@ template <typename T> struct IntraArgs {
     float *ds;          // general form: their gradient (with sin)
     int readout;
     float gate_tau;     // general form: > 0 when g holds gate logits
+    int phi;            // general form: feature map on q, k, v
 };
 
 template <typename T, int M, bool GEN>
@@ -304,6 +308,12 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
                 for (int ni = 0; ni < CI; ++ni) fk[hh][ni] = Atom<T>::load(kb + tk[ni] + kk + 32 * hh);
             __builtin_amdgcn_sched_barrier(0);   // all loads of the step before its multiplies (see gated_scores)
+            if (GEN && a.phi) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int ni = 0; ni < CI; ++ni) { swish_frag<T>(fq[hh][ni]); swish_frag<T>(fk[hh][ni]); }
+            }
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -326,6 +336,12 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
                 for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load_nt(SendK + ek[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
+            if (GEN && a.phi) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int ni = 0; ni < CI; ++ni) swish_frag<T>(fk[hh][ni]);
+            }
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
@@ -353,6 +369,12 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
                 for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load_nt(SendV + ev[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
+            if (GEN && a.phi) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int ni = 0; ni < CI; ++ni) swish_frag<T>(fv[hh][ni]);
+            }
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
@@ -597,7 +619,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     // 1. recompute the chunk-start memories (and the memories after the last token)
     GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
     {
-        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false};
+        const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false, pl.phi != 0, pl.phi != 0};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     dim3 grid(pl.chunk_slots, pl.H);
@@ -609,12 +631,12 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         KernelTimer kt(kSlotChunkDz, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_v, pl.scale, (const T *)v,
                            (const T *)dO, g, z, (const T *)w.S, pl.lay, w.dz, w.dgf, (T *)w.Wr, (T *)w.tAvT, pl.s_in,
-                           (int)pl.readout, pl.gate_tau);
+                           pl.opts(), pl.gate_tau);
         GSA_HIP_TRY(hipGetLastError());
     }
     // 3. reverse scan of the memory gradient
     {
-        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true};
+        const ScanIo io = {q, dO, dKT, dVT, dK0, dV0, nullptr, true, pl.phi != 0, false};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     // 4. everything chunk-local except the wide contractions
@@ -630,16 +652,17 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         a.tAvT = (const T *)w.tAvT;
         a.dg = dg;
         a.tB = (T *)w.tA; a.tBT = (T *)w.tBT; a.tA2T = (T *)w.tA2T; a.tDZe = (T *)w.tP; a.tSbe = (T *)w.tSbe;
-        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout; a.gate_tau = pl.gate_tau;
+        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout; a.gate_tau = pl.gate_tau; a.phi = pl.phi;
         KernelTimer kt(kSlotChunkIntra, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, a);
         GSA_HIP_TRY(hipGetLastError());
     }
-    // 5. dq, dk, dv
+    // 5. dq, dk, dv (with the feature map: through its slope at the raw q, k, v)
+    const bool phi = pl.phi != 0;
     const ApplyIo io[3] = {
-        {w.tA, w.tP, k, w.S, pl.lay.oK, pl.lay.stride, dq, pl.d_k},
-        {w.tBT, w.tSbe, q, w.E, pl.lay.oK, pl.lay.stride, dk, pl.d_k},
-        {w.tA2T, w.tSbe, dO, w.E, pl.lay.oV, pl.lay.stride, dv, pl.d_v},
+        {w.tA, w.tP, k, w.S, pl.lay.oK, pl.lay.stride, dq, pl.d_k, phi, phi ? q : nullptr},
+        {w.tBT, w.tSbe, q, w.E, pl.lay.oK, pl.lay.stride, dk, pl.d_k, phi, phi ? k : nullptr},
+        {w.tA2T, w.tSbe, dO, w.E, pl.lay.oV, pl.lay.stride, dv, pl.d_v, false, phi ? v : nullptr},
     };
     return launch_apply(pl, w, io, 3, kSlotApplyBwd, st);
 }

@@ -154,12 +154,13 @@ __device__ __forceinline__ void build_write_tiles(const float *Gs, const float *
 // caller knows nobody reads again soon.  Both halves of every 128-byte line are asked for by the
 // same wave in the same step, so a hinted line is never dropped between its two readers.
 constexpr int kHintX = 1, kHintY = 2, kHintSt = 4;
+// phi (general form only): which of X, Y get the feature map after the load (kHintX | kHintY bits).
 template <typename T, int M, int C, bool GEN = false, int RPR = 1, int HINT = 0>
 __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsafe, float *Gs, float *Ss, int ldg,
                                              float *tot, const float *g, size_t gld, T *As, int lda, T *Vt, int ldv,
                                              float *Rb, f32x4 *Red, const T *X, const T *Y,
                                              size_t ldx, int d, const T *St, int len, int tid,
-                                             const float *sin = nullptr, float gate_tau = 0.f)
+                                             const float *sin = nullptr, float gate_tau = 0.f, int phi = 0)
 {
     constexpr int MI = M / 16, CI = C / 16, NW = CI, NB = CI + MI;
     const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -204,6 +205,15 @@ __device__ __forceinline__ void gated_scores(float (&out)[M / 16][4], bool &unsa
                 for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = (HINT & kHintSt) ? Atom<T>::load_nt(St + so[ni] + snap_col<M>(k0)) : Atom<T>::load(St + so[ni] + snap_col<M>(k0));
             }
             __builtin_amdgcn_sched_barrier(0);
+            if (GEN && phi) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int ni = 0; ni < CI; ++ni) {
+                        if (phi & kHintX) swish_frag<T>(fx[hh][ni]);
+                        if (phi & kHintY) swish_frag<T>(fy[hh][ni]);
+                    }
+            }
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh)
 #pragma unroll

@@ -183,6 +183,7 @@ template <> struct Raw8<bf16_t> {
         for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.f;
     }
     __device__ __forceinline__ bf16_t get(int e) const { return v[e]; }
+    __device__ __forceinline__ void set(int e, bf16_t x) { v[e] = x; }
     __device__ __forceinline__ void keep(bool live) {   // zero unless live, by register select
         bf16x8 z;
 #pragma unroll
@@ -210,6 +211,7 @@ template <> struct Raw8<float> {
     }
     __device__ __forceinline__ void zero() { lo = f32x4{0.f, 0.f, 0.f, 0.f}; hi = lo; }
     __device__ __forceinline__ float get(int e) const { return e < 4 ? lo[e] : hi[e - 4]; }
+    __device__ __forceinline__ void set(int e, float x) { if (e < 4) lo[e] = x; else hi[e - 4] = x; }
     __device__ __forceinline__ void keep(bool live) {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         lo = live ? lo : z;
@@ -437,6 +439,26 @@ __device__ __forceinline__ float readout_slope(int ro, float z)
                                                                                                : 2.f * fmaxf(z, 0.f);
 }
 
+// ----------------------------------------------------------------------------
+// Feature map on q, k, v (Section 3.2: the layer feeds phi(W x) with phi = Swish into the operator).
+// With the option on, the q, k, v arguments hold the raw projections and every kernel applies
+// phi(x) = x sigmoid(x) to what it has just loaded, in registers: the values are rounded to the I/O
+// type once more (they are matrix-core operands), and dq, dk, dv leave multiplied by the slope at
+// the raw value.  The arithmetic runs under the loads that are still in flight, which is what makes
+// this cheaper than a pass of its own over the three tensors.
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ float swish_value(float x) { return x * __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
+__device__ __forceinline__ float swish_slope(float x)
+{
+    const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-x));
+    return sg * (1.f + x * (1.f - sg));
+}
+template <typename T> __device__ __forceinline__ void swish_frag(typename Atom<T>::Frag &f)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = from_f32<T>(swish_value((float)f[e]));
+}
+
 // Fragment straight from global memory: 8 consecutive elements of one row.  Loads in this
 // library are never placed under a data-dependent branch (the compiler would have to wait for
 // each one before leaving the branch, which serialises them): callers clamp the row index into
@@ -513,6 +535,8 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
             la[u] = lb[u] = ok;
         }
     }
+    // PHI: with the feature map applied on the way (see swish_value)
+    template <bool PHI = false>
     __device__ __forceinline__ void store_transposed(T *XT, int ld, int ncols, int tid) const
     {
 #pragma unroll
@@ -527,8 +551,8 @@ template <typename T, int C, int NCOLS, int NT> struct TokTile {
                 for (int e = 0; e < 8; ++e) {
                     // two 2-byte stores: measured faster here than one packed 4-byte store
                     T *dst = XT + xt_off<C>(cg * 8 + e, 2 * rp, ld);
-                    dst[0] = x.get(e);
-                    dst[1] = y.get(e);
+                    dst[0] = PHI ? from_f32<T>(swish_value((float)x.get(e))) : x.get(e);
+                    dst[1] = PHI ? from_f32<T>(swish_value((float)y.get(e))) : y.get(e);
                 }
             }
         }

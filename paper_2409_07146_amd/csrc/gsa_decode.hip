@@ -50,17 +50,19 @@ template <> __device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t *p) {
 // PIECES > 0 (split form): a pair is spread over PIECES workgroups of NWAVES waves, each covering
 // M/PIECES slots (blockIdx.x = pair * PIECES + piece); instead of the output the workgroup writes to
 // `scratch`, per pair [PIECES][2] (maximum, sum) followed by [PIECES][d_v] (unnormalised partial output).
-// GEN: the general form (write intensities from `sin` when given, read-out `readout`, gate logits with
-// gate_tau > 0); the plain calls run GEN = false, where none of this is compiled in.
+// GEN: the general form (write intensities from `sin` when given; opts: read-out in the low byte and
+// kFeatureMapBit for the feature map on q, k, v; gate logits with gate_tau > 0); the plain calls run
+// GEN = false, where none of this is compiled in.
 template <typename T, int M, int NV, bool EARLY_V, int NWAVES, int PIECES, bool GEN>
 __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const T *__restrict__ v, const float *__restrict__ g,
                                                                float *__restrict__ Kst, float *__restrict__ Vst,
                                                                T *__restrict__ o, float *__restrict__ scratch,
-                                                               const float *__restrict__ sin, int readout,
+                                                               const float *__restrict__ sin, int opts,
                                                                float gate_tau)
 {
+    const int readout = opts & kReadoutMask;
     constexpr bool SPLIT = PIECES > 0;
     constexpr int NSPLIT = SPLIT ? PIECES : 1;
     static_assert(M % (NWAVES * NSPLIT) == 0, "slots must split evenly over the workgroups and their waves");
@@ -130,6 +132,16 @@ __global__ __launch_bounds__(NWAVES * kWave) void decode_kernel(int d_k, int d_v
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NV; ++j) qv[j] = okk[j] ? qv[j] : zero4;   // masked lanes contribute nothing to the row dots
+    if (GEN && (opts & kFeatureMapBit)) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                qv[j][e] = swish_value(qv[j][e]);
+                kv[j][e] = swish_value(kv[j][e]);
+                vv[j][e] = swish_value(vv[j][e]);
+            }
+    }
     float a[R], s[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
@@ -292,7 +304,7 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
         }
         KernelTimer kt(kSlotDecodeMerge, st);
         const dim3 mgrid((d_v + 4 * kWave - 1) / (4 * kWave), BH);
-        hipLaunchKernelGGL((decode_merge_kernel<T, pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o, readout);
+        hipLaunchKernelGGL((decode_merge_kernel<T, pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o, readout & kReadoutMask);
         return hipGetLastError();
     }
     const size_t lds = (128 + (size_t)kDecWaves * d_v) * sizeof(float);

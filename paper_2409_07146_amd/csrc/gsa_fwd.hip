@@ -109,7 +109,8 @@ template <typename T, int M> struct ChunkFwdLds {
     static constexpr size_t bytes = end > szRed ? end : szRed;
 };
 
-// GEN: the general form (write intensities from `sin` when it is not NULL; read-out `readout`).
+// GEN: the general form (write intensities from `sin` when it is not NULL; opts: read-out in the low
+// byte, kFeatureMapBit for the feature map on q and k).
 template <typename T, int M, bool GEN>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
@@ -117,9 +118,10 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
                                                                const T *__restrict__ S, StateLayout lay,
                                                                float *__restrict__ z_saved, T *__restrict__ tA,
                                                                T *__restrict__ tP, const float *__restrict__ sin,
-                                                               int readout, float gate_tau)
+                                                               int opts, float gate_tau)
 {
     using L = ChunkFwdLds<T, M>;
+    const int readout = opts & kReadoutMask;
     constexpr int C = Geo<T>::C, NT = Geo<T>::NT;
     constexpr int MI = M / 16, CI = C / 16, KM = L::KM;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -149,8 +151,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
     gated_scores<T, M, C, GEN, L::kRpr, kHintX | kHintY | kHintSt>(
         p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb,
         reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
-                               (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr,
-                               gate_tau);
+        (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr, gate_tau,
+        (GEN && (opts & kFeatureMapBit)) ? (kHintX | kHintY) : 0);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
@@ -270,7 +272,7 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
     const ChunkMap cm = make_chunk_map(pl, w);
     GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
     {
-        const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false};
+        const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false, pl.phi != 0, pl.phi != 0};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     {
@@ -281,10 +283,10 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
         KernelTimer kt(kSlotChunkFwd, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.scale, (const T *)q,
                            (const T *)k, g, (const T *)w.S, pl.lay, z_saved, (T *)w.tA, (T *)w.tP, pl.s_in,
-                           (int)pl.readout, pl.gate_tau);
+                           pl.opts(), pl.gate_tau);
         GSA_HIP_TRY(hipGetLastError());
     }
-    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v};
+    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v, pl.phi != 0, nullptr};
     return launch_apply(pl, w, &io, 1, kSlotApplyFwd, st);
 }
 

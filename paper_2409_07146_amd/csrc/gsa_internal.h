@@ -28,7 +28,9 @@ struct Plan {
     float *ds_out = nullptr;       // backward: gradient of s_in
     int32_t readout = 0;           // Readout
     float gate_tau = 0.f;          // > 0: g holds gate logits, the log gate is logsigmoid(g) / gate_tau
-    bool general() const { return s_in != nullptr || readout != 0 || gate_tau > 0.f; }
+    int32_t phi = 0;               // 1: q, k, v hold raw projections, the kernels apply the Swish feature map
+    bool general() const { return s_in != nullptr || readout != 0 || gate_tau > 0.f || phi != 0; }
+    int opts() const { return readout | (phi ? kFeatureMapBit : 0); }   // what the device kernels take
 };
 
 // Workspace views handed to the launchers.
@@ -86,6 +88,7 @@ struct ScanIo {
     float *outK, *outV;
     void *outJ;
     bool reverse;
+    bool phi_k = false, phi_v = false;   // feature map on xk / xv as they are loaded
 };
 hipError_t launch_scan(const Plan &pl, const Work &w, const ScanIo &io, hipStream_t st);
 
@@ -97,6 +100,8 @@ struct ApplyIo {
     long long xslot_off, xslot_stride;
     void *out;
     int d;
+    bool phi_tok = false;        // feature map on xtok as it is loaded
+    const void *raw = nullptr;   // [tokens][H][d] or NULL: out is multiplied by the feature map's slope at raw
 };
 hipError_t launch_apply(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st);
 
@@ -110,9 +115,10 @@ hipError_t launch_bwd(const Plan &pl, const Work &w, const void *q, const void *
                       hipStream_t st);
 
 // scratch: NULL (one workgroup per pair) or decode_scratch_floats(...) floats (split form, small BH).
+// opts: Readout in the low byte, kFeatureMapBit.
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
                          const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
-                         int readout, float gate_tau, hipStream_t st);
+                         int opts, float gate_tau, hipStream_t st);
 size_t decode_scratch_floats(int BH, int d_v, int m);
 
 }  // namespace gsa

@@ -20,6 +20,11 @@ constexpr int kSnapTile = 64;
 // workgroup's chain over the chunks no longer dominates the launch (measured: 32 chunks).
 constexpr int kSegChunks = 32;
 
+// The device kernels take the read-out and the feature-map switch in one int: the Readout value in
+// the low byte, this bit for "q, k, v are raw projections: apply the feature map to them".
+constexpr int kFeatureMapBit = 0x100;
+constexpr int kReadoutMask = 0xff;
+
 struct StateLayout {
     long long stride;   // elements per record
     long long oK, oV;   // key part, value part

@@ -63,6 +63,7 @@ template <typename T> struct ScanArgs {
     int w_parts;           // 1 (forward) or 2 (reverse: key part, value part)
     const float *dec;      // [chunk][H][M]
     const T *xk, *xv;      // token tensors feeding the key / value columns
+    bool phi_k, phi_v;     // feature map on xk / xv on their way into LDS
     const float *initK, *initV;   // [n_seqs][H][M][d] or NULL
     T *snap;               // one record per (chunk, head)
     StateLayout lay;       // layout of every record
@@ -152,6 +153,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
     const int col0 = slice * NS;
     const bool isK = col0 < d_k;
     const T *src = isK ? a.xk : a.xv;
+    const bool phi = isK ? a.phi_k : a.phi_v;
     const int dsrc = isK ? d_k : d_v;
     const int c0 = isK ? col0 : col0 - d_k;
     const size_t wpart = (a.w_parts == 2 && !isK) ? (size_t)M * C : 0;
@@ -273,7 +275,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
                 st.wreg[u].store(w + i * L::ldw + tg * 8);
             }
         }
-        st.xt.store_transposed(XT(b), L::ldw, NS, tid);
+        if (phi) st.xt.template store_transposed<true>(XT(b), L::ldw, NS, tid);
+        else st.xt.store_transposed(XT(b), L::ldw, NS, tid);
         Dec(b)[tid] = st.dec;   // every thread stores (threads >= M a copy of slot 0's): no branch around a loaded value
     };
     // position in the walk -> chunk; positions past the end repeat the last chunk, so that refills can be
@@ -453,6 +456,8 @@ static hipError_t launch_scan_tm(const Plan &pl, const Work &w, const ScanIo &io
     a.dec = w.dec;
     a.xk = static_cast<const T *>(io.xk);
     a.xv = static_cast<const T *>(io.xv);
+    a.phi_k = io.phi_k;
+    a.phi_v = io.phi_v;
     a.initK = io.initK;
     a.initV = io.initV;
     a.snap = static_cast<T *>(io.reverse ? w.E : w.S);

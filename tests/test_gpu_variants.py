@@ -105,10 +105,13 @@ def test_bad_readout_is_rejected():
     lib = _lib.load()
     p = _lib.GsaProblem(B=1, T=64, H=1, d_k=64, d_v=64, m=16, dtype=1, scale=1.0, cu_seqlens=None, n_seqs=0)
     null = ctypes.c_void_p(None)
-    assert lib.gsa_fwd_ex(ctypes.byref(p), 7, 0.0, *([null] * 11), null, 0, null) == 2
-    assert lib.gsa_bwd_ex(ctypes.byref(p), -1, 0.0, *([null] * 18), null, 0, null) == 2
-    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, -1.0, *([null] * 11), null, 0, null) == 2
-    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, float("nan"), *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 7, 0.0, 0, *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_bwd_ex(ctypes.byref(p), -1, 0.0, 0, *([null] * 18), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, -1.0, 0, *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, float("nan"), 0, *([null] * 11), null, 0, null) == 2
+    assert lib.gsa_fwd_ex(ctypes.byref(p), 0, 0.0, 2, *([null] * 11), null, 0, null) == 2     # unknown feature map
+    assert lib.gsa_bwd_ex(ctypes.byref(p), 0, 0.0, -1, *([null] * 18), null, 0, null) == 2
+    assert lib.gsa_decode_step_ex(1, 1, 64, 64, 16, 1, 1.0, 0, 0.0, 5, *([null] * 8), null, 0, null) == 2
 
 
 def test_variant_on_a_long_sequence(oracle):
@@ -161,3 +164,109 @@ def test_gate_logits_evaluated_inside(oracle, readout, given, dtype):
                             s=None if a["s"] is None else a["s"][:, -1], readout=readout)
     check("decode o", to_np64(o1), oo, dtype)
     check("decode K", to_np64(Kc), Ko, dtype)
+
+
+def _feature_map_case(oracle, cfg, x, readout="softmax", cu=None, scale=1.0):
+    """feature_map="swish": q, k, v are raw projections and the kernels apply phi(x) = x*sigmoid(x) (Section 3.2)
+    as they load them.  The oracle gets phi of the same raw values computed here in fp64, and its dq, dk, dv go
+    through phi's slope here as well."""
+    import paper_2409_07146_amd as gsa
+    from scipy.special import expit
+    dev = torch.device(DEV)
+    put = lambda t: None if t is None else t.to(dev)
+    d = {n: put(x[n]) for n in ("q", "k", "v", "g", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    cud = None if cu is None else torch.tensor(cu, dtype=torch.int32, device=dev)
+    o, z, KT, VT = gsa.gsa_fwd(d["q"], d["k"], d["v"], d["g"], K0=d["K0"], V0=d["V0"], scale=scale, cu_seqlens=cud,
+                               final_state=True, s=d["s"], readout=readout, feature_map="swish")
+    res = gsa.gsa_bwd(d["q"], d["k"], d["v"], d["g"], z, d["dO"], K0=d["K0"], V0=d["V0"], dKT=d["dKT"],
+                      dVT=d["dVT"], scale=scale, cu_seqlens=cud, initial_state_grad=True, s=d["s"], readout=readout,
+                      feature_map="swish")
+    torch.cuda.synchronize()
+    n64 = lambda t: None if t is None else to_np64(t)
+    a = {n: n64(x[n]) for n in ("q", "k", "v", "g", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    phi = lambda u: u * expit(u)
+    slope = lambda u: expit(u) * (1.0 + u * (1.0 - expit(u)))
+    cun = None if cu is None else np.asarray(cu, dtype=np.int32)
+    f = oracle.fwd(phi(a["q"]), phi(a["k"]), phi(a["v"]), a["g"], cu_seqlens=cun, K0=a["K0"], V0=a["V0"], scale=scale,
+                   s=a["s"], readout=readout)
+    for n, t in (("o", o), ("z", z), ("KT", KT), ("VT", VT)):
+        check(n, to_np64(t), f[n], cfg.dtype)
+    r = oracle.bwd(phi(a["q"]), phi(a["k"]), phi(a["v"]), a["g"], a["dO"], cu_seqlens=cun, K0=a["K0"], V0=a["V0"],
+                   dKT=a["dKT"], dVT=a["dVT"], scale=scale, s=a["s"], readout=readout)
+    for n in ("q", "k", "v"):
+        r["d" + n] = r["d" + n] * slope(a[n])
+    names = ["dq", "dk", "dv", "dg", "dK0", "dV0"] + (["ds"] if x["s"] is not None else [])
+    for n, t in zip(names, res):
+        check(n, to_np64(t), r[n], cfg.dtype)
+    return d, a, f
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("readout,given", [("softmax", False), ("softmax", True), ("relu2", False)])
+def test_feature_map_applied_inside(oracle, readout, given, dtype):
+    import paper_2409_07146_amd as gsa
+    from scipy.special import expit
+    cfg, x = _inputs(2, 200, 2, 128, 192, 64, dtype, seed=81, given=given)
+    for n in ("q", "k", "v"):      # raw projections: wider than the unit-variance inputs, both signs
+        x[n] = (x[n].float() * 1.5).to(x[n].dtype)
+    d, a, f = _feature_map_case(oracle, cfg, x, readout=readout, scale=0.7)
+    # decode step with the same option, continuing from the final memories
+    q1, k1, v1, g1 = (d[n][:, -1].contiguous() for n in ("q", "k", "v", "g"))
+    s1 = None if d["s"] is None else d["s"][:, -1].contiguous()
+    Kc, Vc = (torch.from_numpy(f[n]).float().to(DEV) for n in ("KT", "VT"))
+    Ko, Vo = Kc.cpu().double().numpy().copy(), Vc.cpu().double().numpy().copy()
+    o1 = gsa.gsa_decode_step(q1, k1, v1, g1, Kc, Vc, scale=0.7, s=s1, readout=readout, feature_map="swish")
+    phi = lambda u: u * expit(u)
+    oo = oracle.decode_step(phi(a["q"][:, -1]), phi(a["k"][:, -1]), phi(a["v"][:, -1]), a["g"][:, -1], Ko, Vo, scale=0.7,
+                            s=None if a["s"] is None else a["s"][:, -1], readout=readout)
+    check("decode o", to_np64(o1), oo, dtype)
+    check("decode K", to_np64(Kc), Ko, dtype)
+    check("decode V", to_np64(Vc), Vo, dtype)
+
+
+@pytest.mark.parametrize("m", [32, 128])
+def test_feature_map_other_slot_counts_packed(oracle, m):
+    """ragged packed sequences (one of them long enough for the segmented scans), m = 32 and 128"""
+    lens = [70, 1, 64 * 50 + 5, 129]
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    cfg, x = _inputs(1, cu[-1], 2, 64, 128, m, "bf16", seed=83, given=False)
+    x["K0"] = x["K0"][:1].repeat(len(lens), 1, 1, 1) * 0.2
+    x["V0"] = x["V0"][:1].repeat(len(lens), 1, 1, 1) * 0.2
+    gs = torch.Generator().manual_seed(84)
+    x["dKT"] = torch.randn(x["K0"].shape, generator=gs) * 0.1
+    x["dVT"] = torch.randn(x["V0"].shape, generator=gs) * 0.1
+    _feature_map_case(oracle, cfg, x, cu=cu)
+
+
+def test_feature_map_with_everything_else_on(oracle):
+    """feature map + gate logits + given intensities + an element-wise read-out in one call"""
+    import paper_2409_07146_amd as gsa
+    from scipy.special import expit, log_expit
+    tau = 8.0
+    cfg, x = _inputs(2, 150, 2, 128, 64, 32, "bf16", seed=86, given=True)
+    gen = torch.Generator().manual_seed(87)
+    u = (torch.randn(x["g"].shape, generator=gen) * 2.0).float()
+    g64 = log_expit(to_np64(u)) / tau
+    x["s"] = (2.0 * torch.rand(u.shape, generator=gen) * -torch.expm1(torch.from_numpy(g64).float())).float()
+    dev = torch.device(DEV)
+    put = lambda t: None if t is None else t.to(dev)
+    d = {n: put(x[n]) for n in ("q", "k", "v", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    ud = u.to(dev)
+    kw = dict(s=d["s"], readout="swish", gate_tau=tau, feature_map="swish")
+    o, z, KT, VT = gsa.gsa_fwd(d["q"], d["k"], d["v"], ud, K0=d["K0"], V0=d["V0"], final_state=True, **kw)
+    res = gsa.gsa_bwd(d["q"], d["k"], d["v"], ud, z, d["dO"], K0=d["K0"], V0=d["V0"], dKT=d["dKT"], dVT=d["dVT"],
+                      initial_state_grad=True, **kw)
+    torch.cuda.synchronize()
+    a = {n: to_np64(x[n]) for n in ("q", "k", "v", "s", "dO", "K0", "V0", "dKT", "dVT")}
+    phi = lambda t: t * expit(t)
+    slope = lambda t: expit(t) * (1.0 + t * (1.0 - expit(t)))
+    f = oracle.fwd(phi(a["q"]), phi(a["k"]), phi(a["v"]), g64, K0=a["K0"], V0=a["V0"], s=a["s"], readout="swish")
+    check("o", to_np64(o), f["o"], "bf16")
+    check("VT", to_np64(VT), f["VT"], "bf16")
+    r = oracle.bwd(phi(a["q"]), phi(a["k"]), phi(a["v"]), g64, a["dO"], K0=a["K0"], V0=a["V0"], dKT=a["dKT"],
+                   dVT=a["dVT"], s=a["s"], readout="swish")
+    r["dg"] = r["dg"] * (1.0 - expit(to_np64(u))) / tau
+    for n in ("q", "k", "v"):
+        r["d" + n] = r["d" + n] * slope(a[n])
+    for n, t in zip(["dq", "dk", "dv", "dg", "dK0", "dV0", "ds"], res):
+        check(n, to_np64(t), r[n], "bf16")
