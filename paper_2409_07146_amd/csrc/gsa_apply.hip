@@ -76,6 +76,15 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
             bx = lin % nx;
             by = (lin / nx) % ny;
             bz = lin / (nx * ny);
+            if (PHI) {
+                // the outputs of one (chunk, head, slice) next to each other as well: the dq workgroup's
+                // token tile (k) is the dk workgroup's raw tile and the other way round, so the second
+                // of them finds it in this XCD's L2
+                const unsigned nout = gridDim.z / (unsigned)H;
+                const unsigned which = (lin / nx) % nout, rest = lin / (nx * nout);
+                by = rest % ny;
+                bz = (rest / ny) + which * (unsigned)H;
+            }
         }
     }
     ChunkInfo ci;
@@ -99,7 +108,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
     TokTile<T, M, L::NS, NT> ts;   // the slot memory's column slice, rows = slots
     ts.template load_snapshot<true>(a.xslot + ch * a.xs_stride, cs, ncols, tid);
     TokTile<T, C, L::NS, NT> tt;   // the token tensor's column slice
-    tt.template load<true>(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);
+    tt.template load<!PHI>(a.xtok + tokh * a.d + cs, (size_t)H * a.d, ci.len, ncols, tid);   // PHI: shared, see above
     // the raw values under this workgroup's output tile, in the thread mapping of the final store
     constexpr int OV = C * (L::NS / 8), OPER = (OV + NT - 1) / NT;
     Raw8<T> rawv[PHI ? OPER : 1];
@@ -109,7 +118,7 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
 #pragma unroll
         for (int u = 0; u < OPER; ++u) {
             const int idx = min(tid + u * NT, C * vpr - 1), t = min(idx / vpr, ci.len - 1), c = (idx - (idx / vpr) * vpr) << 3;
-            rawv[PHI ? u : 0].load_nt(a.raw + tokh * a.d + cs + (size_t)t * H * a.d + c);
+            rawv[PHI ? u : 0].load(a.raw + tokh * a.d + cs + (size_t)t * H * a.d + c);
         }
     }
     // the two small matrices go through LDS: every wave needs all of both
