@@ -238,6 +238,31 @@ def test_feature_map_other_slot_counts_packed(oracle, m):
     _feature_map_case(oracle, cfg, x, cu=cu)
 
 
+def test_feature_map_at_the_layer_shape(oracle):
+    """d = 512, m = 64, bf16, ragged length, several sequences' worth of chunks: the contraction length and
+    the launch shape of the headline workload"""
+    cfg, x = _inputs(2, 64 * 9 + 13, 2, 512, 512, 64, "bf16", seed=88, given=False)
+    _feature_map_case(oracle, cfg, x)
+
+
+def test_feature_map_through_autograd():
+    """gsa_attention passes the option to both calls: same numbers as calling them directly"""
+    import paper_2409_07146_amd as gsa
+    cfg, x = _inputs(2, 100, 2, 64, 128, 32, "bf16", seed=89, given=False)
+    dev = torch.device(DEV)
+    q, k, v, g, dO = (x[n].to(dev) for n in ("q", "k", "v", "g", "dO"))
+    leaves = [t.clone().requires_grad_(True) for t in (q, k, v, g)]
+    o = gsa.gsa_attention(*leaves, feature_map="swish")
+    (o.float() * dO.float()).sum().backward()
+    o2, z2, _, _ = gsa.gsa_fwd(q, k, v, g, feature_map="swish")
+    ref = gsa.gsa_bwd(q, k, v, g, z2, dO, feature_map="swish")
+    assert torch.equal(o, o2)
+    for leaf, r in zip(leaves, ref):
+        assert torch.equal(leaf.grad, r)
+    o3, _, _, _ = gsa.gsa_fwd(q, k, v, g)
+    assert not torch.equal(o3, o2)      # the option does something
+
+
 def test_feature_map_with_everything_else_on(oracle):
     """feature map + gate logits + given intensities + an element-wise read-out in one call"""
     import paper_2409_07146_amd as gsa
