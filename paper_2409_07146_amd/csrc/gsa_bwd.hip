@@ -262,7 +262,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 
     // ---- phase 1: contractions over the head dimension, operands straight from global memory
     //   A[t][r] = q_t . k_r (r <= t),  X[r][i] = <E[i], [k_r | v_r]>,  carry[i] = <E[i], S_end[i]>
-    // Split over the waves in steps of 32 columns (see gated_scores): every wave covers all row
+    // Split over the waves in steps of 64 columns (see gated_scores): every wave covers all row
     // blocks over its share of the columns, the partial sums meet in LDS.
     f32x4 accA[CI], accX[MI];
     GatePrep<M, NT, C, GEN> gp;

@@ -8,7 +8,7 @@
 // X = [k | v], snapshots = memory at chunk start.  Reverse: W = scale*dz*exp(G) (key
 // columns) or p*exp(G) (value columns), X = [q | dO], snapshots = memory gradient at chunk
 // end.  Nothing in W depends on acc, so the weights are produced by chunk-parallel kernels
-// (gate_kernel here, bwd_dz_kernel for the reverse scan) and the sequential loop only
+// (gate_kernel here, chunk_dz_kernel for the reverse scan) and the sequential loop only
 // copies tiles, multiplies and stores:
 //
 //   * one workgroup per (sequence, head, column slice); the slice of acc lives in MFMA
@@ -79,15 +79,21 @@ template <typename T> struct ScanArgs {
 template <typename T, int M, int NS> struct ScanLds {
     static constexpr int C = Geo<T>::C;
     static constexpr int PAD = Atom<T>::kPad;
-    static constexpr int ldw = C + PAD;      // We [M][ldw], XT [NS][ldw]
+    static constexpr int ldw = C + PAD;      // XT [NS][ldw]
     static constexpr int lds = NS + PAD;     // snapshot tile [M][lds]
+    // We [M][C] has no padding: its 8-element groups are XOR-swizzled by the row instead (we_off), which
+    // keeps the fragment reads of 16 rows off each other's banks just as well and, with the decays at
+    // one word per slot, brings a workgroup under a third of a CU's LDS: three are resident instead of
+    // two, which is what lets 640 scan workgroups (d = 640, or five heads) run as one round.
+    static constexpr int GW = C / 8;         // groups per row
+    __device__ static __forceinline__ int we_off(int i, int t8) { return i * C + (((t8 >> 3) ^ (i & (GW - 1))) << 3); }
     // one set per parity of the chunk's position in the walk: a set is written while the other is read
-    static constexpr size_t szW = sizeof(T) * M * ldw, szX = sizeof(T) * NS * ldw, szS = sizeof(T) * M * lds;
+    static constexpr size_t szW = sizeof(T) * M * C, szX = sizeof(T) * NS * ldw, szS = sizeof(T) * M * lds;
     static constexpr size_t oW = 0;
     static constexpr size_t oX = oW + szW;
     static constexpr size_t oSn = oX + szX;
-    static constexpr size_t oDec = oSn + szS;             // chunk decays, fp32: [M] used, one word per thread written
-    static constexpr size_t set = oDec + sizeof(float) * Geo<T>::NT;
+    static constexpr size_t oDec = oSn + szS;             // chunk decays, fp32 [M]
+    static constexpr size_t set = oDec + sizeof(float) * M;
     static constexpr size_t bytes = 2 * set;
 };
 
@@ -225,7 +231,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
     };
     auto fetch = [&](Stage &st, int n) {
         const size_t ch = (size_t)(chunk0 + n) * H + h;
-        st.dec = a.dec[ch * M + (tid < M ? tid : 0)];
+        st.dec = a.dec[ch * M + (tid & (M - 1))];
         const T *Wg = a.W + ch * a.w_parts * M * C + wpart;
 #pragma unroll
         for (int u = 0; u < WV; ++u) {
@@ -272,12 +278,12 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
             const int idx = tid + NT * u;
             if (idx < WVEC) {
                 const int i = idx / (C / 8), tg = idx - i * (C / 8);
-                st.wreg[u].store(w + i * L::ldw + tg * 8);
+                st.wreg[u].store(w + L::we_off(i, tg * 8));
             }
         }
         if (phi) st.xt.template store_transposed<true>(XT(b), L::ldw, NS, tid);
         else st.xt.store_transposed(XT(b), L::ldw, NS, tid);
-        Dec(b)[tid] = st.dec;   // every thread stores (threads >= M a copy of slot 0's): no branch around a loaded value
+        Dec(b)[tid & (M - 1)] = st.dec;   // every thread stores (slots have NT/M writers of the same value): no branch around a loaded value
     };
     // position in the walk -> chunk; positions past the end repeat the last chunk, so that refills can be
     // issued unconditionally (a refill under a branch makes the number of loads in flight unknown to the
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void scan_kernel(Chun
 #pragma unroll
         for (int ks = 0; ks < C / 32; ++ks) {
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) af[ks][mi] = Atom<T>::load(w + (mi * 16 + r) * L::ldw + ks * 32 + g8);
+            for (int mi = 0; mi < MI; ++mi) af[ks][mi] = Atom<T>::load(w + L::we_off(mi * 16 + r, ks * 32 + g8));
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
                 bf[ks][ni] = Atom<T>::load(x + xt_off<C>(wcol + ni * 16 + r, ks * 32 + g8, L::ldw));
