@@ -54,8 +54,8 @@ template <typename T, int M> struct DzLds {
 };
 
 // GEN: the general form (write intensities from `sin` when it is not NULL; opts: read-out in the low
-// byte, kFeatureMapBit for the feature map on v).
-template <typename T, int M, bool GEN>
+// byte).  PHI (with GEN): the feature map on v.
+template <typename T, int M, bool GEN, bool PHI>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(ChunkMap cm, int H, int d_v, float scale,
                                                               const T *__restrict__ v, const T *__restrict__ dO,
                                                               const float *__restrict__ g, const float *__restrict__ z,
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_dz_kernel(
                                reinterpret_cast<float *>(smem + L::oRb), reinterpret_cast<f32x4 *>(smem), dO + tokh * d_v,
                                v + tokh * d_v, (size_t)H * d_v, d_v, Vn, ci.len, tid,
                                (GEN && sin) ? sin + tokh * M : nullptr, gate_tau,
-                               (GEN && (opts & kFeatureMapBit)) ? kHintY : 0);
+                               PHI ? kHintY : 0);
     float zv[MI][4], p[MI][4], rmax[4], rsum[4], pdp[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) rmax[j] = -INFINITY;
@@ -215,10 +215,9 @@ template <typename T> struct IntraArgs {
     float *ds;          // general form: their gradient (with sin)
     int readout;
     float gate_tau;     // general form: > 0 when g holds gate logits
-    int phi;            // general form: feature map on q, k, v
 };
 
-template <typename T, int M, bool GEN>
+template <typename T, int M, bool GEN, bool PHI>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kernel(ChunkMap cm, int H, int d_k, int d_v, float scale,
                                                                  IntraArgs<T> a)
 {
@@ -308,7 +307,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
                 for (int ni = 0; ni < CI; ++ni) fk[hh][ni] = Atom<T>::load(kb + tk[ni] + kk + 32 * hh);
             __builtin_amdgcn_sched_barrier(0);   // all loads of the step before its multiplies (see gated_scores)
-            if (GEN && a.phi) {
+            if (PHI) {
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -336,7 +335,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
                 for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load_nt(SendK + ek[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
-            if (GEN && a.phi) {
+            if (PHI) {
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -369,7 +368,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
                 for (int ni = 0; ni < MI; ++ni) fs[hh][ni] = Atom<T>::load_nt(SendV + ev[ni] + snap_col<M>(kk + 32 * hh));
             __builtin_amdgcn_sched_barrier(0);
-            if (GEN && a.phi) {
+            if (PHI) {
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -625,7 +624,9 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     dim3 grid(pl.chunk_slots, pl.H);
     // 2. dp, dz and the weights of the reverse scan
     {
-        auto kern = pl.general() ? chunk_dz_kernel<T, M, true> : chunk_dz_kernel<T, M, false>;
+        auto kern = !pl.general() ? chunk_dz_kernel<T, M, false, false>
+                    : pl.phi     ? chunk_dz_kernel<T, M, true, true>
+                                 : chunk_dz_kernel<T, M, true, false>;
         const size_t lds = DzLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         KernelTimer kt(kSlotChunkDz, st);
@@ -641,7 +642,9 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
     }
     // 4. everything chunk-local except the wide contractions
     {
-        auto kern = pl.general() ? chunk_intra_kernel<T, M, true> : chunk_intra_kernel<T, M, false>;
+        auto kern = !pl.general() ? chunk_intra_kernel<T, M, false, false>
+                    : pl.phi     ? chunk_intra_kernel<T, M, true, true>
+                                 : chunk_intra_kernel<T, M, true, false>;
         const size_t lds = IntraLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         IntraArgs<T> a;
@@ -652,7 +655,7 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
         a.tAvT = (const T *)w.tAvT;
         a.dg = dg;
         a.tB = (T *)w.tA; a.tBT = (T *)w.tBT; a.tA2T = (T *)w.tA2T; a.tDZe = (T *)w.tP; a.tSbe = (T *)w.tSbe;
-        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout; a.gate_tau = pl.gate_tau; a.phi = pl.phi;
+        a.sin = pl.s_in; a.ds = pl.ds_out; a.readout = pl.readout; a.gate_tau = pl.gate_tau;
         KernelTimer kt(kSlotChunkIntra, st);
         hipLaunchKernelGGL(kern, grid, dim3(Geo<T>::NT), lds, st, cm, pl.H, pl.d_k, pl.d_v, pl.scale, a);
         GSA_HIP_TRY(hipGetLastError());

@@ -110,8 +110,8 @@ template <typename T, int M> struct ChunkFwdLds {
 };
 
 // GEN: the general form (write intensities from `sin` when it is not NULL; opts: read-out in the low
-// byte, kFeatureMapBit for the feature map on q and k).
-template <typename T, int M, bool GEN>
+// byte).  PHI (with GEN): the feature map on q and k.
+template <typename T, int M, bool GEN, bool PHI>
 __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel(ChunkMap cm, int H, int d_k, float scale,
                                                                const T *__restrict__ q, const T *__restrict__ k,
                                                                const float *__restrict__ g,
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_fwd_kernel
         p, unsafe, Gs, Ss, L::ldg, tot, g + tokh * M, (size_t)H * M, As, L::lda, Vt, L::lda, Rb,
         reinterpret_cast<f32x4 *>(smem), q + tokh * d_k, k + tokh * d_k,
         (size_t)H * d_k, d_k, Kn, ci.len, tid, (GEN && sin) ? sin + tokh * M : nullptr, gate_tau,
-        (GEN && (opts & kFeatureMapBit)) ? (kHintX | kHintY) : 0);
+        PHI ? (kHintX | kHintY) : 0);
     // ---- softmax over the slots, in registers
     float rmax[4], rsum[4];
 #pragma unroll
@@ -276,7 +276,9 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     {
-        auto kern = pl.general() ? chunk_fwd_kernel<T, M, true> : chunk_fwd_kernel<T, M, false>;
+        auto kern = !pl.general() ? chunk_fwd_kernel<T, M, false, false>
+                    : pl.phi     ? chunk_fwd_kernel<T, M, true, true>
+                                 : chunk_fwd_kernel<T, M, true, false>;
         const size_t lds = ChunkFwdLds<T, M>::bytes;
         GSA_HIP_TRY(allow_lds(kern, lds));
         dim3 grid(pl.chunk_slots, pl.H);
