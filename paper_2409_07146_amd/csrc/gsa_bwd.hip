@@ -401,18 +401,6 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) accX[ni] = own[CI + ni];
     }
-    // What phase 2b needs from global memory is asked for here, a few microseconds ahead: issued where it
-    // is used, each of the two loads costs the wave a full trip to memory in the middle of the tail
-    // (measured 5.2 us for the phase against 1 us for its neighbours).
-    typename Atom<T>::Frag avt[C / 32];
-#pragma unroll
-    for (int u = 0; u < C / 32; ++u) avt[u] = Atom<T>::load(AvT + (rowb + r) * C + u * 32 + g8);
-    float dgfv[MI][4];
-#pragma unroll
-    for (int ni = 0; ni < MI; ++ni)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            dgfv[ni][j] = a.dgf[(tokh + (size_t)min(rowb + g4 + j, ci.len - 1) * H) * M + ni * 16 + r];
     // gate tiles; p and dz tiles (they overwrite the reduction buffer, which every wave has left by now)
     gp.finish(Gs, Ss, L::ldg, tot, ci.len, tid);
     if (!GEN || a.readout == kReadSoftmax) sr.finish(Pf, Df, L::ldg, ci.len, tid);
@@ -457,12 +445,9 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
 #pragma unroll
         for (int ni = 0; ni < MI; ++ni) gend[ni] = Gs[(rowb + 15) * L::ldg + ni * 16 + r];
         // LDS reads are unconditional (every token of the tile exists); masking is a register select
-#pragma unroll
-        for (int u = 0; u < C / 32; ++u) {
-            const int k0 = 32 * u;
-            if (k0 < (tstart & ~31)) continue;   // wave-uniform: tokens before the block meet zero weights only
+        for (int k0 = (tstart & ~31); k0 < C; k0 += 32) {
             const typename Atom<T>::Frag aA = Atom<T>::load(ATs + (rowb + r) * L::lda + k0 + g8);
-            const typename Atom<T>::Frag aAv = avt[u];
+            const typename Atom<T>::Frag aAv = Atom<T>::load(AvT + (rowb + r) * C + k0 + g8);
 #pragma unroll
             for (int ni = 0; ni < MI; ++ni) {
                 const int i = ni * 16 + r;
@@ -504,7 +489,8 @@ __global__ __launch_bounds__(Geo<T>::NT, (M > 64 ? 1 : 2)) void chunk_intra_kern
                     ds += sum;
                 }
                 const float sv = Ss[rr * L::ldg + i];
-                const float f = (rr < ci.len) ? dgfv[ni][j] : 0.f;
+                const float fl = a.dgf[(tokh + (size_t)min(rr, ci.len - 1) * H) * M + i];
+                const float f = (rr < ci.len) ? fl : 0.f;
                 dGam[ni][j] = f - sv * ds;
                 ads[ni][j] = given ? ds : (1.f - sv) * ds;   // tied: d(1 - e^g)/dg = -e^g = -(1 - s)
             }
