@@ -282,13 +282,14 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(int d_v, const floa
 template <typename T, int M, int NV>
 static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
                                    const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                   const float *sin, int readout, float gate_tau, hipStream_t st)
+                                   const float *sin, int opts, float gate_tau, hipStream_t st)
 {
     if (scratch && BH <= kSplitPairsMax) {
         // few pairs: m/4 workgroups of four waves per pair (one slot row per wave)
         constexpr int pieces = M / kSplitWaves;
         const size_t lds = (128 + (size_t)kSplitWaves * d_v) * sizeof(float);
-        const bool gen = sin != nullptr || readout != kReadSoftmax || gate_tau > 0.f;
+        // opts is non-zero for a read-out other than the softmax and for the feature map
+        const bool gen = sin != nullptr || opts != kReadSoftmax || gate_tau > 0.f;
         auto kern = gen ? decode_kernel<T, M, NV, true, kSplitWaves, pieces, true>
                         : decode_kernel<T, M, NV, true, kSplitWaves, pieces, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -297,54 +298,54 @@ static hipError_t launch_decode_nv(int BH, int d_k, int d_v, float scale, const 
         {
             KernelTimer kt(kSlotDecode, st);
             hipLaunchKernelGGL(kern, dim3(BH * pieces), dim3(kSplitWaves * kWave), lds, st, d_k, d_v, scale,
-                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch, sin, readout,
+                               (const T *)q, (const T *)k, (const T *)v, g, K, V, (T *)o, scratch, sin, opts,
                                gate_tau);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
         KernelTimer kt(kSlotDecodeMerge, st);
         const dim3 mgrid((d_v + 4 * kWave - 1) / (4 * kWave), BH);
-        hipLaunchKernelGGL((decode_merge_kernel<T, pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o, readout & kReadoutMask);
+        hipLaunchKernelGGL((decode_merge_kernel<T, pieces>), mgrid, dim3(kWave), 0, st, d_v, scratch, (T *)o, opts & kReadoutMask);
         return hipGetLastError();
     }
     const size_t lds = (128 + (size_t)kDecWaves * d_v) * sizeof(float);
     constexpr bool early = (NV * (M / kDecWaves) <= 8);
-    const bool gen = sin != nullptr || readout != kReadSoftmax || gate_tau > 0.f;
+    const bool gen = sin != nullptr || opts != kReadSoftmax || gate_tau > 0.f;
     auto kern = gen ? decode_kernel<T, M, NV, early, kDecWaves, 0, true> : decode_kernel<T, M, NV, early, kDecWaves, 0, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     KernelTimer kt(kSlotDecode, st);
     hipLaunchKernelGGL(kern, dim3(BH), dim3(kDecThreads), lds, st, d_k, d_v, scale, (const T *)q, (const T *)k,
-                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr), sin, readout, gate_tau);
+                       (const T *)v, g, K, V, (T *)o, static_cast<float *>(nullptr), sin, opts, gate_tau);
     return hipGetLastError();
 }
 
 template <typename T, int M>
 static hipError_t launch_decode_m(int BH, int d_k, int d_v, float scale, const void *q, const void *k,
                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                  const float *sin, int readout, float gate_tau, hipStream_t st)
+                                  const float *sin, int opts, float gate_tau, hipStream_t st)
 {
     const int dmax = d_k > d_v ? d_k : d_v;
     const int nv = (dmax + 255) / 256;
     switch (nv) {
-    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    case 1: return launch_decode_nv<T, M, 1>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    case 2: return launch_decode_nv<T, M, 2>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    case 3: return launch_decode_nv<T, M, 3>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    default: return launch_decode_nv<T, M, 4>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
     }
 }
 
 template <typename T>
 static hipError_t launch_decode_t(int BH, int d_k, int d_v, int m, float scale, const void *q, const void *k,
                                   const void *v, const float *g, float *K, float *V, void *o, float *scratch,
-                                  const float *sin, int readout, float gate_tau, hipStream_t st)
+                                  const float *sin, int opts, float gate_tau, hipStream_t st)
 {
     switch (m) {
-    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    case 16: return launch_decode_m<T, 16>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    case 32: return launch_decode_m<T, 32>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    case 64: return launch_decode_m<T, 64>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    default: return launch_decode_m<T, 128>(BH, d_k, d_v, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
     }
 }
 
@@ -357,10 +358,10 @@ size_t decode_scratch_floats(int BH, int d_v, int m)
 
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,
                          const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
-                         int readout, float gate_tau, hipStream_t st)
+                         int opts, float gate_tau, hipStream_t st)
 {
-    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
-    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, readout, gate_tau, st);
+    if (dtype == 0) return launch_decode_t<float>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
+    return launch_decode_t<bf16_t>(BH, d_k, d_v, m, scale, q, k, v, g, K, V, o, scratch, sin, opts, gate_tau, st);
 }
 
 }  // namespace gsa
