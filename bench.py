@@ -134,7 +134,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the operator has no cross-GPU path); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+              "--gpus %d with WORLD_SIZE=%s is not supported" % (args.gpus, os.environ.get("WORLD_SIZE", "1")),
+              file=sys.stderr)
         sys.exit(2)
 
     if args.workload == "prefill_decode":
