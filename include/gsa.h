@@ -21,8 +21,10 @@
  *     z_saved and every memory (slot state) are fp32.  Accumulation is fp32.
  *   - g must be <= 0.  Values below -30 are treated as -30 (alpha = 9e-14,
  *     below fp32 resolution of the result).  NaN gates give NaN outputs.
- *   - Outputs must not overlap inputs or each other (the decode step updates
- *     its memories in place, that is its contract).
+ *   - Outputs must not overlap inputs, the workspace or each other: gsa_fwd*
+ *     and gsa_bwd* check this on the host and return GSA_ERR_SHAPE (the decode
+ *     step updates its memories in place, that is its contract; its other
+ *     arguments are the caller's to keep apart).
  *   - Errors are return codes; arguments are validated on the host before any
  *     device work is enqueued, and a failed call enqueues nothing.
  *   - Supported shapes: m in {16, 32, 64, 128}; d_k and d_v
@@ -128,12 +130,12 @@ gsa_status gsa_bwd(const gsa_problem *p,
  *           identity, Swish z*sigmoid(z), ReLU, or ReLU squared.
  *   gate_tau 0: g is the log gate, as in gsa_fwd.  > 0: g holds gate LOGITS u and
  *           the log gate is logsigmoid(u) / gate_tau, i.e. the layer's
- *           alpha = sigmoid(W x)^(1/tau) of Section 3.2 (tau = 8 in the paper)
+ *           alpha = sigmoid(W x)^(1/tau) of Section 3.3 (tau = 8 in the paper)
  *           evaluated inside the kernels; gsa_bwd_ex then returns in dg the
  *           gradient with respect to the logits.
  *   feature_map GSA_FEATURE_NONE: q, k, v enter Eq. (gsa) as given.  GSA_FEATURE_SWISH:
  *           they hold the layer's raw projections W_q x, W_k x, W_v x and the
- *           kernels apply phi(x) = x*sigmoid(x) of Section 3.2 to them as they load
+ *           kernels apply phi(x) = x*sigmoid(x) of Section 3.3 to them as they load
  *           them (rounded once more to dtype, since they feed the matrix
  *           cores); gsa_bwd_ex then returns dq, dk, dv with respect to the raw
  *           values.
@@ -196,6 +198,24 @@ gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, in
                               const void *q, const void *k, const void *v, const float *g,
                               float *K_state, float *V_state, void *o,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * gsa_decode_step_ws for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * split form's partial read-outs go through an array built into the library (4 MiB of device
+ * memory per GPU, held until the process ends) instead of a caller's workspace; the call
+ * allocates nothing and frees nothing.  The array's address is looked up on the first call on
+ * each device (make that call outside a capture).  Arguments and results as for
+ * gsa_decode_step_ws on the same inputs.  A problem whose split form needs more than the array
+ * holds -- B*H <= 64 and B*H * (m/4) * (d_v + 2) > 1,048,576 floats -- returns
+ * GSA_ERR_WORKSPACE and enqueues nothing (above 64 memory pairs no scratch is needed and any
+ * size is taken).  Every call on one GPU shares that GPU's array: calls that overlap in time on
+ * one GPU (different streams, or threads) race; nothing in it needs clearing between calls.
+ */
+gsa_status gsa_decode_step_static(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m,
+                                  int32_t dtype, float scale,
+                                  const void *q, const void *k, const void *v, const float *g,
+                                  float *K_state, float *V_state, void *o, void *stream);
 
 /*
  * The decode step (Eq. (gsa), decode form) with the options of gsa_fwd_ex (Algorithm 1's

@@ -80,12 +80,8 @@ static void readout_fwd(int ro, int m, const double *z, double *p)
     }
 }
 
-/* dz from dp (p = f(z) as computed by readout_fwd).  ReLU's slope jumps at z = 0; zdec, when
- * not NULL, supplies the scores whose SIGN takes that decision (a caller comparing against an
- * implementation in lower precision passes that implementation's scores, so that both sides
- * decide alike); every value still comes from z. */
-static void readout_bwd(int ro, int m, const double *z, const double *zdec, const double *p, const double *dp,
-                        double *dz)
+/* dz from dp (p = f(z) as computed by readout_fwd).  ReLU's slope at z = 0 is taken as 0. */
+static void readout_bwd(int ro, int m, const double *z, const double *p, const double *dp, double *dz)
 {
     if (ro == RO_SOFTMAX) {
         double pdp = 0.0;
@@ -97,7 +93,7 @@ static void readout_bwd(int ro, int m, const double *z, const double *zdec, cons
         double x = z[i], d;
         if (ro == RO_IDENTITY) d = 1.0;
         else if (ro == RO_SWISH) { double sg = sigmoid(x); d = sg + x * sg * (1.0 - sg); }
-        else if (ro == RO_RELU) d = (zdec ? zdec[i] : x) > 0.0 ? 1.0 : 0.0;
+        else if (ro == RO_RELU) d = x > 0.0 ? 1.0 : 0.0;
         else d = x > 0.0 ? 2.0 * x : 0.0;
         dz[i] = d * dp[i];
     }
@@ -186,19 +182,20 @@ int gsa_oracle_fwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
 
 /*
  * Backward of L = sum_t <dO_t, o_t> + <dKT, K_T> + <dVT, V_T>.
- * dO [Ttot,H,dv]; dKT,dVT [n_seqs,H,m,d] (may be NULL = zero); zdec [Ttot,H,m] or NULL, see readout_bwd.
+ * dO [Ttot,H,dv]; dKT,dVT [n_seqs,H,m,d] (may be NULL = zero).
  * Outputs (double): dq,dk [Ttot,H,dk], dv [Ttot,H,dv], dg [Ttot,H,m] (gradient
  * with respect to the log forget gate g, with s = 1 - exp(g) coupled to it when
  * sin is NULL; with sin given, dg is the gradient through the decay alone and
  * dsin [Ttot,H,m] receives the gradient of the write intensity),
- * dK0,dV0 [n_seqs,H,m,d] (may be NULL).
+ * dK0,dV0 [n_seqs,H,m,d] (may be NULL); dp_out, dz_out [Ttot,H,m] (may be NULL): the gradients with
+ * respect to the read weights p_t and the scores z_t, the two intermediates of the chain.
  */
 int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, double scale, int readout,
                    const double *q, const double *k, const double *v, const double *g, const double *sin,
-                   const double *K0, const double *V0, const double *dO, const double *zdec,
+                   const double *K0, const double *V0, const double *dO,
                    const double *dKT, const double *dVT,
                    double *dq, double *dkk, double *dvv, double *dg, double *dsin,
-                   double *dK0, double *dV0)
+                   double *dK0, double *dV0, double *dp_out, double *dz_out)
 {
     int fail = 0;
     const size_t nK = (size_t)m * dk, nV = (size_t)m * dv;
@@ -283,7 +280,9 @@ int gsa_oracle_bwd(int n_seqs, const int32_t *cu, int H, int dk, int dv, int m, 
                         dp[i] = acc;
                     }
                     /* p = f(z) */
-                    readout_bwd(readout, m, z, zdec ? zdec + th * m : NULL, p, dp, dz);
+                    readout_bwd(readout, m, z, p, dp, dz);
+                    if (dp_out) memcpy(dp_out + th * m, dp, sizeof(double) * (size_t)m);
+                    if (dz_out) memcpy(dz_out + th * m, dz, sizeof(double) * (size_t)m);
                     /* z = scale * K q  =>  dq = scale K^T dz,  dK += scale dz (x) q */
                     for (int cc = 0; cc < dk; ++cc) dq[th * dk + cc] = 0.0;
                     for (int i = 0; i < m; ++i) {

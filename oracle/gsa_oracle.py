@@ -26,7 +26,8 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 def _lib():
     global _LIB
     if _LIB is None:
-        path = os.path.join(_HERE, "liboracle.so")
+        # GSA_ORACLE_LIB: another build of the same source (the sanitizer run of the tests sets it)
+        path = os.environ.get("GSA_ORACLE_LIB") or os.path.join(_HERE, "liboracle.so")
         if not os.path.exists(path):
             from . import build as _b  # type: ignore
             _b.build()
@@ -40,8 +41,8 @@ def _lib():
         lib.gsa_oracle_bwd.restype = ctypes.c_int
         lib.gsa_oracle_bwd.argtypes = [ctypes.c_int, _i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_int, ctypes.c_double, ctypes.c_int,
-                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p,
-                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p]
+                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p,
+                                       _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p, _f64p]
         lib.gsa_oracle_decode_step.restype = ctypes.c_int
         lib.gsa_oracle_decode_step.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_double, ctypes.c_int, _f64p, _f64p, _f64p, _f64p, _f64p,
@@ -98,12 +99,12 @@ def fwd(q, k, v, g, cu_seqlens=None, K0=None, V0=None, scale=1.0, s=None, readou
 
 
 def bwd(q, k, v, g, dO, cu_seqlens=None, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, s=None,
-        readout="softmax", z_decide=None):
-    """Returns dict(dq, dk, dv, dg, dK0, dV0) and, when s is given, ds; all float64.
-    z_decide [B,T,H,m]: scores whose sign decides ReLU's slope (None: the oracle's own)."""
-    q, k, v, g, dO, s, z_decide = _f64(q), _f64(k), _f64(v), _f64(g), _f64(dO), _f64(s), _f64(z_decide)
+        readout="softmax", intermediates=False):
+    """Returns dict(dq, dk, dv, dg, dK0, dV0) and, when s is given, ds; all float64.  With
+    intermediates=True also dp and dz [B,T,H,m], the gradients with respect to the read weights and the
+    scores."""
+    q, k, v, g, dO, s = _f64(q), _f64(k), _f64(v), _f64(g), _f64(dO), _f64(s)
     assert s is None or s.shape == g.shape
-    assert z_decide is None or z_decide.shape == g.shape
     B, T, H, dk = q.shape
     dv, m = v.shape[-1], g.shape[-1]
     cu = _seqs(q, cu_seqlens)
@@ -116,15 +117,19 @@ def bwd(q, k, v, g, dO, cu_seqlens=None, K0=None, V0=None, dKT=None, dVT=None, s
     ds = None if s is None else np.empty((B, T, H, m), np.float64)
     dK0 = np.empty((n, H, m, dk), np.float64)
     dV0 = np.empty((n, H, m, dv), np.float64)
+    dp = np.empty((B, T, H, m), np.float64) if intermediates else None
+    dz = np.empty((B, T, H, m), np.float64) if intermediates else None
     rc = _lib().gsa_oracle_bwd(n, cu.ctypes.data_as(_i32p), H, dk, dv, m, float(scale), READOUTS[readout],
                                _p64(q), _p64(k), _p64(v), _p64(g), _p64(s), _p64(K0), _p64(V0), _p64(dO),
-                               _p64(z_decide), _p64(dKT), _p64(dVT),
-                               _p64(dq), _p64(dk_), _p64(dv_), _p64(dg), _p64(ds), _p64(dK0), _p64(dV0))
+                               _p64(dKT), _p64(dVT),
+                               _p64(dq), _p64(dk_), _p64(dv_), _p64(dg), _p64(ds), _p64(dK0), _p64(dV0), _p64(dp), _p64(dz))
     if rc != 0:
         raise MemoryError("gsa_oracle_bwd failed")
     out = dict(dq=dq, dk=dk_, dv=dv_, dg=dg, dK0=dK0, dV0=dV0)
     if ds is not None:
         out["ds"] = ds
+    if intermediates:
+        out["dp"], out["dz"] = dp, dz
     return out
 
 

@@ -7,7 +7,8 @@ LIB_PATH = os.path.join(_HERE, "libgsa.so")
 
 # every symbol include/gsa.h declares
 EXPORTS = ("gsa_status_string", "gsa_abi_version", "gsa_workspace_bytes", "gsa_fwd", "gsa_bwd", "gsa_fwd_ex", "gsa_bwd_ex",
-           "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_decode_step_ws", "gsa_decode_step_ex", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read", "gsa_profile_copy")
+           "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_decode_step_ws", "gsa_decode_step_ex",
+           "gsa_decode_step_static", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read", "gsa_profile_copy")
 
 
 class GsaProblem(ctypes.Structure):
@@ -47,6 +48,8 @@ def load():
     lib.gsa_bwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32, i32] + [vp] * 18 + [vp, ctypes.c_size_t, vp]
     lib.gsa_decode_step.restype = ctypes.c_int
     lib.gsa_decode_step.argtypes = [i32, i32, i32, i32, i32, i32, f32] + [vp] * 8
+    lib.gsa_decode_step_static.restype = ctypes.c_int
+    lib.gsa_decode_step_static.argtypes = [i32, i32, i32, i32, i32, i32, f32] + [vp] * 8
     lib.gsa_decode_workspace_bytes.restype = ctypes.c_int
     lib.gsa_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.gsa_decode_step_ws.restype = ctypes.c_int

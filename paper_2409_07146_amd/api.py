@@ -102,9 +102,9 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
     VT = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if final_state else None
     if s is not None or readout != "softmax" or gate_tau or feature_map != "none":
         _check(s, "s", torch.float32, (B, T, H, m), optional=True)
-        rc = _lib.load().gsa_fwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map], _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
-                                    _ptr(K0), _ptr(V0), _ptr(o), _ptr(z), _ptr(KT), _ptr(VT), _ptr(workspace),
-                                    workspace.numel(), _stream(q))
+        rc = _lib.load().gsa_fwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map],
+                                    _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s), _ptr(K0), _ptr(V0), _ptr(o), _ptr(z),
+                                    _ptr(KT), _ptr(VT), _ptr(workspace), workspace.numel(), _stream(q))
         if rc != 0:
             raise GsaError(rc, "gsa_fwd_ex")
         return o, z, KT, VT
@@ -139,10 +139,10 @@ def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale
     if s is not None or readout != "softmax" or gate_tau or feature_map != "none":
         _check(s, "s", torch.float32, (B, T, H, m), optional=True)
         ds = None if s is None else torch.empty_like(g)
-        rc = _lib.load().gsa_bwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map], _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s),
-                                    _ptr(K0), _ptr(V0), _ptr(z_saved), _ptr(dO), _ptr(dKT), _ptr(dVT), _ptr(dq),
-                                    _ptr(dk), _ptr(dv), _ptr(dg), _ptr(ds), _ptr(dK0), _ptr(dV0), _ptr(workspace),
-                                    workspace.numel(), _stream(q))
+        rc = _lib.load().gsa_bwd_ex(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map],
+                                    _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s), _ptr(K0), _ptr(V0), _ptr(z_saved),
+                                    _ptr(dO), _ptr(dKT), _ptr(dVT), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(ds),
+                                    _ptr(dK0), _ptr(dV0), _ptr(workspace), workspace.numel(), _stream(q))
         if rc != 0:
             raise GsaError(rc, "gsa_bwd_ex")
         return (dq, dk, dv, dg, dK0, dV0) if s is None else (dq, dk, dv, dg, dK0, dV0, ds)
@@ -204,6 +204,26 @@ def gsa_decode_step(q, k, v, g, K_state, V_state, scale=1.0, out=None, workspace
     if rc != 0:
         raise GsaError(rc, "gsa_decode_step")
     return o
+
+
+def gsa_decode_step_static(q, k, v, g, K_state, V_state, out, scale=1.0):
+    """gsa_decode_step_static of the C ABI: the decode step for callers that cannot allocate (the split
+    form's scratch is an array inside the library).  `out` [B,H,d_v] is required: nothing is allocated
+    here either.  Raises GsaError (workspace) when the problem exceeds the built-in scratch."""
+    B, H, d_k = q.shape
+    d_v, m = v.shape[-1], g.shape[-1]
+    if q.dtype not in _DTYPES:
+        raise ValueError("q,k,v must be float32 or bfloat16")
+    _check(q, "q", q.dtype, (B, H, d_k)); _check(k, "k", q.dtype, (B, H, d_k))
+    _check(v, "v", q.dtype, (B, H, d_v)); _check(g, "g", torch.float32, (B, H, m))
+    _check(K_state, "K_state", torch.float32, (B, H, m, d_k))
+    _check(V_state, "V_state", torch.float32, (B, H, m, d_v))
+    _check(out, "out", q.dtype, (B, H, d_v))
+    rc = _lib.load().gsa_decode_step_static(B, H, d_k, d_v, m, _DTYPES[q.dtype], float(scale), _ptr(q), _ptr(k),
+                                            _ptr(v), _ptr(g), _ptr(K_state), _ptr(V_state), _ptr(out), _stream(q))
+    if rc != 0:
+        raise GsaError(rc, "gsa_decode_step_static")
+    return out
 
 
 def gsa_profile_enable(on: bool) -> None:

@@ -112,6 +112,28 @@ Work make_work(const Plan &pl, void *ws)
     return w;
 }
 
+// An argument's bytes; n = 0 or p = NULL: absent.
+struct Span {
+    const void *p;
+    size_t n;
+};
+
+// True when some output (the first n_out spans) shares a byte with any other span.
+bool outputs_overlap(const Span *spans, int n_out, int n_all)
+{
+    for (int i = 0; i < n_out; ++i) {
+        if (!spans[i].p || !spans[i].n) continue;
+        const uintptr_t a0 = reinterpret_cast<uintptr_t>(spans[i].p), a1 = a0 + spans[i].n;
+        for (int j = 0; j < n_all; ++j) {
+            if (j == i || !spans[j].p || !spans[j].n) continue;
+            if (j < i && j < n_out) continue;   // that pair was looked at from the other side
+            const uintptr_t b0 = reinterpret_cast<uintptr_t>(spans[j].p), b1 = b0 + spans[j].n;
+            if (a0 < b1 && b0 < a1) return true;
+        }
+    }
+    return false;
+}
+
 gsa_status check_workspace(void *ws, size_t have, size_t need)
 {
     if (need == 0) return GSA_OK;
@@ -169,9 +191,10 @@ const char *gsa_status_string(gsa_status s)
     switch (s) {
     case GSA_OK: return "ok";
     case GSA_ERR_NULL: return "a required pointer is NULL";
-    case GSA_ERR_SHAPE: return "a dimension is out of range or inconsistent";
+    case GSA_ERR_SHAPE: return "a dimension is out of range or inconsistent, or an output overlaps another argument";
     case GSA_ERR_UNSUPPORTED: return "shape not supported by this build";
-    case GSA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GSA_ERR_WORKSPACE:
+        return "workspace missing, misaligned or too small (or the problem exceeds the built-in scratch)";
     case GSA_ERR_HIP: return "HIP runtime error at launch";
     }
     return "unknown status";
@@ -190,9 +213,10 @@ gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes
 }
 
 namespace {
-gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v, const float *g,
-                   const float *s, const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
-                   void *workspace, size_t workspace_bytes, void *stream)
+gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q,
+                   const void *k, const void *v, const float *g, const float *s, const float *K0, const float *V0,
+                   void *o, float *z_saved, float *KT, float *VT, void *workspace, size_t workspace_bytes,
+                   void *stream)
 {
     Plan pl;
     gsa_status st = make_plan(p, &pl);
@@ -207,6 +231,15 @@ gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_
         return GSA_ERR_SHAPE;
     st = check_workspace(workspace, workspace_bytes, pl.total_fwd);
     if (st != GSA_OK) return st;
+    {
+        const size_t esz = pl.dtype == GSA_BF16 ? 2 : 4, th = (size_t)pl.tokens * pl.H, M = pl.m;
+        const size_t nk = th * pl.d_k * esz, nv = th * pl.d_v * esz, nm = th * M * sizeof(float);
+        const size_t sk = (size_t)pl.n_seqs * pl.H * M * pl.d_k * sizeof(float);
+        const size_t sv = (size_t)pl.n_seqs * pl.H * M * pl.d_v * sizeof(float);
+        const Span spans[] = {{o, nv}, {z_saved, nm}, {KT, sk}, {VT, sv}, {workspace, pl.total_fwd},
+                              {q, nk}, {k, nk}, {v, nv}, {g, nm}, {s, nm}, {K0, sk}, {V0, sv}};
+        if (outputs_overlap(spans, 5, (int)(sizeof(spans) / sizeof(spans[0])))) return GSA_ERR_SHAPE;
+    }
     pl.s_in = s;
     pl.readout = readout;
     pl.gate_tau = gate_tau;
@@ -217,10 +250,11 @@ gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_
     return e == hipSuccess ? GSA_OK : GSA_ERR_HIP;
 }
 
-gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v, const float *g,
-                   const float *s, const float *K0, const float *V0, const float *z_saved, const void *dO,
-                   const float *dKT, const float *dVT, void *dq, void *dk, void *dv, float *dg, float *ds, float *dK0,
-                   float *dV0, void *workspace, size_t workspace_bytes, void *stream)
+gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q,
+                   const void *k, const void *v, const float *g, const float *s, const float *K0, const float *V0,
+                   const float *z_saved, const void *dO, const float *dKT, const float *dVT, void *dq, void *dk,
+                   void *dv, float *dg, float *ds, float *dK0, float *dV0, void *workspace, size_t workspace_bytes,
+                   void *stream)
 {
     Plan pl;
     gsa_status st = make_plan(p, &pl);
@@ -236,6 +270,17 @@ gsa_status bwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_
         if (!aligned16(ptr)) return GSA_ERR_SHAPE;
     st = check_workspace(workspace, workspace_bytes, pl.total_bwd);
     if (st != GSA_OK) return st;
+    {
+        const size_t esz = pl.dtype == GSA_BF16 ? 2 : 4, th = (size_t)pl.tokens * pl.H, M = pl.m;
+        const size_t nk = th * pl.d_k * esz, nv = th * pl.d_v * esz, nm = th * M * sizeof(float);
+        const size_t sk = (size_t)pl.n_seqs * pl.H * M * pl.d_k * sizeof(float);
+        const size_t sv = (size_t)pl.n_seqs * pl.H * M * pl.d_v * sizeof(float);
+        const Span spans[] = {{dq, nk}, {dk, nk}, {dv, nv}, {dg, nm}, {s ? ds : nullptr, nm}, {dK0, sk}, {dV0, sv},
+                              {workspace, pl.total_bwd},
+                              {q, nk}, {k, nk}, {v, nv}, {g, nm}, {s, nm}, {K0, sk}, {V0, sv}, {z_saved, nm},
+                              {dO, nv}, {dKT, sk}, {dVT, sv}};
+        if (outputs_overlap(spans, 8, (int)(sizeof(spans) / sizeof(spans[0])))) return GSA_ERR_SHAPE;
+    }
     pl.s_in = s;
     pl.ds_out = s ? ds : nullptr;
     pl.readout = readout;
@@ -252,15 +297,17 @@ gsa_status gsa_fwd(const gsa_problem *p, const void *q, const void *k, const voi
                    const float *K0, const float *V0, void *o, float *z_saved, float *KT, float *VT,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    return fwd_any(p, GSA_READOUT_SOFTMAX, 0.f, GSA_FEATURE_NONE, q, k, v, g, nullptr, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes,
-                   stream);
+    return fwd_any(p, GSA_READOUT_SOFTMAX, 0.f, GSA_FEATURE_NONE, q, k, v, g, nullptr, K0, V0, o, z_saved, KT, VT,
+                   workspace, workspace_bytes, stream);
 }
 
-gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v,
-                      const float *g, const float *s, const float *K0, const float *V0, void *o, float *z_saved,
-                      float *KT, float *VT, void *workspace, size_t workspace_bytes, void *stream)
+gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q,
+                      const void *k, const void *v, const float *g, const float *s, const float *K0,
+                      const float *V0, void *o, float *z_saved, float *KT, float *VT, void *workspace,
+                      size_t workspace_bytes, void *stream)
 {
-    return fwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace, workspace_bytes, stream);
+    return fwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace,
+                   workspace_bytes, stream);
 }
 
 gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
@@ -268,17 +315,18 @@ gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const voi
                    const float *dVT, void *dq, void *dk, void *dv, float *dg, float *dK0, float *dV0,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    return bwd_any(p, GSA_READOUT_SOFTMAX, 0.f, GSA_FEATURE_NONE, q, k, v, g, nullptr, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, nullptr,
-                   dK0, dV0, workspace, workspace_bytes, stream);
+    return bwd_any(p, GSA_READOUT_SOFTMAX, 0.f, GSA_FEATURE_NONE, q, k, v, g, nullptr, K0, V0, z_saved, dO, dKT, dVT,
+                   dq, dk, dv, dg, nullptr, dK0, dV0, workspace, workspace_bytes, stream);
 }
 
-gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k, const void *v,
-                      const float *g, const float *s, const float *K0, const float *V0, const float *z_saved,
-                      const void *dO, const float *dKT, const float *dVT, void *dq, void *dk, void *dv, float *dg,
-                      float *ds, float *dK0, float *dV0, void *workspace, size_t workspace_bytes, void *stream)
+gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q,
+                      const void *k, const void *v, const float *g, const float *s, const float *K0,
+                      const float *V0, const float *z_saved, const void *dO, const float *dKT, const float *dVT,
+                      void *dq, void *dk, void *dv, float *dg, float *ds, float *dK0, float *dV0, void *workspace,
+                      size_t workspace_bytes, void *stream)
 {
-    return bwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, ds, dK0, dV0, workspace,
-                   workspace_bytes, stream);
+    return bwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg,
+                   ds, dK0, dV0, workspace, workspace_bytes, stream);
 }
 
 gsa_status gsa_decode_step(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
@@ -299,11 +347,26 @@ gsa_status gsa_decode_workspace_bytes(int32_t B, int32_t H, int32_t d_k, int32_t
 
 gsa_status gsa_decode_step_ex(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,
                               int32_t readout, float gate_tau, int32_t feature_map, const void *q, const void *k,
-                              const void *v, const float *g, const float *s, float *K_state, float *V_state, void *o, void *workspace,
-                              size_t workspace_bytes, void *stream)
+                              const void *v, const float *g, const float *s, float *K_state, float *V_state,
+                              void *o, void *workspace, size_t workspace_bytes, void *stream)
 {
     return decode_any(B, H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o, workspace != nullptr,
                       workspace, workspace_bytes, stream, s, readout, gate_tau, feature_map);
+}
+
+gsa_status gsa_decode_step_static(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype,
+                                  float scale, const void *q, const void *k, const void *v, const float *g,
+                                  float *K_state, float *V_state, void *o, void *stream)
+{
+    const gsa_status st = decode_checks(B, H, d_k, d_v, m, dtype, scale);
+    if (st != GSA_OK) return st;
+    if (B == 0) return GSA_OK;
+    const size_t need = gsa::decode_scratch_floats(B * H, d_v, m);
+    if (need > gsa::decode_static_scratch_floats()) return GSA_ERR_WORKSPACE;   // beyond the built-in scratch
+    float *scratch = nullptr;
+    if (need && gsa::decode_static_scratch(&scratch) != hipSuccess) return GSA_ERR_HIP;
+    return decode_any(B, H, d_k, d_v, m, dtype, scale, q, k, v, g, K_state, V_state, o, need != 0, scratch,
+                      need * sizeof(float), stream);
 }
 
 gsa_status gsa_decode_step_ws(int32_t B, int32_t H, int32_t d_k, int32_t d_v, int32_t m, int32_t dtype, float scale,

@@ -21,7 +21,7 @@
 // tile; the two small matrices are staged once per workgroup.  ~37 KB of LDS per workgroup, so
 // several workgroups are resident per CU and their loads overlap.
 //
-// With the feature map on q, k, v (Section 3.2; the PHI instantiation) the token operand gets
+// With the feature map on q, k, v (Section 3.3; the PHI instantiation) the token operand gets
 // phi(x) = x sigmoid(x) on its way into LDS where it is one of q, k, v, and the three backward
 // outputs leave multiplied by phi'(raw) of the tensor they are the gradient of.
 #include "gsa_chunk.h"

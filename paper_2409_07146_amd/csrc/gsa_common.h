@@ -358,7 +358,7 @@ __device__ __forceinline__ float log_gate_slope(float u, float tau) { return 1.f
 // GEN: the general form, in which the write intensity may come from an array of its own
 // (sin: [len][M] fp32, same layout as g; NULL = 1 - exp(g) as above), and the array g may hold gate
 // LOGITS u instead of log gates: with tau > 0 the log gate is logsigmoid(u) / tau, the layer's gate
-// alpha = sigmoid(W x)^(1/tau) of Section 3.2 (tau = 0: g is the log gate itself).
+// alpha = sigmoid(W x)^(1/tau) of Section 3.3 (tau = 0: g is the log gate itself).
 template <int M, int NT, int C, bool GEN = false> struct GatePrep {
     static constexpr int P = NT / M;     // token partitions
     static constexpr int TP = C / P;     // tokens per partition
@@ -440,7 +440,7 @@ __device__ __forceinline__ float readout_slope(int ro, float z)
 }
 
 // ----------------------------------------------------------------------------
-// Feature map on q, k, v (Section 3.2: the layer feeds phi(W x) with phi = Swish into the operator).
+// Feature map on q, k, v (Section 3.3: the layer feeds phi(W x) with phi = Swish into the operator).
 // With the option on, the q, k, v arguments hold the raw projections and every kernel applies
 // phi(x) = x sigmoid(x) to what it has just loaded, in registers: the values are rounded to the I/O
 // type once more (they are matrix-core operands), and dq, dk, dv leave multiplied by the slope at

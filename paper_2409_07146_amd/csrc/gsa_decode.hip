@@ -14,6 +14,8 @@
 // output with its own softmax maximum and sum to a workspace, and a second, tiny kernel merges
 // the partials of a pair in a fixed order.  No workgroup waits for another.  (With many pairs the
 // one-workgroup form is the faster one again.)
+#include <mutex>
+
 #include "gsa_common.h"
 #include "gsa_internal.h"
 
@@ -354,6 +356,38 @@ size_t decode_scratch_floats(int BH, int d_v, int m)
 {
     if (BH > kSplitPairsMax) return 0;
     return (size_t)BH * (m / kSplitWaves) * (d_v + 2);
+}
+
+// ---------------------------------------------------------------------------------------
+// Scratch memory of the split form for callers that cannot allocate (gsa_decode_step_static): a
+// file-scope device array, one copy per GPU, held until the process ends.  In host code the array's
+// name is only a handle; its device address is asked for once per device with that device current
+// (static_scratch below) and only that address is ever passed on.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchFloats = (size_t)1 << 20;   // 4 MiB
+static __device__ __align__(256) float scratch_static[kStaticScratchFloats];
+
+size_t decode_static_scratch_floats() { return kStaticScratchFloats; }
+
+hipError_t decode_static_scratch(float **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static float *addr[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch_static));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = static_cast<float *>(p);
+    }
+    *ptr = addr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale, const void *q, const void *k,

@@ -120,5 +120,9 @@ hipError_t launch_decode(int BH, int d_k, int d_v, int m, int dtype, float scale
                          const void *v, const float *g, float *K, float *V, void *o, float *scratch, const float *sin,
                          int opts, float gate_tau, hipStream_t st);
 size_t decode_scratch_floats(int BH, int d_v, int m);
+// The library's own scratch array for the split form (one per GPU, never freed): its capacity, and its
+// address on the current device (looked up on the first call per device; allocates nothing).
+size_t decode_static_scratch_floats();
+hipError_t decode_static_scratch(float **ptr);
 
 }  // namespace gsa

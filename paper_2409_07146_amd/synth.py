@@ -57,8 +57,8 @@ CONFIGS = {
                             cu_seqlens=(0, 8192, 12288, 14336, 16384), seed=4),
 }
 
-# Shape variants beyond the five workloads (Table 5 of the paper varies the number of slots;
-# Appendix D gives the 2.7B model 5 heads of 512).
+# Shape variants beyond the five workloads (the ablation table of Section 4 varies the number of slots;
+# the experimental-setup appendix gives the 2.7B model 5 heads of 512).
 VARIANTS = {
     "layer_1p3b_m32": GsaConfig("layer_1p3b_m32", B=8, T=2048, H=4, d_k=512, d_v=512, m=32, seed=12),
     "layer_1p3b_m128": GsaConfig("layer_1p3b_m128", B=8, T=2048, H=4, d_k=512, d_v=512, m=128, seed=13),

@@ -83,6 +83,17 @@ def test_null_and_workspace_errors_without_device(lib):
     odd = ctypes.c_void_p(0x10004)
     assert lib.gsa_fwd(ctypes.byref(p), odd, fake, fake, fake, null, null, fake, null, null, null,
                        fake, 1 << 30, null) == 2                               # misaligned tensor
+    # an output that overlaps an input (or another output, or the workspace) is refused
+    at = lambda i: ctypes.c_void_p(0x10000000 * (i + 1))
+    ok = [at(0), at(1), at(2), at(3), null, null, at(4), at(5), null, null]
+    big = ctypes.c_void_p(0x10000000 * 9)
+    for clash in (0, 1, 2, 3, 7):                                             # o on top of q, k, v, g, z_saved
+        bad = list(ok)
+        bad[6] = ctypes.c_void_p(bad[clash].value + 64)
+        assert lib.gsa_fwd(ctypes.byref(p), *bad, big, 1 << 27, null) == 2
+    bad = list(ok)
+    bad[6] = ctypes.c_void_p(big.value + 4096)                                # o inside the workspace
+    assert lib.gsa_fwd(ctypes.byref(p), *bad, big, 1 << 27, null) == 2
     # T = 0 is a no-op
     p0 = _problem(T=0)
     assert lib.gsa_fwd(ctypes.byref(p0), *([null] * 10), null, 0, null) == 0

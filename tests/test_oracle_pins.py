@@ -319,6 +319,34 @@ def test_p9_gradients_by_central_differences(oracle, packed):
         assert err < 2e-7, (key, err)
 
 
+@pytest.mark.parametrize("readout", ["softmax", "swish"])
+def test_p9_score_gradients_from_their_definitions(oracle, readout):
+    """The two intermediates the backward can hand out: dp_t[i] = <Vt_t[i,:], dO_t> with Vt_t the value
+    memory after token t's write (obtained here as the final memory of a forward over the first t tokens),
+    and dz_t = J^T dp_t with J the read-out's Jacobian at z_t (written out with library functions).  The
+    loss here has no final-memory term and one sequence, so both are direct."""
+    rng = np.random.default_rng(29)
+    B, T, H, dk, dv, m = 1, 9, 2, 4, 5, 3
+    q, k, v, g, K0, V0 = _rand(rng, B, T, H, dk, dv, m, gate="strong", init=True)
+    dO = rng.standard_normal(v.shape)
+    gr = oracle.bwd(q, k, v, g, dO, K0=K0, V0=V0, scale=0.7, readout=readout, intermediates=True)
+    f = oracle.fwd(q, k, v, g, K0=K0, V0=V0, scale=0.7, readout=readout)
+    for t in range(T):
+        pre = oracle.fwd(q[:, :t + 1], k[:, :t + 1], v[:, :t + 1], g[:, :t + 1], K0=K0, V0=V0, scale=0.7,
+                         readout=readout)
+        for h in range(H):
+            dp = pre["VT"][0, h] @ dO[0, t, h]
+            np.testing.assert_allclose(gr["dp"][0, t, h], dp, rtol=1e-12, atol=1e-13)
+            z = f["z"][0, t, h]
+            if readout == "softmax":
+                pz = sp_softmax(z)
+                jac = np.diag(pz) - np.outer(pz, pz)
+            else:
+                sg = sp_expit(z)
+                jac = np.diag(sg + z * sg * (1.0 - sg))
+            np.testing.assert_allclose(gr["dz"][0, t, h], jac.T @ dp, rtol=1e-11, atol=1e-13)
+
+
 def test_p9_gate_gradient_identity(oracle):
     """Cross-check of dg against the log-space identity behind the paper's dA line
     (Algorithm 1, backward driver; reading: it is a gradient with respect to log
