@@ -30,14 +30,29 @@ def per_token_bytes(cfg, esz):
 
 
 def per_token_head_flops(cfg, C=64):
-    """Executed matrix-core FLOPs per (token, head) at chunk size C, and the chunk-free
-    algorithmic count (recurrent form)."""
+    """Matrix-core FLOPs per (token, head) at chunk size C.
+
+    nominal: the count of the chunkwise scheme as written (Appendix A; Algorithm 1), every C x C product in
+             full: forward 2C(d_k+d_v) + 4Cm + 4m(d_k+d_v); backward (recompute, dp/dz, reverse scan,
+             gradients) 5C(d_k+d_v) + 10Cm + 10m(d_k+d_v).
+    executed: what the kernels issue.  The chunk kernels skip the 16 x 16 blocks above the diagonal of every
+             causally masked C x C product (10 of 16 blocks at C = 64); the wide contractions (apply kernel)
+             multiply the masked matrices in full.  This is the number the MFMA fraction is quoted on.
+    algorithmic: the chunk-free recurrent form, 4m(d_k+d_v) forward and 8m(d_k+d_v) backward."""
     dk, dv, m = cfg.d_k, cfg.d_v, cfg.m
     D = dk + dv
-    fwd = 2 * C * D + 4 * C * m + 4 * m * D
-    bwd = 5 * 2 * C * D + 12 * C * m + 10 * m * D   # recompute scan, dz, reverse scan, main kernel
-    alg_fwd, alg_bwd = 4 * m * D, 8 * m * D
-    return fwd, bwd, alg_fwd, alg_bwd
+    nb = C // 16
+    tri = (nb * (nb + 1) // 2) / float(nb * nb)
+    nominal = (2 * C * D + 4 * C * m + 4 * m * D, 5 * C * D + 10 * C * m + 10 * m * D)
+    fwd = (2 * m * D                                             # scan
+           + 2 * C * dk * tri + 2 * m * dk + 4 * C * m * tri     # QK^T, Q Kt^T, gated intra scores, pair weights A2
+           + 2 * C * dv + 2 * m * dv)                            # o
+    bwd = (2 * m * D                                             # recomputed scan
+           + 2 * C * dv * tri + 2 * m * dv + 2 * C * m * tri     # dO V^T, dO Vt^T, gated intra part of dp
+           + 2 * m * D                                           # reverse scan
+           + 2 * C * dk * tri + 2 * m * D + 8 * C * m * tri      # QK^T, [K|V] E^T, intra part of ds (2x), Bm, A2
+           + 2 * C * (2 * dk + dv) + 2 * m * (2 * dk + dv))      # dq, dk, dv
+    return dict(executed=(fwd, bwd), nominal=nominal, algorithmic=(4 * m * D, 8 * m * D))
 
 
 def prefill_decode(args):
@@ -171,6 +186,16 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens = cfg.tokens
     tok_s = tokens / (dt / args.steps)
+    # the same steps again, each bracketed by a pair of events on the launch stream (the library enqueues on
+    # torch's current stream, so torch's events see its kernels): median and spread of single steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.steps, 50))]
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    ev_ms = sorted(a.elapsed_time(b) for a, b in evs)
+    ev_median, ev_min, ev_p90 = ev_ms[len(ev_ms) // 2], ev_ms[0], ev_ms[(9 * len(ev_ms)) // 10]
 
     # the same work with the feature map outside the operator: three element-wise passes before the
     # forward, three through the slope after the backward (torch's kernels; a comparison leg only)
@@ -233,8 +258,9 @@ def main():
     alg_bytes = {n: b * tokens for n, b in per_tok.items()}
     dom = max((n for n in kern_ms if n in alg_bytes), key=lambda n: kern_ms[n])
     achieved = alg_bytes[dom] / (kern_ms[dom] * 1e-3) / 1e9
-    ffl, bfl, aff, abf = per_token_head_flops(cfg)
-    exec_flops = (ffl + bfl) * tokens * cfg.H
+    fl = per_token_head_flops(cfg)
+    exec_flops = sum(fl["executed"]) * tokens * cfg.H
+    nominal_flops = sum(fl["nominal"]) * tokens * cfg.H
     # HBM traffic per launch of that kernel, from hardware counters collected in separate profiler
     # runs of this same command (stored next to their summaries); None when no such record exists
     traffic = None
@@ -244,10 +270,17 @@ def main():
             rec = json.load(f).get("kernels", {}).get(dom)
         if rec:
             traffic = int(rec["fetch_bytes"] + rec["write_bytes"])
+    step_bytes = (fwd_b + bwd_b) * tokens
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_ms": round(kern_ms[dom], 4),
-                "algorithmic_bytes_per_launch": alg_bytes[dom]}
+                "algorithmic_bytes_per_launch": alg_bytes[dom],
+                # the per-kernel figure credits a kernel with every API tensor it touches, and several kernels
+                # touch the same tensor; the whole step against every API tensor counted ONCE is the honest total
+                "whole_step": {"compulsory_bytes": step_bytes,
+                               "GB_per_s": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                               "frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "note": "per-kernel algorithmic bytes overlap across kernels"}}
 
     # decode step: 512 steps at batch 64 (one state set, then rotating over 8 state sets)
     dd = synth.DECODE
@@ -306,10 +339,14 @@ def main():
             "feature_map": args.feature_map},
         **({} if outside_ms is None else {"feature_map_outside_ms_per_step": round(outside_ms, 4)}),
         "roofline": roofline,
-        "path": {"executed_tflops": round(exec_flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "timing": {"wall_mean_ms": round(ms_per_step, 4), "event_median_ms": round(ev_median, 4),
+                   "event_min_ms": round(ev_min, 4), "event_p90_ms": round(ev_p90, 4), "event_steps": len(ev_ms)},
+        "path": {"executed_gflop_per_step": round(exec_flops / 1e9, 2),
+                 "nominal_gflop_per_step": round(nominal_flops / 1e9, 2),
+                 "executed_tflops": round(exec_flops / (ms_per_step * 1e-3) / 1e12, 2),
                  "frac_mfma_bf16_peak": round(exec_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                 "algorithmic_GB_per_s": round((fwd_b + bwd_b) * tokens / (ms_per_step * 1e-3) / 1e9, 1),
-                 "frac_hbm_peak": round((fwd_b + bwd_b) * tokens / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                 "algorithmic_GB_per_s": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                 "frac_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                  "kernel_ms": {n: round(ms, 4) for n, ms in kern_ms.items()}},
         "decode": dec,
         "copy_probe": {"bytes_moved": 2 * (256 << 20), "us": round(kern_ms["copy_probe_kernel"] * 1e3, 2),

@@ -93,7 +93,7 @@ def test_fwd_d128_bf16(oracle):
     from paper_2409_07146_amd import synth
     rep = []
     run_fwd_case(oracle, synth.CONFIGS["fwd_d128"], report=rep)
-    print("worst rel-L2 %.3e  worst max-abs %.3e" % (max(r for _, r, _ in rep), max(a for _, _, a in rep)))
+    print("worst rel-L2 %.3e  worst max-abs %.3e" % (max(e[1] for e in rep), max(e[2] for e in rep)))
 
 
 def test_fwd_is_deterministic():

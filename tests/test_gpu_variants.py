@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.util import check, suffix_sum_mass, to_np64
+from tests.util import check, suffix_mass, to_np64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -64,12 +64,13 @@ def _run_and_compare(oracle, cfg, x, readout, scale=1.0):
 
 
 def _residue(name, a, r):
-    """With the write intensity an input of its own, dg is the gradient through the decay alone: a suffix
-    sum, over all later tokens of the sequence, of per-token terms of either sign, several times smaller
-    than the tied gate gradient (which also holds -exp(g) ds).  Its error is relative to what is summed
-    (tests.util.suffix_sum_mass, from the oracle's own dg)."""
+    """With the write intensity an input of its own, dg is the gradient through the decay alone: the suffix
+    sum, over all later tokens of the sequence, of dGam_t = (z dz + p dp)_t - (s ds)_t, in which every
+    (writer, reader) pair of later tokens enters once with each sign.  It comes out several times smaller
+    than the tied gate gradient (which also holds -exp(g) ds) and than what is summed; its error is
+    relative to the latter (tests.util.suffix_mass of the oracle's s * ds)."""
     if name == "dg" and a.get("s") is not None:
-        return suffix_sum_mass(r["dg"], axis=1)
+        return suffix_mass(a["s"] * r["ds"], axis=1)
     return None
 
 

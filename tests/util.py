@@ -31,15 +31,13 @@ def to_np64(t):
 TOL = {"f32": dict(rel=1e-4, abs=None), "bf16": dict(rel=5e-3, abs=2e-2)}
 
 
-def suffix_sum_mass(dg_decay, axis=1):
-    """A gate gradient through the decay alone is a suffix sum over the later tokens of its sequence,
-    dg_j = sum_{t >= j} dGam_t, of per-token terms of either sign.  From the ORACLE's dg_decay (tokens of
-    one sequence along `axis`) this returns sqrt(sum_{t >= j} dGam_t^2), dGam_t = dg_t - dg_{t+1}: the
-    magnitude of what is being summed, which is what a rounding error is relative to."""
-    dg = np.moveaxis(np.asarray(dg_decay, dtype=np.float64), axis, 0)
-    dgam = dg.copy()
-    dgam[:-1] -= dg[1:]
-    mass = np.sqrt(np.cumsum((dgam * dgam)[::-1], axis=0)[::-1])
+def suffix_mass(terms, axis=1):
+    """The gate gradient is a suffix sum over the later tokens of a sequence (Algorithm 1's reversed
+    cumulative sum): dg_j = sum_{t >= j} (per-token terms of either sign).  Rounding errors of the terms add
+    up like a random walk, so the error of the sum is relative to sqrt(sum_{t >= j} terms_t^2), which this
+    returns for ORACLE terms [.., tokens of one sequence along `axis`, ..]."""
+    x = np.moveaxis(np.asarray(terms, dtype=np.float64), axis, 0)
+    mass = np.sqrt(np.cumsum((x * x)[::-1], axis=0)[::-1])
     return np.moveaxis(mass, 0, axis)
 
 
@@ -51,14 +49,15 @@ def check(name, got, ref, dtype, report=None, residue_of=None, widen=1.0):
       "residue"   only with residue_of: `ref` is a cancellation residue of larger ORACLE quantities (the
                   caller passes them: an array, or a list of arrays, computed from the oracle's outputs
                   and the inputs, never from the device result), so its error cannot be small next to
-                  `ref` itself.  The same relative bar is then applied against the magnitude of those
-                  quantities: rms(got - ref) <= rel * rms(residue_of), and max|got - ref| <= rel *
-                  max|residue_of| (and still inside the max-abs bar).
+                  `ref` itself.  The bars are then applied against the magnitude of those quantities:
+                  rms(got - ref) <= rel * rms(residue_of), and max|got - ref| <= 4 * rel *
+                  max|residue_of| (the bf16 bars' own ratio of max-abs to rel-L2) and still inside the
+                  max-abs bar.
     Anything else fails, whatever its absolute size.
     widen (>= 1, an oracle-side number) multiplies the bars: the bars are stated for scores of order one;
     the softmax turns an absolute error of a score into a relative error of its weight, and the error of a
     score is relative to the score, so a test that drives the scores far beyond order one (a large
-    `scale`) passes widen = max(1, rms of the oracle's scores)."""
+    `scale`) passes widen = max(1, mean spread of the oracle's scores over the slots of a token)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert np.all(np.isfinite(got)), "%s has non-finite values" % name
@@ -73,7 +72,7 @@ def check(name, got, ref, dtype, report=None, residue_of=None, widen=1.0):
         parts = residue_of if isinstance(residue_of, (list, tuple)) else [residue_of]
         scale_rms = max(rms(p) for p in parts)
         scale_max = max(float(np.max(np.abs(p))) if np.size(p) else 0.0 for p in parts)
-        if rms(got - ref) <= tol["rel"] * scale_rms and a <= tol["rel"] * scale_max and (bar is None or a <= bar):
+        if rms(got - ref) <= tol["rel"] * scale_rms and a <= 4.0 * tol["rel"] * scale_max and (bar is None or a <= bar):
             branch = "residue"
     if report is not None:
         report.append((name, r, a, branch))
