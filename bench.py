@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--feature-map", default="none", choices=["none", "swish"],
                     help="q, k, v as raw projections with the Swish feature map applied inside the kernels; also "
                          "times the same work with the feature map as element-wise passes of their own")
+    ap.add_argument("--epilogue", action="store_true",
+                    help="also time the forward with the layer's output epilogue fused in (gsa_fwd_act) against the "
+                         "forward followed by the same work as element-wise passes of their own")
     ap.add_argument("--decode-one-workgroup", action="store_true",
                     help="prefill_decode: use gsa_decode_step (one workgroup per memory) instead of gsa_decode_step_ws")
     args = ap.parse_args()
@@ -219,6 +222,33 @@ def main():
             step_outside()
         torch.cuda.synchronize()
         outside_ms = (time.perf_counter() - t0) / args.steps * 1e3
+
+    # the layer's output epilogue (Swish(o), sums of squares for the RMS norm): fused into the kernel that
+    # writes o against torch's element-wise kernels after it (a comparison leg only; forward calls)
+    epilogue = None
+    if args.epilogue:
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / args.steps * 1e3
+
+        def outside():
+            o = gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws, **var)[0]
+            y = torch.nn.functional.silu(o)
+            return y, y.float().pow(2).sum(-1)
+
+        epilogue = {"fwd_ms": round(timed(lambda: gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws, **var)), 4),
+                    "fwd_act_fused_ms": round(timed(lambda: gsa.gsa_fwd_act(q, k, v, g, cu_seqlens=cu, workspace=ws,
+                                                                            **var)), 4),
+                    "fwd_act_fused_without_o_ms": round(timed(lambda: gsa.gsa_fwd_act(q, k, v, g, cu_seqlens=cu,
+                                                                                      workspace=ws, want_o=False,
+                                                                                      **var)), 4),
+                    "fwd_then_elementwise_passes_ms": round(timed(outside), 4)}
 
     # per-kernel durations, HIP events on the launch stream (second pass, same work)
     gsa.gsa_profile_reset()
@@ -338,6 +368,7 @@ def main():
             "write_intensity": "given" if args.given_intensity else "1 - exp(g)",
             "feature_map": args.feature_map},
         **({} if outside_ms is None else {"feature_map_outside_ms_per_step": round(outside_ms, 4)}),
+        **({} if epilogue is None else {"epilogue": epilogue}),
         "roofline": roofline,
         "timing": {"wall_mean_ms": round(ms_per_step, 4), "event_median_ms": round(ev_median, 4),
                    "event_min_ms": round(ev_min, 4), "event_p90_ms": round(ev_p90, 4), "event_steps": len(ev_ms)},

@@ -167,6 +167,26 @@ gsa_status gsa_bwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * gsa_fwd_ex with the layer's output epilogue fused into the kernel that writes o (Section 3.3: the layer
+ * feeds RMSNorm(Swish(o)), over the concatenated heads, into its output projection):
+ *   act     [B,T,H,d_v] (dtype) or NULL: Swish(o) = o*sigmoid(o), computed from o as stored (rounded to dtype)
+ *   act_ssq [B,T,H,ns] fp32 or NULL, ns = ceil(d_v / gsa_act_slice_cols(dtype)): the sum of act^2 (of the
+ *           stored values) over each slice of gsa_act_slice_cols(dtype) consecutive columns of a head.  The
+ *           RMS norm's statistic for token t is sqrt(sum over h and slices / (H*d_v)): no pass of its own
+ *           over the tensor.
+ *   o       may be NULL here (inference: nothing reads the un-activated output); with both o and act NULL
+ *           the call returns GSA_ERR_NULL.
+ * Everything else as for gsa_fwd_ex.  The backward of the activation stays with the layer's norm backward,
+ * which passes over these tensors anyway; gsa_bwd* take dO, the gradient with respect to o.
+ */
+gsa_status gsa_fwd_act(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map,
+                       const void *q, const void *k, const void *v, const float *g, const float *s,
+                       const float *K0, const float *V0,
+                       void *o, void *act, float *act_ssq, float *z_saved, float *KT, float *VT,
+                       void *workspace, size_t workspace_bytes, void *stream);
+int32_t gsa_act_slice_cols(int32_t dtype);   /* 0 for an unknown dtype */
+
+/*
  * One recurrent step of Eq. (gsa) (the decode form, Figure 1) for B*H
  * independent memories, which are read, updated and written back in place.
  *   q,k [B,H,d_k]  v [B,H,d_v] (dtype)   g [B,H,m] fp32

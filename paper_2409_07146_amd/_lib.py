@@ -8,7 +8,7 @@ LIB_PATH = os.path.join(_HERE, "libgsa.so")
 # every symbol include/gsa.h declares
 EXPORTS = ("gsa_status_string", "gsa_abi_version", "gsa_workspace_bytes", "gsa_fwd", "gsa_bwd", "gsa_fwd_ex", "gsa_bwd_ex",
            "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_decode_step_ws", "gsa_decode_step_ex",
-           "gsa_decode_step_static", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read", "gsa_profile_copy")
+           "gsa_decode_step_static", "gsa_fwd_act", "gsa_act_slice_cols", "gsa_profile_enable", "gsa_profile_reset", "gsa_profile_read", "gsa_profile_copy")
 
 
 class GsaProblem(ctypes.Structure):
@@ -44,6 +44,10 @@ def load():
     lib.gsa_bwd.argtypes = [ctypes.POINTER(GsaProblem)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
     lib.gsa_fwd_ex.restype = ctypes.c_int
     lib.gsa_fwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32, i32] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_fwd_act.restype = ctypes.c_int
+    lib.gsa_fwd_act.argtypes = [ctypes.POINTER(GsaProblem), i32, f32, i32] + [vp] * 13 + [vp, ctypes.c_size_t, vp]
+    lib.gsa_act_slice_cols.restype = i32
+    lib.gsa_act_slice_cols.argtypes = [i32]
     lib.gsa_bwd_ex.restype = ctypes.c_int
     lib.gsa_bwd_ex.argtypes = [ctypes.POINTER(GsaProblem), i32, f32, i32] + [vp] * 18 + [vp, ctypes.c_size_t, vp]
     lib.gsa_decode_step.restype = ctypes.c_int

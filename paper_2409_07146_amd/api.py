@@ -116,6 +116,38 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
     return o, z, KT, VT
 
 
+def gsa_fwd_act(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=True, final_state=False,
+                workspace=None, s=None, readout="softmax", gate_tau=0.0, feature_map="none", want_o=True):
+    """gsa_fwd_act of the C ABI: the forward with the layer's output epilogue fused in.  Returns
+    (o or None, act, act_ssq, z_saved or None, KT or None, VT or None) with act = Swish(o) and act_ssq
+    [B,T,H,ceil(d_v/slice)] the per-slice sums of squares of act."""
+    B, T, H, d_k = q.shape
+    d_v, m = v.shape[-1], g.shape[-1]
+    p = make_problem(q, v, g, scale, cu_seqlens)
+    n = p.n_seqs
+    _check(q, "q", q.dtype, (B, T, H, d_k)); _check(k, "k", q.dtype, (B, T, H, d_k))
+    _check(v, "v", q.dtype, (B, T, H, d_v)); _check(g, "g", torch.float32, (B, T, H, m))
+    _check(K0, "K0", torch.float32, (n, H, m, d_k), optional=True)
+    _check(V0, "V0", torch.float32, (n, H, m, d_v), optional=True)
+    _check(s, "s", torch.float32, (B, T, H, m), optional=True)
+    if workspace is None:
+        workspace = alloc_workspace(p, False, q.device)
+    slice_cols = _lib.load().gsa_act_slice_cols(p.dtype)
+    o = torch.empty_like(v) if want_o else None
+    act = torch.empty_like(v)
+    ssq = torch.empty((B, T, H, (d_v + slice_cols - 1) // slice_cols), dtype=torch.float32, device=q.device)
+    z = torch.empty((B, T, H, m), dtype=torch.float32, device=q.device) if save_z else None
+    KT = torch.empty((n, H, m, d_k), dtype=torch.float32, device=q.device) if final_state else None
+    VT = torch.empty((n, H, m, d_v), dtype=torch.float32, device=q.device) if final_state else None
+    rc = _lib.load().gsa_fwd_act(ctypes.byref(p), READOUTS[readout], float(gate_tau), FEATURE_MAPS[feature_map],
+                                 _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(s), _ptr(K0), _ptr(V0), _ptr(o), _ptr(act),
+                                 _ptr(ssq), _ptr(z), _ptr(KT), _ptr(VT), _ptr(workspace), workspace.numel(),
+                                 _stream(q))
+    if rc != 0:
+        raise GsaError(rc, "gsa_fwd_act")
+    return o, act, ssq, z, KT, VT
+
+
 def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, cu_seqlens=None,
             initial_state_grad=False, workspace=None, s=None, readout="softmax", gate_tau=0.0,
             feature_map="none"):

@@ -216,7 +216,7 @@ namespace {
 gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q,
                    const void *k, const void *v, const float *g, const float *s, const float *K0, const float *V0,
                    void *o, float *z_saved, float *KT, float *VT, void *workspace, size_t workspace_bytes,
-                   void *stream)
+                   void *stream, void *act = nullptr, float *ssq = nullptr, bool with_act = false)
 {
     Plan pl;
     gsa_status st = make_plan(p, &pl);
@@ -225,9 +225,11 @@ gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_
     if (!(gate_tau >= 0.f)) return GSA_ERR_SHAPE;
     if (feature_map != GSA_FEATURE_NONE && feature_map != GSA_FEATURE_SWISH) return GSA_ERR_SHAPE;
     if (pl.tokens == 0) return GSA_OK;
-    if (!q || !k || !v || !g || !o) return GSA_ERR_NULL;
+    if (!q || !k || !v || !g) return GSA_ERR_NULL;
+    if (with_act ? (!act && !o) : !o) return GSA_ERR_NULL;   // the epilogue form may leave o out, not both
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) || !aligned16(K0) ||
-        !aligned16(V0) || !aligned16(z_saved) || !aligned16(KT) || !aligned16(VT) || !aligned16(s))
+        !aligned16(V0) || !aligned16(z_saved) || !aligned16(KT) || !aligned16(VT) || !aligned16(s) ||
+        !aligned16(act) || !aligned16(ssq))
         return GSA_ERR_SHAPE;
     st = check_workspace(workspace, workspace_bytes, pl.total_fwd);
     if (st != GSA_OK) return st;
@@ -236,10 +238,14 @@ gsa_status fwd_any(const gsa_problem *p, int32_t readout, float gate_tau, int32_
         const size_t nk = th * pl.d_k * esz, nv = th * pl.d_v * esz, nm = th * M * sizeof(float);
         const size_t sk = (size_t)pl.n_seqs * pl.H * M * pl.d_k * sizeof(float);
         const size_t sv = (size_t)pl.n_seqs * pl.H * M * pl.d_v * sizeof(float);
-        const Span spans[] = {{o, nv}, {z_saved, nm}, {KT, sk}, {VT, sv}, {workspace, pl.total_fwd},
+        const int slice = gsa::apply_slice_cols(pl.dtype);
+        const size_t nq = th * (size_t)((pl.d_v + slice - 1) / slice) * sizeof(float);
+        const Span spans[] = {{o, nv}, {z_saved, nm}, {KT, sk}, {VT, sv}, {workspace, pl.total_fwd}, {act, nv}, {ssq, nq},
                               {q, nk}, {k, nk}, {v, nv}, {g, nm}, {s, nm}, {K0, sk}, {V0, sv}};
-        if (outputs_overlap(spans, 5, (int)(sizeof(spans) / sizeof(spans[0])))) return GSA_ERR_SHAPE;
+        if (outputs_overlap(spans, 7, (int)(sizeof(spans) / sizeof(spans[0])))) return GSA_ERR_SHAPE;
     }
+    pl.act_out = act;
+    pl.act_ssq = ssq;
     pl.s_in = s;
     pl.readout = readout;
     pl.gate_tau = gate_tau;
@@ -309,6 +315,17 @@ gsa_status gsa_fwd_ex(const gsa_problem *p, int32_t readout, float gate_tau, int
     return fwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace,
                    workspace_bytes, stream);
 }
+
+gsa_status gsa_fwd_act(const gsa_problem *p, int32_t readout, float gate_tau, int32_t feature_map, const void *q,
+                       const void *k, const void *v, const float *g, const float *s, const float *K0,
+                       const float *V0, void *o, void *act, float *act_ssq, float *z_saved, float *KT, float *VT,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fwd_any(p, readout, gate_tau, feature_map, q, k, v, g, s, K0, V0, o, z_saved, KT, VT, workspace,
+                   workspace_bytes, stream, act, act_ssq, true);
+}
+
+int32_t gsa_act_slice_cols(int32_t dtype) { return (dtype == GSA_F32 || dtype == GSA_BF16) ? gsa::apply_slice_cols(dtype) : 0; }
 
 gsa_status gsa_bwd(const gsa_problem *p, const void *q, const void *k, const void *v, const float *g,
                    const float *K0, const float *V0, const float *z_saved, const void *dO, const float *dKT,

@@ -39,6 +39,8 @@ template <typename T> struct ApplyOne {
     int d;
     bool phi_tok;         // feature map on xtok on its way into LDS
     const T *raw;         // [tokens][H][d] or NULL: out leaves multiplied by the feature map's slope at raw
+    T *act;               // output epilogue (EPI): Swish(out) [tokens][H][d], or NULL
+    float *ssq;           // output epilogue (EPI): [tokens][H][slices] sums of squares of act over each column slice, or NULL
 };
 template <typename T> struct ApplyArgs { ApplyOne<T> one[3]; };
 
@@ -56,7 +58,12 @@ template <typename T, int M> struct ApplyLds {
 
 // PHI: compiled with the feature-map options (ApplyOne::phi_tok, ApplyOne::raw); the plain calls run
 // PHI = false, where those fields are ignored.
-template <typename T, int M, bool PHI>
+// EPI: the layer's output epilogue (Section 3.3: the layer applies RMSNorm(Swish(.)) to the operator's
+// output).  The output tile leaves as it is (when ApplyOne::out is given) and as act = Swish(out), computed
+// from the stored (rounded) out; the sum of squares of the stored act over this workgroup's columns goes to
+// ssq[token][head][slice], so that the norm that follows needs no pass of its own over the tensor for its
+// statistic (it adds the slices' partial sums and scales).  Plain calls run EPI = false.
+template <typename T, int M, bool PHI, bool EPI>
 __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, ApplyArgs<T> args)
 {
     using L = ApplyLds<T, M>;
@@ -218,8 +225,41 @@ __global__ __launch_bounds__(Geo<T>::NT) void apply_kernel(ChunkMap cm, int H, A
         }
         return;
     }
+    if (EPI) {
+        // same walk as store_tile: consecutive threads take consecutive 8-element pieces of a row, so the
+        // vpr threads of a row are neighbours in one wave and meet by shuffles
+        const int vpr = ncols >> 3;   // 8 or 16 pieces per row
+        const int nslices = (a.d + L::NS - 1) / L::NS;
+        constexpr int OV = C * (L::NS / 8), OPER = (OV + NT - 1) / NT;
+#pragma unroll
+        for (int u = 0; u < OPER; ++u) {
+            const int idx = tid + u * NT, t = idx / vpr, c = (idx - t * vpr) << 3;
+            const bool live = idx < C * vpr && t < ci.len;
+            Raw8<T> x;
+            x.load(Os + min(t, C - 1) * L::ldo + c);
+            Raw8<T> y;
+            float sq = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const T ye = from_f32<T>(swish_value((float)x.get(e)));
+                y.set(e, ye);
+                sq += (float)ye * (float)ye;
+            }
+            sq = live ? sq : 0.f;
+            for (int o = 1; o < vpr; o <<= 1) sq += __shfl_xor(sq, o, 64);
+            if (live) {
+                const size_t off = tokh * a.d + cs + (size_t)t * H * a.d + c;
+                if (a.out) x.store_nt(a.out + off);
+                if (a.act) y.store_nt(a.act + off);
+                if (a.ssq && c == 0) a.ssq[(tokh + (size_t)t * H) * nslices + bx] = sq;
+            }
+        }
+        return;
+    }
     store_tile<T, true>(a.out + tokh * a.d + cs, (size_t)H * a.d, Os, L::ldo, C, ncols, ci.len, tid, NT);
 }
+
+int apply_slice_cols(int dtype) { return dtype == 0 ? ApplyLds<float, 64>::NS : ApplyLds<bf16_t, 64>::NS; }
 
 template <typename T, int M>
 static hipError_t launch_apply_tm(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st)
@@ -239,13 +279,18 @@ static hipError_t launch_apply_tm(const Plan &pl, const Work &w, const ApplyIo *
         o.d = s.d;
         o.phi_tok = s.phi_tok;
         o.raw = static_cast<const T *>(s.raw);
+        o.act = static_cast<T *>(s.act);
+        o.ssq = s.ssq;
         if (i < n && s.d > dmax) dmax = s.d;
     }
     constexpr int NS = ApplyLds<T, M>::NS;
     dim3 grid((dmax + NS - 1) / NS, pl.chunk_slots, pl.H * n);
     KernelTimer kt(slot, st);
-    if (pl.phi) hipLaunchKernelGGL((apply_kernel<T, M, true>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
-    else hipLaunchKernelGGL((apply_kernel<T, M, false>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    const bool epi = io[0].act != nullptr || io[0].ssq != nullptr;   // forward only
+    if (epi && pl.phi) hipLaunchKernelGGL((apply_kernel<T, M, true, true>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    else if (epi) hipLaunchKernelGGL((apply_kernel<T, M, false, true>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    else if (pl.phi) hipLaunchKernelGGL((apply_kernel<T, M, true, false>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
+    else hipLaunchKernelGGL((apply_kernel<T, M, false, false>), grid, dim3(Geo<T>::NT), 0, st, cm, pl.H, args);
     return hipGetLastError();
 }
 

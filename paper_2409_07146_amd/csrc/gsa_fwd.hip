@@ -288,7 +288,9 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
                            pl.opts(), pl.gate_tau);
         GSA_HIP_TRY(hipGetLastError());
     }
-    const ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v, pl.phi != 0, nullptr};
+    ApplyIo io = {w.tA, w.tP, v, w.S, pl.lay.oV, pl.lay.stride, o, pl.d_v, pl.phi != 0, nullptr};
+    io.act = pl.act_out;
+    io.ssq = pl.act_ssq;
     return launch_apply(pl, w, &io, 1, kSlotApplyFwd, st);
 }
 

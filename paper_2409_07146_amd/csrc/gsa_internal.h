@@ -29,6 +29,9 @@ struct Plan {
     int32_t readout = 0;           // Readout
     float gate_tau = 0.f;          // > 0: g holds gate logits, the log gate is logsigmoid(g) / gate_tau
     int32_t phi = 0;               // 1: q, k, v hold raw projections, the kernels apply the Swish feature map
+    // forward output epilogue (gsa_fwd_act): y = Swish(o) and per-slice sums of squares of y beside (or instead of) o
+    void *act_out = nullptr;       // [B,T,H,d_v] I/O dtype, or NULL
+    float *act_ssq = nullptr;      // [B,T,H,ceil(d_v / slice)] fp32, or NULL
     bool general() const { return s_in != nullptr || readout != 0 || gate_tau > 0.f || phi != 0; }
     int opts() const { return readout | (phi ? kFeatureMapBit : 0); }   // what the device kernels take
 };
@@ -102,7 +105,13 @@ struct ApplyIo {
     int d;
     bool phi_tok = false;        // feature map on xtok as it is loaded
     const void *raw = nullptr;   // [tokens][H][d] or NULL: out is multiplied by the feature map's slope at raw
+    // output epilogue (forward): act = Swish(out) as stored, ssq[token][head][slice] = sum over the slice's
+    // columns of act^2; out itself may then be NULL (not written)
+    void *act = nullptr;
+    float *ssq = nullptr;
 };
+// Columns per workgroup of the apply kernel (= columns per partial sum of squares of the output epilogue).
+int apply_slice_cols(int dtype);
 hipError_t launch_apply(const Plan &pl, const Work &w, const ApplyIo *io, int n, int slot, hipStream_t st);
 
 hipError_t launch_fwd(const Plan &pl, const Work &w, const void *q, const void *k, const void *v, const float *g,
