@@ -55,12 +55,16 @@ def find_csv(directory, suffix):
 
 def split_apply(rows):
     """The apply kernel is launched twice per step; its launches are told apart by grid size."""
-    grids = sorted({int(r["Grid_Size"]) for r in rows if "apply_kernel" in r["Kernel_Name"]})
+    def grid(r):   # the counter file has one column, the kernel trace one per dimension
+        if "Grid_Size" in r:
+            return int(r["Grid_Size"])
+        return int(r["Grid_Size_X"]) * int(r["Grid_Size_Y"]) * int(r["Grid_Size_Z"])
+    grids = sorted({grid(r) for r in rows if "apply_kernel" in r["Kernel_Name"]})
 
     def name(r):
         s = short(r["Kernel_Name"])
         if s.startswith("apply_kernel") and len(grids) == 2:
-            s += " forward (o)" if int(r["Grid_Size"]) == grids[0] else " backward (dq,dk,dv)"
+            s += " forward (o)" if grid(r) == grids[0] else " backward (dq,dk,dv)"
         return s
     return name
 
