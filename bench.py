@@ -200,6 +200,28 @@ def main():
     ev_ms = sorted(a.elapsed_time(b) for a, b in evs)
     ev_median, ev_min, ev_p90 = ev_ms[len(ev_ms) // 2], ev_ms[0], ev_ms[(9 * len(ev_ms)) // 10]
 
+    # "GSA w/o recomp." (Section 4, Efficiency): the forward keeps the per-chunk memories for the backward.
+    # A second figure beside the headline one, which recomputes them as the paper's default does.
+    prob_k = gsa.make_problem(q, v, g, 1.0, cu, keep_states=True)
+    ws_k = gsa.alloc_workspace(prob_k, True, dev)
+
+    def step_keep():
+        o, z, _, _ = gsa.gsa_fwd(q, k, v, g, cu_seqlens=cu, workspace=ws_k, keep_states=True, **var)
+        return gsa.gsa_bwd(q, k, v, g, z, dO, cu_seqlens=cu, workspace=ws_k, keep_states=True, **var)
+
+    for _ in range(args.warmup):
+        step_keep()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_keep()
+    torch.cuda.synchronize()
+    keep_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    esz_k = 2 if cfg.dtype == "bf16" else 4
+    chunk_k = 64 if cfg.dtype == "bf16" else 32
+    kept_bytes = (tokens // chunk_k) * cfg.H * cfg.m * (cfg.d_k + cfg.d_v) * esz_k
+    del ws_k
+
     # the same work with the feature map outside the operator: three element-wise passes before the
     # forward, three through the slope after the backward (torch's kernels; a comparison leg only)
     outside_ms = None
@@ -379,6 +401,9 @@ def main():
                  "algorithmic_GB_per_s": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                  "frac_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                  "kernel_ms": {n: round(ms, 4) for n, ms in kern_ms.items()}},
+        "without_recompute": {"entry": "gsa_fwd/gsa_bwd with gsa_problem.keep_states", "ms_per_step": round(keep_ms, 4),
+                              "tokens_per_s": round(tokens / (keep_ms * 1e-3), 1),
+                              "memories_kept_bytes": kept_bytes},
         "decode": dec,
         "copy_probe": {"bytes_moved": 2 * (256 << 20), "us": round(kern_ms["copy_probe_kernel"] * 1e3, 2),
                        "GB_per_s": round(2 * (256 << 20) / (kern_ms["copy_probe_kernel"] * 1e-3) / 1e9, 1)},

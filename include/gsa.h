@@ -68,6 +68,10 @@ typedef struct {
     float scale;
     const int32_t *cu_seqlens;  /* device pointer or NULL */
     int32_t n_seqs;
+    int32_t keep_states;        /* 0: the backward recomputes the per-chunk memories (the paper's default,
+                                 * Section 4 "Efficiency").  Nonzero: "GSA w/o recomp." of the throughput
+                                 * and memory figures there: gsa_fwd* leaves them in the workspace and
+                                 * gsa_bwd* reads them from it; see gsa_workspace_bytes. */
 } gsa_problem;
 
 const char *gsa_status_string(gsa_status s);
@@ -81,6 +85,14 @@ int32_t gsa_abi_version(void);
  * chunkwise evaluation (Appendix A, Eq. (gla-chunk-gate)) and small per-token
  * scratch; its contents are meaningless to the caller.  It must be 256-byte
  * aligned.  Host call, touches no device.
+ * With p->keep_states set, both calls need the larger (want_bwd) size, and
+ * gsa_bwd* must be given the very workspace, untouched since, that a gsa_fwd*
+ * call with the same problem, the same q,k,v,g,s,K0,V0 and the same options
+ * filled last: it then skips the recomputation (the gate tables and the forward
+ * scan).  The library cannot check that; a workspace that went through another
+ * call in between gives wrong gradients, not an error.  The memories kept are
+ * (d_k + d_v) * m elements of dtype per chunk of 64 (bf16) or 32 (fp32) tokens
+ * and head, i.e. for m = 64 as many bytes as q, k, v and o together.
  */
 gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes);
 

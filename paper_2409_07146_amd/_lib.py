@@ -15,7 +15,7 @@ class GsaProblem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("m", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("cu_seqlens", ctypes.c_void_p), ("n_seqs", ctypes.c_int32)]
+                ("cu_seqlens", ctypes.c_void_p), ("n_seqs", ctypes.c_int32), ("keep_states", ctypes.c_int32)]
 
 
 _lib = None

@@ -44,7 +44,7 @@ def _stream(t: torch.Tensor):
     return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
 
 
-def make_problem(q, v, g, scale=1.0, cu_seqlens=None):
+def make_problem(q, v, g, scale=1.0, cu_seqlens=None, keep_states=False):
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
     if q.dtype not in _DTYPES:
@@ -53,6 +53,7 @@ def make_problem(q, v, g, scale=1.0, cu_seqlens=None):
     p.B, p.T, p.H, p.d_k, p.d_v, p.m = B, T, H, d_k, d_v, m
     p.dtype = _DTYPES[q.dtype]
     p.scale = float(scale)
+    p.keep_states = int(bool(keep_states))
     if cu_seqlens is not None:
         _check(cu_seqlens, "cu_seqlens", torch.int32)
         p.cu_seqlens = cu_seqlens.data_ptr()
@@ -81,20 +82,23 @@ FEATURE_MAPS = {"none": 0, "swish": 1}
 
 
 def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=True, final_state=False,
-            workspace=None, s=None, readout="softmax", gate_tau=0.0, feature_map="none"):
-    """Returns (o, z_saved or None, KT or None, VT or None).  With s (write intensities [B,T,H,m] fp32),
+            workspace=None, s=None, readout="softmax", gate_tau=0.0, feature_map="none", keep_states=False):
+    """Returns (o, z_saved or None, KT or None, VT or None).  keep_states: leave the per-chunk memories in
+    `workspace` (then required, of the backward's size) for a gsa_bwd call with keep_states.  With s (write intensities [B,T,H,m] fp32),
     a readout other than "softmax", gate_tau > 0 (g holds gate logits, log gate = logsigmoid(g)/gate_tau)
     or feature_map "swish" (q, k, v hold raw projections, the kernels apply x*sigmoid(x) to them) the call
     goes through gsa_fwd_ex."""
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
-    p = make_problem(q, v, g, scale, cu_seqlens)
+    p = make_problem(q, v, g, scale, cu_seqlens, keep_states)
     n = p.n_seqs
     _check(q, "q", q.dtype, (B, T, H, d_k)); _check(k, "k", q.dtype, (B, T, H, d_k))
     _check(v, "v", q.dtype, (B, T, H, d_v)); _check(g, "g", torch.float32, (B, T, H, m))
     _check(K0, "K0", torch.float32, (n, H, m, d_k), optional=True)
     _check(V0, "V0", torch.float32, (n, H, m, d_v), optional=True)
     if workspace is None:
+        if keep_states:
+            raise ValueError("keep_states: pass the workspace that the backward call will be given")
         workspace = alloc_workspace(p, False, q.device)
     o = torch.empty_like(v)
     z = torch.empty((B, T, H, m), dtype=torch.float32, device=q.device) if save_z else None
@@ -117,13 +121,14 @@ def gsa_fwd(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=Tru
 
 
 def gsa_fwd_act(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z=True, final_state=False,
-                workspace=None, s=None, readout="softmax", gate_tau=0.0, feature_map="none", want_o=True):
+                workspace=None, s=None, readout="softmax", gate_tau=0.0, feature_map="none", want_o=True,
+                keep_states=False):
     """gsa_fwd_act of the C ABI: the forward with the layer's output epilogue fused in.  Returns
     (o or None, act, act_ssq, z_saved or None, KT or None, VT or None) with act = Swish(o) and act_ssq
     [B,T,H,ceil(d_v/slice)] the per-slice sums of squares of act."""
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
-    p = make_problem(q, v, g, scale, cu_seqlens)
+    p = make_problem(q, v, g, scale, cu_seqlens, keep_states)
     n = p.n_seqs
     _check(q, "q", q.dtype, (B, T, H, d_k)); _check(k, "k", q.dtype, (B, T, H, d_k))
     _check(v, "v", q.dtype, (B, T, H, d_v)); _check(g, "g", torch.float32, (B, T, H, m))
@@ -131,6 +136,8 @@ def gsa_fwd_act(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z
     _check(V0, "V0", torch.float32, (n, H, m, d_v), optional=True)
     _check(s, "s", torch.float32, (B, T, H, m), optional=True)
     if workspace is None:
+        if keep_states:
+            raise ValueError("keep_states: pass the workspace that the backward call will be given")
         workspace = alloc_workspace(p, False, q.device)
     slice_cols = _lib.load().gsa_act_slice_cols(p.dtype)
     o = torch.empty_like(v) if want_o else None
@@ -150,12 +157,13 @@ def gsa_fwd_act(q, k, v, g, K0=None, V0=None, scale=1.0, cu_seqlens=None, save_z
 
 def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale=1.0, cu_seqlens=None,
             initial_state_grad=False, workspace=None, s=None, readout="softmax", gate_tau=0.0,
-            feature_map="none"):
+            feature_map="none", keep_states=False):
     """Returns (dq, dk, dv, dg, dK0 or None, dV0 or None), plus ds as a seventh item when s is given
-    (gsa_bwd_ex; dg is then the gradient through the decay alone)."""
+    (gsa_bwd_ex; dg is then the gradient through the decay alone).  keep_states: `workspace` is the one the
+    forward call with keep_states filled for the same inputs; the per-chunk memories are not recomputed."""
     B, T, H, d_k = q.shape
     d_v, m = v.shape[-1], g.shape[-1]
-    p = make_problem(q, v, g, scale, cu_seqlens)
+    p = make_problem(q, v, g, scale, cu_seqlens, keep_states)
     n = p.n_seqs
     _check(q, "q", q.dtype, (B, T, H, d_k)); _check(k, "k", q.dtype, (B, T, H, d_k))
     _check(v, "v", q.dtype, (B, T, H, d_v)); _check(g, "g", torch.float32, (B, T, H, m))
@@ -163,6 +171,8 @@ def gsa_bwd(q, k, v, g, z_saved, dO, K0=None, V0=None, dKT=None, dVT=None, scale
     for t, nm, d in ((K0, "K0", d_k), (V0, "V0", d_v), (dKT, "dKT", d_k), (dVT, "dVT", d_v)):
         _check(t, nm, torch.float32, (n, H, m, d), optional=True)
     if workspace is None:
+        if keep_states:
+            raise ValueError("keep_states: pass the workspace the forward call filled")
         workspace = alloc_workspace(p, True, q.device)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     dg = torch.empty_like(g)

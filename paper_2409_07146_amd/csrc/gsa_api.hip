@@ -35,6 +35,7 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     pl->B = p->B; pl->T = p->T; pl->H = p->H; pl->d_k = p->d_k; pl->d_v = p->d_v; pl->m = p->m;
     pl->dtype = p->dtype; pl->scale = p->scale; pl->cu_seqlens = p->cu_seqlens;
     pl->n_seqs = p->cu_seqlens ? p->n_seqs : p->B;
+    pl->keep = p->keep_states != 0;
     pl->tokens = tokens;
     pl->chunk = gsa::chunk_of_dtype(p->dtype);
     const int64_t slots = p->cu_seqlens ? ((int64_t)p->T / pl->chunk + p->n_seqs)
@@ -83,6 +84,7 @@ gsa_status make_plan(const gsa_problem *p, Plan *pl)
     pl->off_dz = off;     off += align_up(tokm);
     pl->off_dgf = off;    off += align_up(tokm);
     pl->total_bwd = off;
+    if (pl->keep) pl->total_fwd = pl->total_bwd;   // one workspace goes through both calls
     return GSA_OK;
 }
 
@@ -200,7 +202,7 @@ const char *gsa_status_string(gsa_status s)
     return "unknown status";
 }
 
-int32_t gsa_abi_version(void) { return 1; }
+int32_t gsa_abi_version(void) { return 2; }
 
 gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes)
 {

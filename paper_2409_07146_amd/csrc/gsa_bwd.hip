@@ -615,9 +615,10 @@ static hipError_t launch_bwd_tm(const Plan &pl, const Work &w, const void *q, co
                                 float *dK0, float *dV0, hipStream_t st)
 {
     const ChunkMap cm = make_chunk_map(pl, w);
-    // 1. recompute the chunk-start memories (and the memories after the last token)
-    GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
-    {
+    // 1. recompute the chunk-start memories (and the memories after the last token), unless the forward
+    // call left them in this workspace (Section 4, "Efficiency": the kernel without recomputation)
+    if (!pl.keep) {
+        GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
         const ScanIo io = {k, v, K0, V0, nullptr, nullptr, w.SF, false, pl.phi != 0, pl.phi != 0};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
@@ -690,7 +691,7 @@ hipError_t launch_bwd(const Plan &pl, const Work &w, const void *q, const void *
                       hipStream_t st)
 {
     if (pl.tokens == 0) return hipSuccess;
-    GSA_HIP_TRY(launch_prepare(pl, w, st));
+    if (!pl.keep) GSA_HIP_TRY(launch_prepare(pl, w, st));
     if (pl.dtype == 0)
         return launch_bwd_t<float>(pl, w, q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0, st);
     return launch_bwd_t<bf16_t>(pl, w, q, k, v, g, K0, V0, z_saved, dO, dKT, dVT, dq, dk, dv, dg, dK0, dV0, st);

@@ -272,7 +272,8 @@ static hipError_t launch_fwd_tm(const Plan &pl, const Work &w, const void *q, co
     const ChunkMap cm = make_chunk_map(pl, w);
     GSA_HIP_TRY(launch_gates(pl, w, g, pl.s_in, pl.gate_tau, st));
     {
-        const ScanIo io = {k, v, K0, V0, KT, VT, nullptr, false, pl.phi != 0, pl.phi != 0};
+        // kept for the backward: also the memories after the last token, as the recomputation would leave them
+        const ScanIo io = {k, v, K0, V0, KT, VT, pl.keep ? w.SF : nullptr, false, pl.phi != 0, pl.phi != 0};
         GSA_HIP_TRY(launch_scan(pl, w, io, st));
     }
     {

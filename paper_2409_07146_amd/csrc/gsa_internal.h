@@ -29,6 +29,7 @@ struct Plan {
     int32_t readout = 0;           // Readout
     float gate_tau = 0.f;          // > 0: g holds gate logits, the log gate is logsigmoid(g) / gate_tau
     int32_t phi = 0;               // 1: q, k, v hold raw projections, the kernels apply the Swish feature map
+    bool keep = false;             // the forward leaves tables, scan weights, S and SF for the backward (no recomputation)
     // forward output epilogue (gsa_fwd_act): y = Swish(o) and per-slice sums of squares of y beside (or instead of) o
     void *act_out = nullptr;       // [B,T,H,d_v] I/O dtype, or NULL
     float *act_ssq = nullptr;      // [B,T,H,ceil(d_v / slice)] fp32, or NULL

@@ -36,7 +36,7 @@ def test_exports_match_header(lib):
     assert declared == set(EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.gsa_abi_version() == 1
+    assert lib.gsa_abi_version() == 2
 
 
 def test_workspace_plan(lib):

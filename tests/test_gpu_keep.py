@@ -1,0 +1,126 @@
+"""The backward without recomputation (gsa_problem.keep_states; Section 4, "Efficiency", and the throughput
+and memory figures there: "GSA w/o recomp."): the forward leaves the per-chunk memories in the workspace and
+the backward reads them instead of running the gate kernel and the forward scan again.
+
+Two kinds of checks: against the fp64 oracle, to the same bars as the recomputing backward; and, since both
+paths run the same deterministic kernels on the same per-chunk memories, bit for bit against the recomputing
+backward (that comparison is between two results of the library, so it proves equality of the two modes and
+nothing about either's correctness; the oracle comparison does that)."""
+import pytest
+import torch
+
+from tests.test_gpu_bwd import compare_bwd
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _run(cfg, keep, scale=1.0, variant=None, poison=False, state_grads=True):
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd import synth
+    x = synth.make_inputs(cfg)
+    dev = torch.device(DEV)
+    put = lambda t: None if t is None else t.to(dev)
+    d = {n: put(x[n]) for n in ("q", "k", "v", "g", "dO", "K0", "V0", "cu_seqlens")}
+    var = dict(variant or {})
+    if var.pop("given_s", False):
+        var["s"] = (-torch.expm1(d["g"])).contiguous()
+    if var.get("gate_tau"):
+        # g holds gate logits then
+        gen = torch.Generator().manual_seed(5)
+        d["g"] = torch.randn(d["g"].shape, generator=gen).to(dev)
+    prob = gsa.make_problem(d["q"], d["v"], d["g"], scale, d["cu_seqlens"], keep_states=keep)
+    ws = gsa.alloc_workspace(prob, True, dev)
+    if poison:
+        ws.fill_(0xFF)   # NaN patterns: whatever the backward reads must have been written by the forward
+    o, z, KT, VT = gsa.gsa_fwd(d["q"], d["k"], d["v"], d["g"], K0=d["K0"], V0=d["V0"], scale=scale,
+                               cu_seqlens=d["cu_seqlens"], final_state=True, workspace=ws, keep_states=keep, **var)
+    gen = torch.Generator().manual_seed(99)
+    x["dKT"] = torch.randn(KT.shape, generator=gen) * 0.5 if state_grads else None
+    x["dVT"] = torch.randn(VT.shape, generator=gen) * 0.5 if state_grads else None
+    res = gsa.gsa_bwd(d["q"], d["k"], d["v"], d["g"], z, d["dO"], K0=d["K0"], V0=d["V0"], dKT=put(x["dKT"]),
+                      dVT=put(x["dVT"]), scale=scale, cu_seqlens=d["cu_seqlens"], initial_state_grad=True,
+                      workspace=ws, keep_states=keep, **var)
+    torch.cuda.synchronize()
+    names = ("dq", "dk", "dv", "dg", "dK0", "dV0", "ds")
+    got = dict(o=o, z=z, KT=KT, VT=VT, **{n: t for n, t in zip(names, res)})
+    return x, got
+
+
+SHAPES = [
+    # B, T, H, d_k, d_v, m, dtype, init, cu_seqlens
+    (2, 200, 2, 64, 128, 64, "bf16", 0.5, None),        # ragged tail, initial memories
+    (1, 333, 2, 192, 64, 32, "f32", 0.5, None),
+    (3, 17, 2, 128, 128, 16, "f32", 0.0, None),         # shorter than a chunk; 16 slots
+    (1, 300, 2, 128, 192, 128, "bf16", 0.5, None),      # 128 slots
+    (1, 700, 2, 128, 128, 64, "bf16", 0.3, (0, 1, 130, 130, 515, 700)),   # packed, an empty sequence
+    (1, 4096, 1, 64, 64, 64, "bf16", 0.2, None),        # one long sequence: the scans run in segments
+]
+
+
+def _cfg(B, T, H, d_k, d_v, m, dtype, init, cu, seed=23):
+    from paper_2409_07146_amd.synth import GsaConfig
+    return GsaConfig("keep", B=B, T=T, H=H, d_k=d_k, d_v=d_v, m=m, dtype=dtype, init_state_std=init,
+                     cu_seqlens=cu, seed=seed)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_kept_states_backward_against_the_oracle(oracle, shape):
+    cfg = _cfg(*shape)
+    x, got = _run(cfg, keep=True, scale=0.8, poison=True)
+    rep = []
+    seqs = [0] if shape[1] >= 4096 else None
+    compare_bwd(oracle, cfg, x, got, scale=0.8, report=rep, seqs=seqs)
+    assert all(b == "relative" for _, _, _, b in rep), rep
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_kept_states_backward_equals_the_recomputing_backward(shape):
+    cfg = _cfg(*shape)
+    _, a = _run(cfg, keep=False, scale=0.8)
+    _, b = _run(cfg, keep=True, scale=0.8, poison=True)
+    for n in ("o", "z", "KT", "VT", "dq", "dk", "dv", "dg", "dK0", "dV0"):
+        assert torch.equal(a[n], b[n]), n
+
+
+@pytest.mark.parametrize("variant", [
+    dict(given_s=True), dict(readout="relu2"), dict(gate_tau=8.0), dict(feature_map="swish"),
+    dict(given_s=True, readout="swish", feature_map="swish"),
+])
+def test_kept_states_with_the_variants(variant):
+    """Section 4's ablation variants go through the same two launch paths."""
+    cfg = _cfg(2, 200, 2, 64, 128, 64, "bf16", 0.5, None)
+    _, a = _run(cfg, keep=False, variant=variant)
+    _, b = _run(cfg, keep=True, variant=variant, poison=True)
+    names = ["o", "z", "dq", "dk", "dv", "dg", "dK0", "dV0"] + (["ds"] if variant.get("given_s") else [])
+    for n in names:
+        assert torch.equal(a[n], b[n]), n
+
+
+def test_kept_states_need_the_backward_sized_workspace():
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd import synth
+    cfg = _cfg(1, 128, 1, 64, 64, 16, "bf16", 0.0, None)
+    x = synth.make_inputs(cfg)
+    dev = torch.device(DEV)
+    q, k, v, g = (x[n].to(dev) for n in ("q", "k", "v", "g"))
+    plain = gsa.make_problem(q, v, g)
+    keep = gsa.make_problem(q, v, g, keep_states=True)
+    nf, nb = gsa.gsa_workspace_bytes(plain, False), gsa.gsa_workspace_bytes(plain, True)
+    assert nb > nf
+    assert gsa.gsa_workspace_bytes(keep, False) == nb and gsa.gsa_workspace_bytes(keep, True) == nb
+    small = torch.empty(nf, dtype=torch.uint8, device=dev)
+    with pytest.raises(gsa.GsaError) as e:
+        gsa.gsa_fwd(q, k, v, g, workspace=small, keep_states=True)
+    assert e.value.code == 4   # GSA_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("name", ["layer_1p3b", "packed_16k"])
+def test_kept_states_at_the_benchmark_sizes(name):
+    """The launch configuration bench.py times (its "without_recompute" figure)."""
+    from paper_2409_07146_amd import synth
+    cfg = synth.CONFIGS[name]
+    _, a = _run(cfg, keep=False, state_grads=False)
+    _, b = _run(cfg, keep=True, poison=True, state_grads=False)
+    for n in ("o", "z", "dq", "dk", "dv", "dg", "dK0", "dV0"):
+        assert torch.equal(a[n], b[n]), n
