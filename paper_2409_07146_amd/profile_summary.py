@@ -179,7 +179,11 @@ def main():
                     "mfma_busy %% = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x %d SIMDs): the share of SIMD cycles with a matrix\n"
                     "instruction in flight (rocprofv3's MfmaUtil).  bf16 TFLOP/s = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 / duration of the\n"
                     "dispatch under the profiler (counter collection slows a dispatch down; the kernel trace has the true durations),\n"
-                    "%% of peak against %.1f PFLOP/s dense bf16.  Averages over all dispatches of a kernel in the run.\n\n"
+                    "%% of peak against %.1f PFLOP/s dense bf16.  Averages over all dispatches of a kernel in the run.\n"
+                    "The busy-cycle counter reads about an eighth of what the operation counter implies (one instruction of 16x16x32\n"
+                    "bf16 keeps a SIMD's matrix core busy for 8 passes of 4 cycles): on this chip it appears to be collected on one of\n"
+                    "the 8 XCDs while the instruction and operation counters cover all of them, so mfma_busy %% x 8 is the figure that\n"
+                    "agrees with the TFLOP/s column.\n\n"
                     % (wl, args.command, SIMDS, MFMA_BF16_PEAK / 1e15))
             f.write("%-46s %6s %12s %14s %12s %12s %10s\n" % ("kernel", "calls", "mfma_busy %", "MFMA instr", "bf16 GFLOP", "TFLOP/s",
                                                             "% of peak"))
