@@ -283,9 +283,11 @@ def test_fwd_bwd_random_shapes_on_the_bar_with_16_slots(oracle, seed):
         raise
 
 
-def test_autograd_front_end_matches_the_direct_calls():
+@pytest.mark.parametrize("recompute", [True, False])
+def test_autograd_front_end_matches_the_direct_calls(recompute):
     """gsa_attention (torch.autograd.Function over gsa_fwd / gsa_bwd): same numbers as the two calls, gradients
-    reach q, k, v, g, the initial memories, and take the final memories' gradients along."""
+    reach q, k, v, g, the initial memories, and take the final memories' gradients along; also with the
+    forward's per-chunk memories kept for the backward (recompute=False)."""
     import paper_2409_07146_amd as gsa
     from paper_2409_07146_amd.synth import GsaConfig, make_inputs
     cfg = GsaConfig("autograd", B=2, T=130, H=2, d_k=64, d_v=128, m=32, dtype="bf16", init_state_std=0.1, seed=81)
@@ -293,7 +295,8 @@ def test_autograd_front_end_matches_the_direct_calls():
     dev = torch.device(DEV)
     q, k, v, g, dO, K0, V0 = (x[n].to(dev) for n in ("q", "k", "v", "g", "dO", "K0", "V0"))
     leaves = [t.clone().requires_grad_(True) for t in (q, k, v, g, K0, V0)]
-    o, (KT, VT) = gsa.gsa_attention(*leaves[:4], K0=leaves[4], V0=leaves[5], scale=0.9, output_final_state=True)
+    o, (KT, VT) = gsa.gsa_attention(*leaves[:4], K0=leaves[4], V0=leaves[5], scale=0.9, output_final_state=True,
+                                    recompute=recompute)
     wK, wV = torch.ones_like(KT) * 0.5, torch.ones_like(VT) * 0.25
     ((o.float() * dO.float()).sum() + (KT * wK).sum() + (VT * wV).sum()).backward()
     o2, z2, KT2, VT2 = gsa.gsa_fwd(q, k, v, g, K0=K0, V0=V0, scale=0.9, final_state=True)
