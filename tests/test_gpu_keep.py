@@ -124,3 +124,23 @@ def test_kept_states_at_the_benchmark_sizes(name):
     _, b = _run(cfg, keep=True, poison=True, state_grads=False)
     for n in ("o", "z", "dq", "dk", "dv", "dg", "dK0", "dV0"):
         assert torch.equal(a[n], b[n]), n
+
+
+def test_kept_states_after_the_forward_with_the_output_epilogue():
+    """gsa_fwd_act is a forward like the others: with keep_states its workspace serves the backward."""
+    import paper_2409_07146_amd as gsa
+    from paper_2409_07146_amd import synth
+    cfg = _cfg(2, 200, 2, 64, 128, 64, "bf16", 0.5, None)
+    x = synth.make_inputs(cfg)
+    dev = torch.device(DEV)
+    q, k, v, g, dO, K0, V0 = (x[n].to(dev) for n in ("q", "k", "v", "g", "dO", "K0", "V0"))
+    ws = gsa.alloc_workspace(gsa.make_problem(q, v, g, keep_states=True), True, dev)
+    ws.fill_(0xFF)
+    o, act, ssq, z, _, _ = gsa.gsa_fwd_act(q, k, v, g, K0=K0, V0=V0, workspace=ws, keep_states=True)
+    kept = gsa.gsa_bwd(q, k, v, g, z, dO, K0=K0, V0=V0, initial_state_grad=True, workspace=ws, keep_states=True)
+    o2, z2, _, _ = gsa.gsa_fwd(q, k, v, g, K0=K0, V0=V0)
+    ref = gsa.gsa_bwd(q, k, v, g, z2, dO, K0=K0, V0=V0, initial_state_grad=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(z, z2)
+    for a, b in zip(kept, ref):
+        assert torch.equal(a, b)
