@@ -4,12 +4,12 @@ It computes nothing of the operator: it reads the CSV files rocprofv3 writes (ke
 collection) and prints per-kernel averages.  Four profiler runs of the same bench command feed it, each in
 a directory of its own (counters are collected one group per run):
 
-    cd /tmp && export TMPDIR=/tmp        # R = repository root
-    rocprofv3 --kernel-trace --output-format csv -d $R/gpurun_out/kt -o bench -- python3 $R/bench.py --steps 20 --warmup 5 --no-cpu-baseline
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $R/gpurun_out/pmc_f -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
-    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $R/gpurun_out/pmc_w -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
-    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_INSTS_MFMA GRBM_GUI_ACTIVE --output-format csv -d $R/gpurun_out/pmc_sq -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
-    python3 -m paper_2409_07146_amd.profile_summary --kernel-trace gpurun_out/kt --fetch gpurun_out/pmc_f --write gpurun_out/pmc_w --sq gpurun_out/pmc_sq --out profiles --workload layer_1p3b
+    cd /tmp && export TMPDIR=/tmp        # R = repository root, OUT = a scratch directory for the raw output
+    rocprofv3 --kernel-trace --output-format csv -d $OUT/kt -o bench -- python3 $R/bench.py --steps 20 --warmup 5 --no-cpu-baseline
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $OUT/pmc_f -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
+    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $OUT/pmc_w -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
+    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_INSTS_MFMA GRBM_GUI_ACTIVE --output-format csv -d $OUT/pmc_sq -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
+    python3 -m paper_2409_07146_amd.profile_summary --kernel-trace $OUT/kt --fetch $OUT/pmc_f --write $OUT/pmc_w --sq $OUT/pmc_sq --out profiles --workload layer_1p3b
 
 Outputs: <workload>_fwd_bwd_kernel_trace.txt, <workload>_fwd_bwd_hbm_traffic.txt, <workload>_mfma_utilisation.txt
 and hbm_traffic_<workload>.json (bytes per launch and kernel, which bench.py puts into `roofline.traffic`).
@@ -38,9 +38,15 @@ def short(name):
     if m:
         return "decode_kernel<%s,%s> %s waves, %s" % ("bf16" if m.group(1) == "DF16b" else "f32", m.group(2), m.group(3),
                                                      "whole pair" if m.group(4) == "0" else m.group(4) + " pieces per pair")
-    m = re.match(r"([a-z_]+_kernel)I(DF16b|f)Li(\d+)", n)
+    m = re.match(r"([a-z_]+_kernel)I(DF16b|f)Li(\d+)(?:ELb([01])ELb([01]))?", n)
     if m:
-        return "%s<%s,%s>" % (m.group(1), "bf16" if m.group(2) == "DF16b" else "f32", m.group(3))
+        base = "%s<%s,%s>" % (m.group(1), "bf16" if m.group(2) == "DF16b" else "f32", m.group(3))
+        if m.group(4) is not None:   # the two template switches after the slot count
+            if m.group(1) == "apply_kernel":
+                base += (" feature map" if m.group(4) == "1" else "") + (" epilogue" if m.group(5) == "1" else "")
+            else:
+                base += (" general form" if m.group(4) == "1" else "") + (" feature map" if m.group(5) == "1" else "")
+        return base
     if "copy_probe_kernel" in n:
         return "copy_probe_kernel"
     return n[:48]
@@ -116,6 +122,10 @@ def main():
     ap.add_argument("--out", default="profiles")
     ap.add_argument("--workload", default="layer_1p3b")
     ap.add_argument("--command", default="python3 $R/bench.py", help="the profiled command, for the file headers")
+    ap.add_argument("--trace-args", default="--steps 20 --warmup 5 --no-cpu-baseline",
+                    help="the arguments the kernel-trace run gave the command, for the file header")
+    ap.add_argument("--trace-name", default=None, help="file name of the kernel-trace summary (default <workload>_fwd_bwd_kernel_trace.txt)")
+    ap.add_argument("--trace-note", default=None, help="replaces the paragraph on what a forward + backward step launches")
     args = ap.parse_args()
     os.makedirs(args.out, exist_ok=True)
     wl = args.workload
@@ -123,16 +133,17 @@ def main():
     if args.kernel_trace:
         dur = kernel_trace(args.kernel_trace)
         total = sum(sum(v) for v in dur.values())
-        with open(os.path.join(args.out, "%s_fwd_bwd_kernel_trace.txt" % wl), "w") as f:
-            f.write("rocprofv3 kernel trace of bench.py, workload %s: forward + backward steps, then the decode steps and\n"
-                    "the launches of the 256 MiB copy probe.  Durations are End - Start of each dispatch.\n\n"
-                    "command (run from /tmp with TMPDIR=/tmp; R = repository root):\n"
-                    "  rocprofv3 --kernel-trace --output-format csv -d $R/gpurun_out/kt -o bench -- %s --steps 20 --warmup 5 --no-cpu-baseline\n"
-                    "summary: python3 -m paper_2409_07146_amd.profile_summary --kernel-trace gpurun_out/kt ...\n\n"
-                    "Per step the forward launches gate, scan(forward), chunk_fwd, apply; the backward launches gate,\n"
-                    "scan(forward), chunk_dz, scan(reverse), chunk_intra, apply (dq, dk, dv in one launch).  scan(forward)\n"
-                    "therefore appears twice per step; its average mixes the forward's and the backward's launch.\n\n"
-                    % (wl, args.command))
+        note = args.trace_note or (
+            "Per step the forward launches gate, scan(forward), chunk_fwd, apply; the backward launches gate,\n"
+            "scan(forward), chunk_dz, scan(reverse), chunk_intra, apply (dq, dk, dv in one launch).  scan(forward)\n"
+            "therefore appears twice per step; its average mixes the forward's and the backward's launch.  The run\n"
+            "also times the steps without recomputation, the decode steps and the 256 MiB copy probe.")
+        with open(os.path.join(args.out, args.trace_name or "%s_fwd_bwd_kernel_trace.txt" % wl), "w") as f:
+            f.write("rocprofv3 kernel trace of bench.py, workload %s.  Durations are End - Start of each dispatch.\n\n"
+                    "command (run from /tmp with TMPDIR=/tmp; R = repository root, OUT = a scratch directory):\n"
+                    "  rocprofv3 --kernel-trace --output-format csv -d $OUT/kt -o bench -- %s %s\n"
+                    "summary: python3 -m paper_2409_07146_amd.profile_summary --kernel-trace $OUT/kt ...\n\n%s\n\n"
+                    % (wl, args.command, args.trace_args, note))
             f.write("%-46s %7s %12s %10s %10s %7s\n" % ("kernel", "calls", "total_us", "avg_us", "median_us", "pct"))
             for k, v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
                 vs = sorted(v)
@@ -148,10 +159,10 @@ def main():
         kern = {}
         with open(os.path.join(args.out, "%s_fwd_bwd_hbm_traffic.txt" % wl), "w") as f:
             f.write("HBM traffic per kernel launch from hardware counters, bench.py workload %s.\n\n"
-                    "commands (run from /tmp with TMPDIR=/tmp; R = repository root), one counter per run:\n"
-                    "  rocprofv3 --pmc FETCH_SIZE --output-format csv -d $R/gpurun_out/pmc_f -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
-                    "  rocprofv3 --pmc WRITE_SIZE --output-format csv -d $R/gpurun_out/pmc_w -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
-                    "summary: python3 -m paper_2409_07146_amd.profile_summary --fetch gpurun_out/pmc_f --write gpurun_out/pmc_w ...\n\n"
+                    "commands (run from /tmp with TMPDIR=/tmp; R = repository root, OUT = a scratch directory), one counter per run:\n"
+                    "  rocprofv3 --pmc FETCH_SIZE --output-format csv -d $OUT/pmc_f -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
+                    "  rocprofv3 --pmc WRITE_SIZE --output-format csv -d $OUT/pmc_w -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
+                    "summary: python3 -m paper_2409_07146_amd.profile_summary --fetch $OUT/pmc_f --write $OUT/pmc_w ...\n\n"
                     "Calibration: copy_probe_kernel reads 256 MiB and writes 256 MiB per launch.  The counters (KiB per dispatch) read\n"
                     "FETCH_SIZE = %.0f and WRITE_SIZE = %.0f for it, so fetched bytes = FETCH_SIZE x %.3f KiB and written bytes =\n"
                     "WRITE_SIZE x %.3f KiB.  Averages are over all dispatches of a kernel in the run.\n\n"
@@ -173,9 +184,9 @@ def main():
         sq, n, dur = counters(args.sq)
         with open(os.path.join(args.out, "%s_mfma_utilisation.txt" % wl), "w") as f:
             f.write("Matrix-core counters per kernel launch, bench.py workload %s.\n\n"
-                    "command (run from /tmp with TMPDIR=/tmp; R = repository root):\n"
-                    "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_INSTS_MFMA GRBM_GUI_ACTIVE --output-format csv -d $R/gpurun_out/pmc_sq -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
-                    "summary: python3 -m paper_2409_07146_amd.profile_summary --sq gpurun_out/pmc_sq ...\n\n"
+                    "command (run from /tmp with TMPDIR=/tmp; R = repository root, OUT = a scratch directory):\n"
+                    "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_INSTS_MFMA GRBM_GUI_ACTIVE --output-format csv -d $OUT/pmc_sq -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
+                    "summary: python3 -m paper_2409_07146_amd.profile_summary --sq $OUT/pmc_sq ...\n\n"
                     "mfma_busy %% = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x %d SIMDs): the share of SIMD cycles with a matrix\n"
                     "instruction in flight (rocprofv3's MfmaUtil).  bf16 TFLOP/s = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 / duration of the\n"
                     "dispatch under the profiler (counter collection slows a dispatch down; the kernel trace has the true durations),\n"
