@@ -92,7 +92,7 @@ int32_t gsa_abi_version(void);
  * scan).  The library cannot check that; a workspace that went through another
  * call in between gives wrong gradients, not an error.  The memories kept are
  * (d_k + d_v) * m elements of dtype per chunk of 64 (bf16) or 32 (fp32) tokens
- * and head, i.e. for m = 64 as many bytes as q, k, v and o together.
+ * and head, i.e. for m = 64 and bf16 as many bytes as k and v together.
  */
 gsa_status gsa_workspace_bytes(const gsa_problem *p, int want_bwd, size_t *bytes);
 
