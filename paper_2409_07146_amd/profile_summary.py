@@ -11,8 +11,12 @@ a directory of its own (counters are collected one group per run):
     rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_INSTS_MFMA GRBM_GUI_ACTIVE --output-format csv -d $OUT/pmc_sq -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
     python3 -m paper_2409_07146_amd.profile_summary --kernel-trace $OUT/kt --fetch $OUT/pmc_f --write $OUT/pmc_w --sq $OUT/pmc_sq --out profiles --workload layer_1p3b
 
-Outputs: <workload>_fwd_bwd_kernel_trace.txt, <workload>_fwd_bwd_hbm_traffic.txt, <workload>_mfma_utilisation.txt
-and hbm_traffic_<workload>.json (bytes per launch and kernel, which bench.py puts into `roofline.traffic`).
+A fifth run, summarised with --insts, gives the executed instruction mix and the LDS bank conflicts:
+
+    rocprofv3 --pmc SQ_WAVES SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_LDS SQ_INSTS_VMEM SQ_INSTS_VALU_TRANS_F32 SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE --output-format csv -d $OUT/pmc_in -o pmc -- python3 $R/bench.py --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline
+
+Outputs: <workload>_fwd_bwd_kernel_trace.txt, <workload>_fwd_bwd_hbm_traffic.txt, <workload>_mfma_utilisation.txt,
+<workload>_instruction_mix.txt and hbm_traffic_<workload>.json (bytes per launch and kernel, which bench.py puts into `roofline.traffic`).
 """
 import argparse
 import collections
@@ -119,6 +123,7 @@ def main():
     ap.add_argument("--fetch")
     ap.add_argument("--write")
     ap.add_argument("--sq")
+    ap.add_argument("--insts", help="directory of the instruction-mix run (SQ_WAVES, SQ_INSTS_*, SQ_LDS_*)")
     ap.add_argument("--out", default="profiles")
     ap.add_argument("--workload", default="layer_1p3b")
     ap.add_argument("--command", default="python3 $R/bench.py", help="the profiled command, for the file headers")
@@ -206,6 +211,31 @@ def main():
                 tf = flop / (dur[k] * 1e-6) / 1e12
                 f.write("%-46s %6d %12.2f %14.0f %12.2f %12.1f %10.2f\n" % (k, n[k], busy, d.get("SQ_INSTS_MFMA", 0.0), flop / 1e9, tf,
                                                                           100.0 * tf * 1e12 / MFMA_BF16_PEAK))
+
+    if args.insts:
+        ins, n, _ = counters(args.insts)
+        with open(os.path.join(args.out, "%s_instruction_mix.txt" % wl), "w") as f:
+            f.write("Executed instructions per wave and LDS bank conflicts per kernel launch, bench.py workload %s.\n\n"
+                    "command (run from /tmp with TMPDIR=/tmp; R = repository root, OUT = a scratch directory):\n"
+                    "  rocprofv3 --pmc SQ_WAVES SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_LDS SQ_INSTS_VMEM SQ_INSTS_VALU_TRANS_F32 SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE --output-format csv -d $OUT/pmc_in -o pmc -- %s --steps 3 --warmup 1 --decode-steps 16 --no-cpu-baseline\n"
+                    "summary: python3 -m paper_2409_07146_amd.profile_summary --insts $OUT/pmc_in ...\n\n"
+                    "Per wave = SQ_INSTS_* / SQ_WAVES (vector-ALU counts include the matrix instructions; trans = exp, log,\n"
+                    "reciprocal and the like).  issue_us = vector-ALU instructions x 4 cycles x waves / (%d SIMDs x 2.4 GHz): the time\n"
+                    "the launch's vector instructions take to issue if spread evenly, a floor that no occupancy shortens.\n"
+                    "lds_conflict %% = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE: the share of LDS cycles lost to bank conflicts.\n"
+                    "Averages over all dispatches of a kernel in the run.\n\n" % (wl, args.command, SIMDS))
+            f.write("%-46s %6s %8s %8s %7s %7s %7s %7s %9s %14s\n" % ("kernel", "calls", "waves", "valu", "trans", "salu", "lds", "vmem",
+                                                                   "issue_us", "lds_conflict %"))
+            for k, d in ins.items():
+                w = d.get("SQ_WAVES", 0.0)
+                if not w:
+                    continue
+                per = lambda c: d.get(c, 0.0) / w
+                act = d.get("SQ_LDS_IDX_ACTIVE", 0.0)
+                f.write("%-46s %6d %8.0f %8.0f %7.0f %7.0f %7.0f %7.0f %9.1f %14.1f\n" % (
+                    k, n[k], w, per("SQ_INSTS_VALU"), per("SQ_INSTS_VALU_TRANS_F32"), per("SQ_INSTS_SALU"), per("SQ_INSTS_LDS"),
+                    per("SQ_INSTS_VMEM"), d.get("SQ_INSTS_VALU", 0.0) * 4 / (SIMDS * 2.4e9) * 1e6,
+                    100.0 * d.get("SQ_LDS_BANK_CONFLICT", 0.0) / act if act else 0.0))
 
 
 if __name__ == "__main__":
